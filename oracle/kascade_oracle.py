@@ -1,0 +1,282 @@
+"""Plain CPU statement of what the Kascade hot path computes (fp64, numpy).
+
+THIS IS TEST INFRASTRUCTURE.  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import it; the product (HIP kernels + C ABI +
+binding) never does, and this file imports nothing from the product.
+
+Everything here is "the definition written out": no blocking, no online
+softmax, no fused passes.  Each function names the passage of the paper
+(Kascade, arXiv 2512.16391) it follows.  All floating point is float64; the
+caller widens the exact device bits (bf16 or fp32) before calling.
+
+Shapes (paper notation: N keys of dimension d per key head; H key heads):
+    q      [Hq, d]              one decode query token, all query heads
+    K, V   [Hkv, L, d]          the first L rows of one sequence's KV cache
+    Q      [S, Hq, d]           prefill queries (token major)
+    Kp, Vp [Hkv, S, d]          prefill keys / values
+Query head h reads key head h // G with G = Hq // Hkv (consecutive grouping;
+the paper leaves the assignment open, Sec. 2.2).
+
+Readings of the paper taken where it is silent or unclear:
+  * the sparse softmax is renormalised over the selected keys (Sec. 3.1: Eq. 2
+    evaluated only over k keys; Sec. 3.6: the reuse kernel is a flash
+    attention over the gathered keys, which has no dense denominator);
+  * "pooling" of post-softmax distributions is the arithmetic mean (Sec. 3.2
+    defines the layer distribution as the average over heads);
+  * ties in Top-k go to the lower key index, index sets are emitted ascending;
+  * an optional recent window W forces the last W positions into the set and
+    they count against k;
+  * prefill: the candidates of tile t are the keys strictly before the tile
+    (Sec. 4.1: each tile attends to a fraction of the previous tokens), the
+    tile's own diagonal block is always attended, causally, on top of k_t;
+    row normalisers used for pooling include the diagonal keys.
+
+parity unpinned: none of the functions below - each has a pin in
+tests/test_oracle_pins.py that does not come from this file.  What stays
+unpinned is the numerical value of attention on the paper's real model
+activations (no worked example is printed, datasets and weights are absent).
+"""
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# Eq. 1 / Eq. 2: scaled dot-product attention, with GQA (Sec. 2.1, 2.2)
+# ----------------------------------------------------------------------------
+
+def softmax_lastdim(s):
+    """softmax along the last axis (Eq. 1), max-subtracted for range only."""
+    s = np.asarray(s, dtype=np.float64)
+    e = np.exp(s - np.max(s, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def default_scale(d):
+    """1/sqrt(d) of Eq. 1."""
+    return 1.0 / np.sqrt(float(d))
+
+
+def decode_logits(q, K, scale):
+    """s[h, j] = scale * <q[h], K[h // G, j]>   (argument of softmax in Eq. 1)."""
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    Hq, d = q.shape
+    Hkv, L, _ = K.shape
+    G = Hq // Hkv
+    s = np.empty((Hq, L), dtype=np.float64)
+    for h in range(Hq):
+        s[h] = scale * (K[h // G] @ q[h])
+    return s
+
+
+def decode_probabilities(q, K, scale):
+    """p[h, :] of Eq. 1 for every query head; returns [Hq, L]."""
+    return softmax_lastdim(decode_logits(q, K, scale))
+
+
+def dense_decode(q, K, V, scale):
+    """y[h] = p[h] . V[h // G]   (Eq. 2); the anchor output in layer 0 (Sec. 3.1)."""
+    V = np.asarray(V, dtype=np.float64)
+    p = decode_probabilities(q, K, scale)
+    Hq = p.shape[0]
+    G = Hq // V.shape[0]
+    return np.stack([p[h] @ V[h // G] for h in range(Hq)])
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.4: post-softmax pooling over the GQA group (decode)
+# ----------------------------------------------------------------------------
+
+def pool_gqa(p, n_kv_heads):
+    """a[hk, j] = mean over the G query heads of key head hk of p[h, j]."""
+    p = np.asarray(p, dtype=np.float64)
+    Hq, L = p.shape
+    G = Hq // n_kv_heads
+    return p.reshape(n_kv_heads, G, L).mean(axis=1)
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.1 / 3.5 / 3.6 pass 3: exact Top-k per key head
+# ----------------------------------------------------------------------------
+
+def select_topk(a, k, recent_window=0):
+    """Index set of the k largest entries of the 1-D score vector a.
+
+    Order of preference: larger score first, lower index first among equal
+    scores.  The last `recent_window` positions are members unconditionally
+    and use up part of k.  Returned ascending, dtype int64, length k.
+    """
+    a = np.asarray(a, dtype=np.float64)
+    L = a.shape[0]
+    W = int(recent_window)
+    if not (0 <= k <= L) or not (0 <= W <= k):
+        raise ValueError("need 0 <= recent_window <= k <= L")
+    n_cand = L - W
+    n_pick = k - W
+    # stable sort of the negated candidate scores = (score desc, index asc)
+    order = np.argsort(-a[:n_cand], kind="stable")
+    chosen = order[:n_pick]
+    forced = np.arange(n_cand, L, dtype=np.int64)
+    return np.sort(np.concatenate([chosen.astype(np.int64), forced]))
+
+
+def decode_anchor_indices(q, K, scale, k, recent_window=0):
+    """Pass 1-3 of an anchor layer in decode (Sec. 3.6): Eq. 1 per query head,
+    mean over each GQA group (Sec. 3.4), Top-k per key head (Sec. 3.5).
+    Returns (idx [Hkv, k] ascending, pooled a [Hkv, L])."""
+    Hkv = np.asarray(K).shape[0]
+    a = pool_gqa(decode_probabilities(q, K, scale), Hkv)
+    idx = np.stack([select_topk(a[hk], k, recent_window) for hk in range(Hkv)])
+    return idx, a
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.1 (Oracle Top-k attention) / Sec. 3.6 (reuse layers, head map)
+# ----------------------------------------------------------------------------
+
+def sparse_decode(q, K, V, idx_sets, scale, head_map=None):
+    """Eq. 1-2 restricted to the keys idx_sets[head_map[h // G]].
+
+    idx_sets: sequence of Hkv_anchor 1-D integer arrays (any order, unique).
+    head_map[hk] = key head of the anchor layer whose set key head hk of this
+    layer uses (Sec. 3.5, many-to-one allowed); None = identity.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    Hq, d = q.shape
+    Hkv = K.shape[0]
+    G = Hq // Hkv
+    y = np.empty((Hq, d), dtype=np.float64)
+    for h in range(Hq):
+        hk = h // G
+        src = hk if head_map is None else int(head_map[hk])
+        I = np.asarray(idx_sets[src], dtype=np.int64)
+        p = softmax_lastdim(scale * (K[hk, I] @ q[h]))
+        y[h] = p @ V[hk, I]
+    return y
+
+
+# ----------------------------------------------------------------------------
+# Prefill, tile granular (Sec. 3.4: one index set per query tile and key head;
+# Sec. 3.6: pass 1 row normalisers, pass 2 pooled weights, pass 3 Top-k,
+# pass 4 sparse attention; Sec. 4.1: rolling Top-k over previous tokens)
+# ----------------------------------------------------------------------------
+
+def tile_bounds(t, T, S):
+    """Token range [lo, hi) of query tile t of T tokens in a prompt of S."""
+    lo = t * T
+    return lo, min(lo + T, S)
+
+
+def prefill_tile_probabilities(Q, Kp, t, T, scale):
+    """Causal Eq. 1 for the rows of tile t.
+
+    Returns P [n_tok, Hq, hi]: P[r, h, j] is the post-softmax weight of key j
+    for token lo + r and head h, zero for j > lo + r (causal mask)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    Kp = np.asarray(Kp, dtype=np.float64)
+    S, Hq, d = Q.shape
+    Hkv = Kp.shape[0]
+    G = Hq // Hkv
+    lo, hi = tile_bounds(t, T, S)
+    P = np.zeros((hi - lo, Hq, hi), dtype=np.float64)
+    for r in range(hi - lo):
+        i = lo + r
+        for h in range(Hq):
+            s = scale * (Kp[h // G, : i + 1] @ Q[i, h])
+            P[r, h, : i + 1] = softmax_lastdim(s)
+    return P
+
+
+def prefill_dense_tile(Q, Kp, Vp, t, T, scale):
+    """Plain causal attention (Eq. 1-2) for the rows of tile t: [n_tok, Hq, d].
+    This is what an anchor layer returns in layer 0 (Sec. 3.1, 3.6)."""
+    Vp = np.asarray(Vp, dtype=np.float64)
+    P = prefill_tile_probabilities(Q, Kp, t, T, scale)
+    n_tok, Hq, hi = P.shape
+    G = Hq // Vp.shape[0]
+    y = np.empty((n_tok, Hq, Vp.shape[2]), dtype=np.float64)
+    for h in range(Hq):
+        y[:, h, :] = P[:, h, :] @ Vp[h // G, :hi]
+    return y
+
+
+def prefill_pooled_tile(Q, Kp, t, T, scale):
+    """a[hk, j], j < t*T: mean over the tile's (token, head-in-group) rows of
+    the causal post-softmax weight of prefix key j (Sec. 3.4, pooling over a
+    full query tile including the GQA grouping).  Returns [Hkv, t*T]."""
+    Hkv = np.asarray(Kp).shape[0]
+    P = prefill_tile_probabilities(Q, Kp, t, T, scale)
+    n_tok, Hq, hi = P.shape
+    G = Hq // Hkv
+    prefix = t * T
+    # rows of the tile for key head hk: all n_tok tokens x its G query heads
+    a = P[:, :, :prefix].reshape(n_tok, Hkv, G, prefix).mean(axis=(0, 2))
+    return a
+
+
+def prefill_anchor_indices_tile(Q, Kp, t, T, scale, k_t):
+    """Top-k_t of the pooled prefix scores of tile t, per key head.
+    Returns (idx [Hkv, k_t] ascending, pooled a [Hkv, t*T])."""
+    a = prefill_pooled_tile(Q, Kp, t, T, scale)
+    idx = np.stack([select_topk(a[hk], k_t, 0) for hk in range(a.shape[0])])
+    return idx, a
+
+
+def prefill_sparse_tile(Q, Kp, Vp, t, T, idx_sets, scale, head_map=None):
+    """Sparse attention of tile t: every row (token i, head h) attends to the
+    prefix keys idx_sets[head_map[h // G]] (all < t*T, unmasked) and to the
+    diagonal keys t*T .. i, one softmax over the union (Sec. 3.6 pass 4 /
+    reuse layers; Sec. 4.1).  Returns [n_tok, Hq, d]."""
+    Q = np.asarray(Q, dtype=np.float64)
+    Kp = np.asarray(Kp, dtype=np.float64)
+    Vp = np.asarray(Vp, dtype=np.float64)
+    S, Hq, d = Q.shape
+    Hkv = Kp.shape[0]
+    G = Hq // Hkv
+    lo, hi = tile_bounds(t, T, S)
+    y = np.empty((hi - lo, Hq, Vp.shape[2]), dtype=np.float64)
+    for r in range(hi - lo):
+        i = lo + r
+        for h in range(Hq):
+            hk = h // G
+            src = hk if head_map is None else int(head_map[hk])
+            I = np.asarray(idx_sets[src], dtype=np.int64)
+            if I.size and I.max() >= lo:
+                raise ValueError("prefill index beyond the tile's prefix")
+            keys = np.concatenate([I, np.arange(lo, i + 1, dtype=np.int64)])
+            p = softmax_lastdim(scale * (Kp[hk, keys] @ Q[i, h]))
+            y[r, h] = p @ Vp[hk, keys]
+    return y
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.2, Eq. 3: how much of layer b's Top-k mass layer a's Top-k recovers
+# (used here only as a quality figure on synthetic inputs)
+# ----------------------------------------------------------------------------
+
+def topk_similarity(p_b, idx_a, idx_b):
+    """sim(a, b) of Eq. 3 for one distribution p_b and two index sets."""
+    p_b = np.asarray(p_b, dtype=np.float64)
+    return float(p_b[np.asarray(idx_a)].sum() / p_b[np.asarray(idx_b)].sum())
+
+
+# ----------------------------------------------------------------------------
+# Sec. 4.1: the k rule;  Table 3 caption: per-layer average time
+# ----------------------------------------------------------------------------
+
+def topk_budget(L, fraction, k_min=0):
+    """k = min(max(ceil(fraction * L), k_min), L).  The paper prints
+    min(max(0.1 L, 128), L) without a rounding rule; the ceiling is what
+    turns 0.1 * 2048 into 205."""
+    # exact integer ceiling of fraction*L for fractions given in per-mille
+    permille = int(round(fraction * 1000))
+    k = -((-permille * int(L)) // 1000)
+    return int(min(max(k, int(k_min)), int(L)))
+
+
+def kascade_layer_average(t_anchor0, t_anchor, t_reuse, n_layers=32, n_anchors=5):
+    """Weighted per-layer time of Table 3's caption: one dense-output anchor
+    (layer 0), n_anchors-1 other anchors, the rest reuse layers."""
+    return (t_anchor0 + (n_anchors - 1) * t_anchor
+            + (n_layers - n_anchors) * t_reuse) / n_layers

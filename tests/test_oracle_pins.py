@@ -1,0 +1,358 @@
+"""Pins of the CPU oracle against things it did not produce itself: a library
+attention routine (torch SDPA in fp64), brute-force subset enumeration, closed
+forms, invariants the method must satisfy, and numbers the paper prints."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import kascade_oracle as ko
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def sdpa_decode(q, K, V, scale):
+    """library attention: q [Hq,d], K/V [Hkv,L,d] -> [Hq,d] (fp64, GQA by repetition)."""
+    Hq = q.shape[0]
+    G = Hq // K.shape[0]
+    tq = torch.from_numpy(q)[None, :, None, :]                       # [1,Hq,1,d]
+    tk = torch.from_numpy(K).repeat_interleave(G, dim=0)[None]       # [1,Hq,L,d]
+    tv = torch.from_numpy(V).repeat_interleave(G, dim=0)[None]
+    return F.scaled_dot_product_attention(tq, tk, tv, scale=scale)[0, :, 0, :].numpy()
+
+
+# ------------------------------------------------------------------ Eq. 1-2
+
+@pytest.mark.parametrize("Hq,Hkv,d,L", [(8, 2, 64, 300), (4, 4, 16, 33), (6, 1, 32, 1), (32, 8, 128, 257)])
+def test_dense_decode_matches_library_attention(Hq, Hkv, d, L):
+    r = rng(L)
+    q, K, V = r.standard_normal((Hq, d)), r.standard_normal((Hkv, L, d)), r.standard_normal((Hkv, L, d))
+    scale = ko.default_scale(d)
+    np.testing.assert_allclose(ko.dense_decode(q, K, V, scale), sdpa_decode(q, K, V, scale), atol=1e-12)
+    # a non-default scale must be honoured too
+    np.testing.assert_allclose(ko.dense_decode(q, K, V, 0.37), sdpa_decode(q, K, V, 0.37), atol=1e-12)
+
+
+def test_probabilities_match_library_via_identity_values():
+    # with V = identity (d_v = L) library attention returns p itself
+    r = rng(5)
+    Hq, Hkv, d, L = 6, 3, 16, 40
+    q, K = r.standard_normal((Hq, d)), r.standard_normal((Hkv, L, d))
+    G = Hq // Hkv
+    tq = torch.from_numpy(q)[None, :, None, :]
+    tk = torch.from_numpy(K).repeat_interleave(G, dim=0)[None]
+    tv = torch.eye(L, dtype=torch.float64).expand(1, Hq, L, L)
+    p_lib = F.scaled_dot_product_attention(tq, tk, tv, scale=0.25)[0, :, 0, :].numpy()
+    p = ko.decode_probabilities(q, K, 0.25)
+    np.testing.assert_allclose(p, p_lib, atol=1e-13)
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-12)
+    assert (p >= 0).all()
+
+
+def test_softmax_closed_forms():
+    # equal logits -> uniform; two logits -> logistic
+    np.testing.assert_allclose(ko.softmax_lastdim(np.full((3, 7), 2.5)), 1.0 / 7, atol=1e-15)
+    x = 1.3
+    p = ko.softmax_lastdim(np.array([x, 0.0]))
+    np.testing.assert_allclose(p[0], 1.0 / (1.0 + np.exp(-x)), atol=1e-15)
+    # shift invariance and no overflow for large logits
+    np.testing.assert_allclose(ko.softmax_lastdim(np.array([1000.0, 999.0])),
+                               ko.softmax_lastdim(np.array([1.0, 0.0])), atol=1e-15)
+
+
+def test_default_scale():
+    assert ko.default_scale(64) == 0.125
+    np.testing.assert_allclose(ko.default_scale(128), 128 ** -0.5)
+
+
+# ------------------------------------------------------------------ pooling
+
+def test_pool_gqa_mean_and_group_assignment():
+    r = rng(7)
+    Hq, Hkv, L = 8, 2, 50
+    p = ko.softmax_lastdim(r.standard_normal((Hq, L)))
+    a = ko.pool_gqa(p, Hkv)
+    np.testing.assert_allclose(a.sum(axis=1), 1.0, atol=1e-12)
+    # heads 0..3 feed key head 0, heads 4..7 feed key head 1 (consecutive grouping)
+    np.testing.assert_allclose(a[0], (p[0] + p[1] + p[2] + p[3]) / 4, atol=1e-15)
+    np.testing.assert_allclose(a[1], (p[4] + p[5] + p[6] + p[7]) / 4, atol=1e-15)
+    # G = 1: pooling is the identity
+    np.testing.assert_allclose(ko.pool_gqa(p, Hq), p, atol=0)
+
+
+# ------------------------------------------------------------------ Top-k
+
+def brute_force_topk(a, k, W):
+    """Enumerate every admissible k-subset; best = largest total score, then
+    the lexicographically smallest index tuple (= lower index wins ties)."""
+    L = len(a)
+    forced = tuple(range(L - W, L))
+    best, best_key = None, None
+    for sub in itertools.combinations(range(L - W), k - W):
+        cand = tuple(sorted(sub + forced))
+        key = (-sum(a[j] for j in sub), cand)
+        if best_key is None or key < best_key:
+            best, best_key = cand, key
+    return np.array(best, dtype=np.int64)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_brute_force_with_exact_ties(seed):
+    r = rng(100 + seed)
+    L = 9
+    # few distinct dyadic values -> many exact ties, exact sums
+    a = r.integers(0, 4, size=L).astype(np.float64) / 8.0
+    for W in (0, 1, 3):
+        for k in range(W, L + 1):
+            got = ko.select_topk(a, k, W)
+            np.testing.assert_array_equal(got, brute_force_topk(a, k, W))
+
+
+def test_topk_matches_library_topk_without_ties():
+    r = rng(11)
+    a = r.random(5000)
+    for k in (1, 17, 500, 4999, 5000):
+        lib = torch.topk(torch.from_numpy(a), k).indices.sort().values.numpy()
+        np.testing.assert_array_equal(ko.select_topk(a, k), lib)
+
+
+def test_topk_invariants_and_window():
+    r = rng(12)
+    L, k, W = 1000, 100, 16
+    a = np.round(r.random(L), 2)          # two-decimal scores: many ties
+    I = ko.select_topk(a, k, W)
+    assert I.shape == (k,) and I.dtype == np.int64
+    assert (np.diff(I) > 0).all() and I[0] >= 0 and I[-1] < L
+    assert set(range(L - W, L)) <= set(I.tolist())
+    cand_in = [j for j in I if j < L - W]
+    cand_out = [j for j in range(L - W) if j not in set(cand_in)]
+    thr = min(a[cand_in])
+    assert max(a[cand_out]) <= thr                       # maximality
+    # among scores equal to the threshold the chosen ones are the lowest indices
+    eq_in = [j for j in cand_in if a[j] == thr]
+    eq_out = [j for j in cand_out if a[j] == thr]
+    if eq_in and eq_out:
+        assert max(eq_in) < min(eq_out)
+    with pytest.raises(ValueError):
+        ko.select_topk(a, L + 1)
+    with pytest.raises(ValueError):
+        ko.select_topk(a, 3, 4)
+    assert ko.select_topk(a, 0).size == 0
+
+
+def test_anchor_indices_single_head_equal_topk_of_raw_logits():
+    # G = 1: softmax is monotone, so the Top-k of p is the Top-k of q.K
+    r = rng(13)
+    Hkv, d, L, k = 3, 32, 400, 40
+    q, K = r.standard_normal((Hkv, d)), r.standard_normal((Hkv, L, d))
+    idx, a = ko.decode_anchor_indices(q, K, ko.default_scale(d), k)
+    for hk in range(Hkv):
+        raw = torch.topk(torch.from_numpy(K[hk] @ q[hk]), k).indices.sort().values.numpy()
+        np.testing.assert_array_equal(idx[hk], raw)
+    np.testing.assert_allclose(a.sum(axis=1), 1.0, atol=1e-12)
+
+
+def test_anchor_indices_find_planted_keys():
+    # one key per key head is made overwhelmingly dominant for every head of the group
+    r = rng(14)
+    Hq, Hkv, d, L = 8, 2, 16, 64
+    q, K = r.standard_normal((Hq, d)), 0.01 * r.standard_normal((Hkv, L, d))
+    plant = [5, 41]
+    for hk in range(Hkv):
+        K[hk, plant[hk]] = 50.0 * q[hk * 4:(hk + 1) * 4].mean(axis=0)
+    idx, _ = ko.decode_anchor_indices(q, K, 1.0, 1)
+    assert idx[:, 0].tolist() == plant
+
+
+# ------------------------------------------------------------------ sparse attention
+
+def test_sparse_decode_special_cases():
+    r = rng(21)
+    Hq, Hkv, d, L = 8, 2, 32, 120
+    q, K, V = r.standard_normal((Hq, d)), r.standard_normal((Hkv, L, d)), r.standard_normal((Hkv, L, d))
+    scale = ko.default_scale(d)
+    full = [np.arange(L)] * Hkv
+    # k = L  =>  dense
+    np.testing.assert_allclose(ko.sparse_decode(q, K, V, full, scale), ko.dense_decode(q, K, V, scale), atol=1e-13)
+    # k = 1  =>  the selected value row
+    one = [np.array([7]), np.array([99])]
+    y1 = ko.sparse_decode(q, K, V, one, scale)
+    for h in range(Hq):
+        np.testing.assert_allclose(y1[h], V[h // 4, one[h // 4][0]], atol=1e-15)
+    # arbitrary sets = library attention on the gathered sub-cache (per key head)
+    sets = [np.sort(r.choice(L, 30, replace=False)) for _ in range(Hkv)]
+    y = ko.sparse_decode(q, K, V, sets, scale)
+    for hk in range(Hkv):
+        ref = sdpa_decode(q[hk * 4:(hk + 1) * 4], K[hk:hk + 1, sets[hk]], V[hk:hk + 1, sets[hk]], scale)
+        np.testing.assert_allclose(y[hk * 4:(hk + 1) * 4], ref, atol=1e-12)
+    # order of the indices does not matter
+    shuffled = [r.permutation(s) for s in sets]
+    np.testing.assert_allclose(ko.sparse_decode(q, K, V, shuffled, scale), y, atol=1e-13)
+    # permuting key positions together with the indices leaves the output unchanged
+    perm = r.permutation(L)
+    inv = np.argsort(perm)
+    np.testing.assert_allclose(ko.sparse_decode(q, K[:, perm], V[:, perm], [inv[s] for s in sets], scale), y, atol=1e-13)
+
+
+def test_head_map():
+    r = rng(22)
+    Hq, Hkv, d, L = 6, 3, 16, 50
+    q, K, V = r.standard_normal((Hq, d)), r.standard_normal((Hkv, L, d)), r.standard_normal((Hkv, L, d))
+    sets = [np.sort(r.choice(L, 10, replace=False)) for _ in range(Hkv)]
+    y_id = ko.sparse_decode(q, K, V, sets, 0.3)
+    np.testing.assert_allclose(ko.sparse_decode(q, K, V, sets, 0.3, head_map=[0, 1, 2]), y_id, atol=0)
+    hm = [2, 0, 0]                                # many-to-one
+    y_map = ko.sparse_decode(q, K, V, sets, 0.3, head_map=hm)
+    y_ref = ko.sparse_decode(q, K, V, [sets[hm[0]], sets[hm[1]], sets[hm[2]]], 0.3)
+    np.testing.assert_allclose(y_map, y_ref, atol=0)
+    assert np.abs(y_map - y_id).max() > 1e-3
+
+
+# ------------------------------------------------------------------ prefill
+
+def sdpa_prefill(Q, Kp, Vp, scale, mask=None):
+    """library attention over a whole prompt: returns [S, Hq, d]."""
+    Hq = Q.shape[1]
+    G = Hq // Kp.shape[0]
+    tq = torch.from_numpy(Q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(Kp).repeat_interleave(G, dim=0)[None]
+    tv = torch.from_numpy(Vp).repeat_interleave(G, dim=0)[None]
+    if mask is None:
+        o = F.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=scale)
+    else:
+        o = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=torch.from_numpy(mask)[None], scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+def make_prefill(seed, S, Hq, Hkv, d):
+    r = rng(seed)
+    return r.standard_normal((S, Hq, d)), r.standard_normal((Hkv, S, d)), r.standard_normal((Hkv, S, d))
+
+
+@pytest.mark.parametrize("S,T", [(40, 8), (37, 8), (16, 1)])
+def test_prefill_dense_tiles_match_library_causal_attention(S, T):
+    Q, Kp, Vp = make_prefill(31, S, 4, 2, 16)
+    ref = sdpa_prefill(Q, Kp, Vp, 0.25)
+    for t in range((S + T - 1) // T):
+        lo, hi = ko.tile_bounds(t, T, S)
+        np.testing.assert_allclose(ko.prefill_dense_tile(Q, Kp, Vp, t, T, 0.25), ref[lo:hi], atol=1e-12)
+
+
+def test_prefill_pooled_is_mean_of_per_row_library_probabilities():
+    S, T, Hq, Hkv, d = 24, 4, 4, 2, 8
+    G = Hq // Hkv
+    Q, Kp, _ = make_prefill(32, S, Hq, Hkv, d)
+    # causal library attention with V = identity returns the causal P matrix
+    eye = np.broadcast_to(np.eye(S), (Hkv, S, S)).copy()
+    P_lib = sdpa_prefill(Q, Kp, eye, 0.4)                      # [S, Hq, S]
+    for t in range(S // T):
+        a = ko.prefill_pooled_tile(Q, Kp, t, T, 0.4)
+        assert a.shape == (Hkv, t * T)
+        for hk in range(Hkv):
+            rows = P_lib[t * T:(t + 1) * T, hk * G:(hk + 1) * G, : t * T]
+            np.testing.assert_allclose(a[hk], rows.mean(axis=(0, 1)), atol=1e-13)
+            # prefix mass + mean diagonal mass = 1
+            diag = P_lib[t * T:(t + 1) * T, hk * G:(hk + 1) * G, t * T:].sum(axis=2).mean()
+            np.testing.assert_allclose(a[hk].sum() + diag, 1.0, atol=1e-12)
+
+
+def test_prefill_single_token_tiles_reduce_to_decode():
+    # T = 1: the row of token i is a decode call at L = i + 1 on the same cache
+    S, Hq, Hkv, d = 12, 4, 2, 8
+    Q, Kp, Vp = make_prefill(33, S, Hq, Hkv, d)
+    for i in (1, 5, 11):
+        a = ko.prefill_pooled_tile(Q, Kp, i, 1, 0.5)
+        p_dec = ko.pool_gqa(ko.decode_probabilities(Q[i], Kp[:, : i + 1], 0.5), Hkv)
+        np.testing.assert_allclose(a, p_dec[:, :i], atol=1e-14)
+        np.testing.assert_allclose(ko.prefill_dense_tile(Q, Kp, Vp, i, 1, 0.5)[0],
+                                   ko.dense_decode(Q[i], Kp[:, : i + 1], Vp[:, : i + 1], 0.5), atol=1e-13)
+        # sparse row: prefix indices plus the diagonal key i = a decode over that set
+        I = [np.array([0, i - 1]) if i > 1 else np.array([0])] * Hkv
+        y = ko.prefill_sparse_tile(Q, Kp, Vp, i, 1, I, 0.5)[0]
+        I_dec = [np.concatenate([s, [i]]) for s in I]
+        np.testing.assert_allclose(y, ko.sparse_decode(Q[i], Kp, Vp, I_dec, 0.5), atol=1e-13)
+
+
+def test_prefill_sparse_matches_library_attention_with_explicit_mask():
+    S, T, Hq, Hkv, d = 40, 8, 4, 2, 16
+    G = Hq // Hkv
+    r = rng(34)
+    Q, Kp, Vp = make_prefill(34, S, Hq, Hkv, d)
+    n_tiles = S // T
+    sets = {}
+    mask = np.zeros((Hq, S, S), dtype=bool)
+    hm = [1, 1]                                    # both key heads use anchor head 1's sets
+    for t in range(n_tiles):
+        kt = min(t * T, 5)
+        sets[t] = [np.sort(r.choice(t * T, kt, replace=False)) if kt else np.zeros(0, np.int64) for _ in range(Hkv)]
+        for i in range(t * T, (t + 1) * T):
+            for h in range(Hq):
+                mask[h, i, sets[t][hm[h // G]]] = True
+                mask[h, i, t * T: i + 1] = True
+    ref = sdpa_prefill(Q, Kp, Vp, 0.25, mask=mask)
+    for t in range(n_tiles):
+        y = ko.prefill_sparse_tile(Q, Kp, Vp, t, T, sets[t], 0.25, head_map=hm)
+        np.testing.assert_allclose(y, ref[t * T:(t + 1) * T], atol=1e-12)
+
+
+def test_prefill_sparse_with_full_prefix_is_dense_and_tile0_is_dense():
+    S, T = 30, 8                                    # ragged last tile
+    Q, Kp, Vp = make_prefill(35, S, 4, 2, 8)
+    for t in range(4):
+        full = [np.arange(t * T)] * 2
+        np.testing.assert_allclose(ko.prefill_sparse_tile(Q, Kp, Vp, t, T, full, 0.3),
+                                   ko.prefill_dense_tile(Q, Kp, Vp, t, T, 0.3), atol=1e-13)
+    with pytest.raises(ValueError):
+        ko.prefill_sparse_tile(Q, Kp, Vp, 1, T, [np.array([8])] * 2, 0.3)
+
+
+def test_prefill_anchor_indices_tile():
+    S, T = 64, 8
+    Q, Kp, _ = make_prefill(36, S, 8, 2, 16)
+    t, kt = 6, 10
+    idx, a = ko.prefill_anchor_indices_tile(Q, Kp, t, T, 0.25, kt)
+    assert idx.shape == (2, kt) and a.shape == (2, t * T)
+    for hk in range(2):
+        lib = torch.topk(torch.from_numpy(a[hk]), kt).indices.sort().values.numpy()
+        np.testing.assert_array_equal(idx[hk], lib)
+
+
+# ------------------------------------------------------------------ Eq. 3
+
+def test_similarity_bounds():
+    r = rng(41)
+    p = ko.softmax_lastdim(3 * r.standard_normal(200))
+    Ib = ko.select_topk(p, 20)
+    assert ko.topk_similarity(p, Ib, Ib) == 1.0
+    for _ in range(10):
+        Ia = np.sort(r.choice(200, 20, replace=False))
+        s = ko.topk_similarity(p, Ia, Ib)
+        assert 0.0 <= s <= 1.0
+    # hand value: p = (.5,.3,.2), own top-1 = {0}, other set {1} -> 0.3/0.5
+    np.testing.assert_allclose(ko.topk_similarity(np.array([.5, .3, .2]), [1], [0]), 0.6)
+
+
+# ------------------------------------------------------------------ numbers the paper prints
+
+def read_rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def test_k_rule_golden():
+    for L, frac, kmin, k in read_rows("k_rule.txt"):
+        assert ko.topk_budget(int(L), float(frac), int(kmin)) == int(k)
+
+
+def test_table3_weighted_average_golden():
+    for step, seqlen, pct, a0, a, r_, avg in read_rows("table3_layer_average.txt"):
+        got = ko.kascade_layer_average(float(a0), float(a), float(r_))
+        # printed inputs carry +-0.005 each, weights sum to 1 -> +-0.005, plus the result's own rounding
+        assert abs(got - float(avg)) <= 0.0101, (step, seqlen, pct, got, avg)
