@@ -1,0 +1,158 @@
+/*
+ * kascade.h - C ABI of the Kascade sparse-attention hot path for AMD MI355X (gfx950).
+ *
+ * Kascade (arXiv 2512.16391) computes exact post-softmax Top-k key sets in a few
+ * "anchor" attention layers and re-uses them in the "reuse" layers in between
+ * (Sec. 3.1-3.2).  Index sets are kept per key head (Sec. 3.5); in decode one set
+ * serves the GQA group of a key head, in prefill one set serves a tile of
+ * consecutive query tokens times that group (Sec. 3.4).  The four entry points
+ * below are the anchor and reuse layer of Sec. 3.6 for decode and for prefill.
+ *
+ * Conventions shared by all calls
+ *  - Every pointer is DEVICE memory owned by the caller (inputs, outputs, index
+ *    buffers, workspace) except the `kascade_desc*` itself, which is HOST memory
+ *    read before the call returns.  The library never allocates, frees or keeps
+ *    a pointer after return.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream) and the call returns without synchronising.
+ *  - Query head h reads key head h / G, G = n_q_heads / n_kv_heads (Sec. 2.2).
+ *  - Strides are in ELEMENTS; the head dimension is contiguous.  Rows (head_dim
+ *    elements) of Q, K, V and O must be 16-byte aligned.
+ *  - softmax is computed in fp32 on fp32-accumulated logits, scale = 1/sqrt(d)
+ *    (Eq. 1) unless `softmax_scale` is non-zero.
+ *  - Top-k order of preference: larger pooled score, then lower key index.  Index
+ *    sets are written ascending.
+ *  - Return value: KASCADE_OK or a negative status.  All argument checks happen
+ *    before the first launch; on error nothing has been enqueued.
+ *  - Results are deterministic: the same inputs give the same bits.
+ */
+#ifndef KASCADE_H
+#define KASCADE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    KASCADE_OK = 0,
+    KASCADE_INVALID_ARG = -1,         /* NULL pointer, non-positive size, k > L, ...          */
+    KASCADE_UNSUPPORTED = -2,         /* head_dim / dtype / group size / tile size not built  */
+    KASCADE_MISALIGNED = -3,          /* a base pointer or stride breaks 16-byte row alignment*/
+    KASCADE_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes < kascade_workspace_bytes(...)       */
+    KASCADE_HIP_ERROR = -5            /* a launch failed; hipGetLastError() has the detail    */
+};
+
+enum { KASCADE_F32 = 0, KASCADE_BF16 = 1 };
+
+/* out_mode of the anchor calls (Sec. 3.6): layer 0 returns dense attention
+ * (Sec. 3.1), every other anchor returns Top-k attention over its own fresh set. */
+enum { KASCADE_OUT_DENSE = 0, KASCADE_OUT_SPARSE = 1 };
+
+enum {
+    KASCADE_OP_DECODE_ANCHOR = 0,
+    KASCADE_OP_DECODE_REUSE = 1,
+    KASCADE_OP_PREFILL_ANCHOR = 2,
+    KASCADE_OP_PREFILL_REUSE = 3
+};
+
+typedef struct {
+    int32_t batch;          /* sequences (decode); must be 1 for prefill                 */
+    int32_t n_q_heads;      /* Hq                                                        */
+    int32_t n_kv_heads;     /* Hkv, divides Hq; G = Hq/Hkv in {1,2,4,8}                  */
+    int32_t head_dim;       /* d in {64, 128}                                            */
+    int32_t dtype;          /* KASCADE_F32 or KASCADE_BF16; Q, K, V, O share it          */
+    float   softmax_scale;  /* 0 -> 1/sqrt(head_dim) (Eq. 1)                             */
+    int64_t q_stride[3];    /* batch, token, head   (decode ignores the token stride)    */
+    int64_t kv_stride[3];   /* batch, head, token   (covers [B,Hkv,L,d] and [B,L,Hkv,d]) */
+    int64_t o_stride[3];    /* batch, token, head                                        */
+} kascade_desc;
+
+/*
+ * Decode, anchor layer (Sec. 3.6, passes 1-4; pooling of Sec. 3.4; Top-k of Sec. 3.5).
+ * For every sequence b (context length seqlens[b], which includes the current
+ * token) and key head hk: logits of the G query heads against all keys (Eq. 1),
+ * softmax per head, mean over the group, then the k_per_seq[b] best keys.  The
+ * last `recent_window` positions are always members and count against k.
+ *   q        [B,Hq,d]           k_cache, v_cache  per kv_stride, >= seqlens[b] rows
+ *   seqlens, k_per_seq  [B] int32 (device); require recent_window <= k_per_seq[b] <= seqlens[b]
+ *   k_max    >= max k_per_seq (host value; row pitch of idx_out)
+ *   idx_out  [B,Hkv,k_max] int32, ascending, entries past k_per_seq[b] set to -1
+ *   out      [B,Hq,d]: dense attention (Eq. 2) if out_mode = KASCADE_OUT_DENSE, else
+ *            attention renormalised over the fresh index set (Sec. 3.1)
+ *   max_seqlen  host upper bound of seqlens (sizes the grid and the workspace)
+ */
+int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k_cache,
+                          const void* v_cache, const int32_t* seqlens, const int32_t* k_per_seq,
+                          int32_t max_seqlen, int32_t k_max, int32_t recent_window, int32_t out_mode,
+                          int32_t* idx_out, void* out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/*
+ * Decode, reuse layer (Sec. 3.6 first paragraph; head map of Sec. 3.5).
+ * Key head hk of this layer attends to rows idx_in[b, head_map[hk], 0:k_per_seq[b]]
+ * of its own K/V cache; softmax over exactly those rows.  Entries that are
+ * negative or >= seqlens[b] are ignored.  Any order is accepted.
+ *   idx_in   [B,Hkv_anchor,k_max] int32 with n_anchor_heads rows per sequence
+ *   head_map [Hkv] int32 (device) with values in [0, n_anchor_heads), or NULL = identity
+ */
+int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_cache,
+                         const void* v_cache, const int32_t* seqlens, const int32_t* k_per_seq,
+                         int32_t k_max, const int32_t* idx_in, int32_t n_anchor_heads,
+                         const int32_t* head_map, void* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Prefill, anchor layer (Sec. 3.6 passes 1-4 with the score matrix recomputed in
+ * pass 2; tile pooling of Sec. 3.4; rolling Top-k of Sec. 4.1).  batch = 1.
+ * Tile t covers tokens [t*T, min((t+1)*T, S)), T = q_tile_tokens; its rows are those
+ * tokens times the G heads of a key head.  Candidates of tile t are the keys
+ * j < t*T; the pooled score of key j is the mean over the tile's rows of the causal
+ * post-softmax weight (row normalisers include the diagonal keys).  k_per_tile[t]
+ * <= t*T keys are selected per key head; the diagonal block t*T..i is always
+ * attended on top, causally.
+ *   q [S,Hq,d] per q_stride;  k, v [Hkv,S,d] per kv_stride
+ *   k_per_tile  [n_tiles] int32 (device), idx_offsets [n_tiles+1] int64 (device),
+ *               idx_offsets[t+1]-idx_offsets[t] = k_per_tile[t], idx_total = idx_offsets[n_tiles]
+ *   idx_out  [Hkv, idx_total] int32: tile t of head hk at hk*idx_total + idx_offsets[t]
+ *   out [S,Hq,d]: causal dense attention (KASCADE_OUT_DENSE) or sparse attention over the
+ *       fresh sets (KASCADE_OUT_SPARSE)
+ */
+int kascade_prefill_anchor(const kascade_desc* desc, const void* q, const void* k, const void* v,
+                           int32_t seqlen, int32_t q_tile_tokens, const int32_t* k_per_tile,
+                           const int64_t* idx_offsets, int64_t idx_total, int32_t out_mode,
+                           int32_t* idx_out, void* out, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
+ * Prefill, reuse layer (Sec. 3.6 first paragraph, Sec. 4.1): every row (token i in
+ * tile t, head h) attends to idx_in[head_map[h/G]] of its tile plus the keys
+ * t*T..i; one softmax over the union.  Entries outside [0, t*T) are ignored.
+ */
+int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k, const void* v,
+                          int32_t seqlen, int32_t q_tile_tokens, const int32_t* k_per_tile,
+                          const int64_t* idx_offsets, int64_t idx_total, const int32_t* idx_in,
+                          int32_t n_anchor_heads, const int32_t* head_map, void* out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Bytes of workspace the given op needs (0 is a valid answer).
+ *   decode ops:  max_seqlen = largest context length, k_or_idx_total = k_max
+ *   prefill ops: max_seqlen = S, k_or_idx_total = idx_total, q_tile_tokens = T
+ * Returns 0 for an unknown op or an invalid descriptor.
+ */
+size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max_seqlen,
+                               int64_t k_or_idx_total, int32_t q_tile_tokens);
+
+/* Static, NUL-terminated description of a status code. */
+const char* kascade_status_string(int32_t status);
+
+/* Library version, "major.minor". */
+const char* kascade_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KASCADE_H */

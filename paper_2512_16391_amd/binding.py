@@ -1,0 +1,237 @@
+"""Thin ctypes binding of libkascade.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+include/kascade.h) and does no arithmetic of the method: it builds the
+descriptor from tensor shapes/strides, allocates outputs and the workspace as
+torch tensors on the inputs' device, and passes raw device pointers plus the
+current HIP stream.  There is no CPU fallback: if the library is not built, or
+a tensor is not on the GPU, the call raises.
+"""
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libkascade.so")
+
+KASCADE_OK = 0
+KASCADE_F32, KASCADE_BF16 = 0, 1
+KASCADE_OUT_DENSE, KASCADE_OUT_SPARSE = 0, 1
+OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE = 0, 1, 2, 3
+
+EXPORTS = [
+    "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
+    "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
+]
+
+
+class KascadeDesc(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("q_stride", ctypes.c_int64 * 3), ("kv_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
+    ]
+
+
+class KascadeError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None):
+    """Loads libkascade.so (built by build.py / __graft_entry__.build()); raises if absent."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "at the repository root (there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    dp = ctypes.POINTER(KascadeDesc)
+    lib.kascade_decode_anchor.argtypes = [dp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.kascade_decode_anchor.restype = ctypes.c_int
+    lib.kascade_decode_reuse.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, sz, vp]
+    lib.kascade_decode_reuse.restype = ctypes.c_int
+    lib.kascade_prefill_anchor.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+    lib.kascade_prefill_anchor.restype = ctypes.c_int
+    lib.kascade_prefill_reuse.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, i64, vp, i32, vp, vp, vp, sz, vp]
+    lib.kascade_prefill_reuse.restype = ctypes.c_int
+    lib.kascade_workspace_bytes.argtypes = [i32, dp, i64, i64, i32]
+    lib.kascade_workspace_bytes.restype = sz
+    lib.kascade_status_string.argtypes = [i32]
+    lib.kascade_status_string.restype = ctypes.c_char_p
+    lib.kascade_version.argtypes = []
+    lib.kascade_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().kascade_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return load_library().kascade_version().decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return KASCADE_F32
+    if t.dtype == torch.bfloat16:
+        return KASCADE_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _need_gpu(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("kascade: tensors must live on the GPU (there is no CPU path)")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def decode_desc(q, k_cache, out=None, softmax_scale=0.0, kv_layout="BHLD") -> KascadeDesc:
+    """q [B,Hq,d]; k_cache [B,Hkv,L,d] ("BHLD") or [B,L,Hkv,d] ("BLHD")."""
+    B, Hq, d = q.shape
+    d_ = KascadeDesc()
+    if kv_layout == "BHLD":
+        Hkv = k_cache.shape[1]
+        kvs = (k_cache.stride(0), k_cache.stride(1), k_cache.stride(2))
+    elif kv_layout == "BLHD":
+        Hkv = k_cache.shape[2]
+        kvs = (k_cache.stride(0), k_cache.stride(2), k_cache.stride(1))
+    else:
+        raise ValueError(kv_layout)
+    if q.stride(2) != 1 or k_cache.stride(3) != 1:
+        raise ValueError("head dimension must be contiguous")
+    d_.batch, d_.n_q_heads, d_.n_kv_heads, d_.head_dim = B, Hq, Hkv, d
+    d_.dtype = _dtype_code(q)
+    d_.softmax_scale = float(softmax_scale)
+    d_.q_stride[:] = (q.stride(0), 0, q.stride(1))
+    d_.kv_stride[:] = kvs
+    o = out if out is not None else q
+    d_.o_stride[:] = (o.stride(0), 0, o.stride(1))
+    return d_
+
+
+def prefill_desc(q, k, out=None, softmax_scale=0.0) -> KascadeDesc:
+    """q [S,Hq,d]; k [Hkv,S,d] (any strides with contiguous head dimension)."""
+    S, Hq, d = q.shape
+    d_ = KascadeDesc()
+    if q.stride(2) != 1 or k.stride(2) != 1:
+        raise ValueError("head dimension must be contiguous")
+    d_.batch, d_.n_q_heads, d_.n_kv_heads, d_.head_dim = 1, Hq, k.shape[0], d
+    d_.dtype = _dtype_code(q)
+    d_.softmax_scale = float(softmax_scale)
+    d_.q_stride[:] = (0, q.stride(0), q.stride(1))
+    d_.kv_stride[:] = (0, k.stride(0), k.stride(1))
+    o = out if out is not None else q
+    d_.o_stride[:] = (0, o.stride(0), o.stride(1))
+    return d_
+
+
+def kascade_workspace_bytes(op, desc, max_seqlen, k_or_idx_total, q_tile_tokens=0) -> int:
+    return int(load_library().kascade_workspace_bytes(int(op), ctypes.byref(desc), int(max_seqlen),
+                                                      int(k_or_idx_total), int(q_tile_tokens)))
+
+
+def _workspace(op, desc, max_seqlen, k_or_total, T, device, workspace):
+    need = kascade_workspace_bytes(op, desc, max_seqlen, k_or_total, T)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def _check(st, where):
+    if st != KASCADE_OK:
+        raise KascadeError(st, where)
+
+
+def kascade_decode_anchor(q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window=0,
+                          out_mode=KASCADE_OUT_SPARSE, idx_out=None, out=None, workspace=None,
+                          softmax_scale=0.0, kv_layout="BHLD"):
+    """Returns (idx_out [B,Hkv,k_max] int32, out [B,Hq,d])."""
+    _need_gpu(q, k_cache, v_cache, seqlens, k_per_seq, idx_out, out, workspace)
+    lib = load_library()
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    desc = decode_desc(q, k_cache, out, softmax_scale, kv_layout)
+    if idx_out is None:
+        idx_out = torch.empty(B, desc.n_kv_heads, int(k_max), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(OP_DECODE_ANCHOR, desc, max_seqlen, k_max, 0, q.device, workspace)
+    st = lib.kascade_decode_anchor(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seqlens),
+                                   _ptr(k_per_seq), int(max_seqlen), int(k_max), int(recent_window), int(out_mode),
+                                   _ptr(idx_out), _ptr(out), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_decode_anchor")
+    return idx_out, out
+
+
+def kascade_decode_reuse(q, k_cache, v_cache, seqlens, k_per_seq, k_max, idx_in, head_map=None, out=None,
+                         workspace=None, softmax_scale=0.0, kv_layout="BHLD"):
+    """idx_in [B,Hkv_anchor,k_max] int32.  Returns out [B,Hq,d]."""
+    _need_gpu(q, k_cache, v_cache, seqlens, k_per_seq, idx_in, head_map, out, workspace)
+    lib = load_library()
+    if out is None:
+        out = torch.empty_like(q)
+    desc = decode_desc(q, k_cache, out, softmax_scale, kv_layout)
+    if idx_in.dtype != torch.int32 or not idx_in.is_contiguous() or idx_in.shape[2] != k_max:
+        raise ValueError("idx_in must be a contiguous int32 [B, Hkv_anchor, k_max] tensor")
+    workspace, nbytes = _workspace(OP_DECODE_REUSE, desc, 1, k_max, 0, q.device, workspace)
+    st = lib.kascade_decode_reuse(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seqlens),
+                                  _ptr(k_per_seq), int(k_max), _ptr(idx_in), int(idx_in.shape[1]), _ptr(head_map),
+                                  _ptr(out), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_decode_reuse")
+    return out
+
+
+def kascade_prefill_anchor(q, k, v, q_tile_tokens, k_per_tile, idx_offsets, idx_total,
+                           out_mode=KASCADE_OUT_SPARSE, idx_out=None, out=None, workspace=None, softmax_scale=0.0):
+    """q [S,Hq,d], k/v [Hkv,S,d].  Returns (idx_out [Hkv, idx_total] int32, out [S,Hq,d])."""
+    _need_gpu(q, k, v, k_per_tile, idx_offsets, idx_out, out, workspace)
+    lib = load_library()
+    S = q.shape[0]
+    if out is None:
+        out = torch.empty_like(q)
+    desc = prefill_desc(q, k, out, softmax_scale)
+    if idx_out is None:
+        idx_out = torch.empty(desc.n_kv_heads, max(int(idx_total), 1), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(OP_PREFILL_ANCHOR, desc, S, idx_total, q_tile_tokens, q.device, workspace)
+    st = lib.kascade_prefill_anchor(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), int(S), int(q_tile_tokens),
+                                    _ptr(k_per_tile), _ptr(idx_offsets), int(idx_total), int(out_mode),
+                                    _ptr(idx_out), _ptr(out), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_prefill_anchor")
+    return idx_out, out
+
+
+def kascade_prefill_reuse(q, k, v, q_tile_tokens, k_per_tile, idx_offsets, idx_total, idx_in, head_map=None,
+                          n_anchor_heads=None, out=None, workspace=None, softmax_scale=0.0):
+    """idx_in [Hkv_anchor, idx_total] int32.  Returns out [S,Hq,d]."""
+    _need_gpu(q, k, v, k_per_tile, idx_offsets, idx_in, head_map, out, workspace)
+    lib = load_library()
+    S = q.shape[0]
+    if out is None:
+        out = torch.empty_like(q)
+    desc = prefill_desc(q, k, out, softmax_scale)
+    if n_anchor_heads is None:
+        n_anchor_heads = idx_in.shape[0]
+    workspace, nbytes = _workspace(OP_PREFILL_REUSE, desc, S, idx_total, q_tile_tokens, q.device, workspace)
+    st = lib.kascade_prefill_reuse(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), int(S), int(q_tile_tokens),
+                                   _ptr(k_per_tile), _ptr(idx_offsets), int(idx_total), _ptr(idx_in),
+                                   int(n_anchor_heads), _ptr(head_map), _ptr(out), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_prefill_reuse")
+    return out

@@ -1,0 +1,253 @@
+// C ABI of the Kascade hot path: argument checks, launch planning, workspace carving.
+// No allocation, no synchronisation, no state kept between calls.
+#include "../../include/kascade.h"
+
+#include <math.h>
+#include <stdlib.h>
+
+#include "kernels.h"
+
+using namespace kascade;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kTargetBlocks = 1024;   // about four workgroups per compute unit (256 CUs)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+int64_t round_up_i(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+int env_int(const char* name, int fallback) {
+    const char* v = getenv(name);
+    if (!v || !*v) return fallback;
+    int x = atoi(v);
+    return x > 0 ? x : fallback;
+}
+
+int check_desc(const kascade_desc* d, bool prefill) {
+    if (!d) return KASCADE_INVALID_ARG;
+    if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0) return KASCADE_INVALID_ARG;
+    if (d->n_q_heads % d->n_kv_heads) return KASCADE_INVALID_ARG;
+    if (prefill && d->batch != 1) return KASCADE_INVALID_ARG;
+    const int G = d->n_q_heads / d->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return KASCADE_UNSUPPORTED;
+    if (d->head_dim != 64 && d->head_dim != 128) return KASCADE_UNSUPPORTED;
+    if (d->dtype != KASCADE_F32 && d->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    if (!(d->softmax_scale >= 0.f) || isinf(d->softmax_scale)) return KASCADE_INVALID_ARG;
+    const int64_t es = d->dtype == KASCADE_F32 ? 4 : 2;
+    const int64_t strides[] = {d->q_stride[0], d->q_stride[2], d->kv_stride[0], d->kv_stride[1], d->kv_stride[2],
+                               prefill ? d->q_stride[1] : 0};
+    for (int64_t s : strides) {
+        if (s < 0) return KASCADE_INVALID_ARG;
+        if ((s * es) % 16) return KASCADE_MISALIGNED;
+    }
+    if (d->kv_stride[2] < d->head_dim || d->q_stride[2] < d->head_dim || d->o_stride[2] < d->head_dim)
+        return KASCADE_INVALID_ARG;
+    return KASCADE_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+Shape make_shape(const kascade_desc* d) {
+    Shape s;
+    s.B = d->batch; s.Hq = d->n_q_heads; s.Hkv = d->n_kv_heads; s.D = d->head_dim;
+    s.G = s.Hq / s.Hkv;
+    s.dtype = d->dtype;
+    const double scale = d->softmax_scale > 0.f ? (double)d->softmax_scale : 1.0 / sqrt((double)d->head_dim);
+    s.scale_log2 = (float)(scale * 1.4426950408889634074);
+    for (int i = 0; i < 3; ++i) { s.q_stride[i] = d->q_stride[i]; s.kv_stride[i] = d->kv_stride[i]; s.o_stride[i] = d->o_stride[i]; }
+    return s;
+}
+
+// rows per workgroup for `n_rows` rows in each of `pairs` (sequence, key head) problems
+DecodePlan plan_rows(int64_t n_rows, int pairs, int min_chunk, int max_chunks, const char* env_name) {
+    DecodePlan p;
+    int64_t want = (kTargetBlocks + pairs - 1) / pairs;
+    if (want < 1) want = 1;
+    int64_t chunk = round_up_i((n_rows + want - 1) / want, 256);
+    if (chunk < min_chunk) chunk = min_chunk;
+    const int64_t floor_chunk = round_up_i((n_rows + max_chunks - 1) / max_chunks, 256);
+    if (chunk < floor_chunk) chunk = floor_chunk;
+    chunk = round_up_i(env_int(env_name, (int)chunk), 64);
+    if (chunk < floor_chunk) chunk = floor_chunk;
+    p.chunk = (int)chunk;
+    p.n_chunks = (int)((n_rows + chunk - 1) / chunk);
+    if (p.n_chunks < 1) p.n_chunks = 1;
+    return p;
+}
+DecodePlan plan_gather(const Shape& s, int64_t k_max) { return plan_rows(k_max, s.B * s.Hkv, 256, 64, "KASCADE_GATHER_CHUNK"); }
+DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 256, 256, "KASCADE_STREAM_CHUNK"); }
+
+struct Carver {
+    char* base; size_t used;
+    explicit Carver(void* p) : base(static_cast<char*>(p)), used(0) {}
+    template <typename T> T* take(size_t count) {
+        T* r = base ? reinterpret_cast<T*>(base + used) : nullptr;
+        used = align_up(used + count * sizeof(T), kAlign);
+        return r;
+    }
+};
+
+struct DecodeReuseWs { float* part_ml; float* part_acc; size_t bytes; };
+DecodeReuseWs carve_decode_reuse(const Shape& s, const DecodePlan& plan, void* ws, size_t offset = 0) {
+    Carver c(ws); c.used = offset;
+    DecodeReuseWs r;
+    const size_t rows = (size_t)s.B * s.Hq * plan.n_chunks;
+    r.part_ml = c.take<float>(rows * 2);
+    r.part_acc = c.take<float>(rows * s.D);
+    r.bytes = c.used;
+    return r;
+}
+
+struct DecodeAnchorWs {
+    float* logits; float* pooled; float* st_ml; float* st_acc; int64_t pitch; DecodeReuseWs gather; size_t bytes;
+};
+DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, const DecodePlan& gather,
+                                   int64_t max_seqlen, void* ws) {
+    Carver c(ws);
+    DecodeAnchorWs r;
+    r.pitch = round_up_i(max_seqlen, 4);
+    r.logits = c.take<float>((size_t)s.B * s.Hq * r.pitch);
+    r.pooled = c.take<float>((size_t)s.B * s.Hkv * r.pitch);
+    const size_t rows = (size_t)s.B * s.Hq * stream.n_chunks;
+    r.st_ml = c.take<float>(rows * 2);
+    r.st_acc = c.take<float>(rows * s.D);
+    r.gather = carve_decode_reuse(s, gather, ws, c.used);
+    r.bytes = r.gather.bytes;
+    return r;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
+
+}  // namespace
+
+extern "C" {
+
+const char* kascade_version(void) { return "0.1"; }
+
+const char* kascade_status_string(int32_t status) {
+    switch (status) {
+        case KASCADE_OK: return "ok";
+        case KASCADE_INVALID_ARG: return "invalid argument";
+        case KASCADE_UNSUPPORTED: return "unsupported head_dim, dtype, group size or tile size";
+        case KASCADE_MISALIGNED: return "pointer or stride breaks 16-byte row alignment";
+        case KASCADE_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case KASCADE_HIP_ERROR: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max_seqlen, int64_t k_or_idx_total,
+                               int32_t q_tile_tokens) {
+    const bool prefill = op == KASCADE_OP_PREFILL_ANCHOR || op == KASCADE_OP_PREFILL_REUSE;
+    if (check_desc(desc, prefill) != KASCADE_OK || max_seqlen <= 0 || k_or_idx_total < 0) return 0;
+    const Shape s = make_shape(desc);
+    (void)q_tile_tokens;
+    switch (op) {
+        case KASCADE_OP_DECODE_REUSE:
+            return carve_decode_reuse(s, plan_gather(s, k_or_idx_total), nullptr).bytes;
+        case KASCADE_OP_DECODE_ANCHOR:
+            return carve_decode_anchor(s, plan_stream(s, max_seqlen), plan_gather(s, k_or_idx_total), max_seqlen, nullptr).bytes;
+        default:
+            return 0;
+    }
+}
+
+int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_in,
+                         int32_t n_anchor_heads, const int32_t* head_map, void* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+    int st = check_desc(desc, false);
+    if (st != KASCADE_OK) return st;
+    if (!q || !k_cache || !v_cache || !seqlens || !k_per_seq || !idx_in || !out) return KASCADE_INVALID_ARG;
+    if (k_max <= 0 || n_anchor_heads <= 0) return KASCADE_INVALID_ARG;
+    if (!head_map && n_anchor_heads != desc->n_kv_heads) return KASCADE_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return KASCADE_MISALIGNED;
+    const Shape s = make_shape(desc);
+    const DecodePlan plan = plan_gather(s, k_max);
+    const DecodeReuseWs ws = carve_decode_reuse(s, plan, workspace);
+    if (ws.bytes > 0 && (!workspace || workspace_bytes < ws.bytes)) return KASCADE_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    DecodeRowsArgs a = {};
+    a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens; a.k_per_seq = k_per_seq;
+    a.idx = idx_in; a.head_map = head_map; a.k_max = k_max; a.n_src_heads = n_anchor_heads;
+    a.part_ml = ws.part_ml; a.part_acc = ws.part_acc; a.out = out;
+    st = hip_status(launch_decode_rows(s, plan, a, true, true, false, stream));
+    if (st != KASCADE_OK) return st;
+    if (plan.n_chunks > 1) st = hip_status(launch_decode_merge(s, plan.n_chunks, ws.part_ml, ws.part_acc, out, stream));
+    return st;
+}
+
+int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
+                          int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    int st = check_desc(desc, false);
+    if (st != KASCADE_OK) return st;
+    if (!q || !k_cache || !v_cache || !seqlens || !k_per_seq || !idx_out || !out) return KASCADE_INVALID_ARG;
+    if (max_seqlen <= 0 || k_max <= 0 || k_max > max_seqlen || recent_window < 0 || recent_window > k_max)
+        return KASCADE_INVALID_ARG;
+    if (out_mode != KASCADE_OUT_DENSE && out_mode != KASCADE_OUT_SPARSE) return KASCADE_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return KASCADE_MISALIGNED;
+    const Shape s = make_shape(desc);
+    const DecodePlan sp = plan_stream(s, max_seqlen);
+    const DecodePlan gp = plan_gather(s, k_max);
+    const DecodeAnchorWs ws = carve_decode_anchor(s, sp, gp, max_seqlen, workspace);
+    if (!workspace || workspace_bytes < ws.bytes) return KASCADE_WORKSPACE_TOO_SMALL;
+    if (!aligned16(workspace)) return KASCADE_MISALIGNED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool dense = out_mode == KASCADE_OUT_DENSE;
+
+    // pass 1: logits of every key + per-chunk softmax statistics (dense: also P.V)
+    DecodeRowsArgs a = {};
+    a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens;
+    a.logits = ws.logits; a.logit_pitch = ws.pitch;
+    a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = out;
+    st = hip_status(launch_decode_rows(s, sp, a, false, dense, true, stream));
+    if (st != KASCADE_OK) return st;
+    if (dense && sp.n_chunks > 1) {
+        st = hip_status(launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream));
+        if (st != KASCADE_OK) return st;
+    }
+    // pass 2: softmax + mean over the GQA group
+    st = hip_status(launch_decode_pool(s, sp.n_chunks, seqlens, ws.logits, ws.pitch, ws.st_ml, ws.pooled, ws.pitch,
+                                       max_seqlen, stream));
+    if (st != KASCADE_OK) return st;
+    // pass 3: Top-k per (sequence, key head)
+    TopkArgs t = {};
+    t.scores = ws.pooled; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
+    t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window;
+    st = hip_status(launch_topk_decode(s, t, stream));
+    if (st != KASCADE_OK || dense) return st;
+    // pass 4: attention over the fresh index set
+    DecodeRowsArgs g = {};
+    g.q = q; g.k = k_cache; g.v = v_cache; g.seqlens = seqlens; g.k_per_seq = k_per_seq;
+    g.idx = idx_out; g.head_map = nullptr; g.k_max = k_max; g.n_src_heads = s.Hkv;
+    g.part_ml = ws.gather.part_ml; g.part_acc = ws.gather.part_acc; g.out = out;
+    st = hip_status(launch_decode_rows(s, gp, g, true, true, false, stream));
+    if (st != KASCADE_OK) return st;
+    if (gp.n_chunks > 1) st = hip_status(launch_decode_merge(s, gp.n_chunks, ws.gather.part_ml, ws.gather.part_acc, out, stream));
+    return st;
+}
+
+int kascade_prefill_anchor(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
+                           int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
+                           int64_t idx_total, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    (void)desc; (void)q; (void)k; (void)v; (void)seqlen; (void)q_tile_tokens; (void)k_per_tile; (void)idx_offsets;
+    (void)idx_total; (void)out_mode; (void)idx_out; (void)out; (void)workspace; (void)workspace_bytes; (void)hip_stream;
+    return KASCADE_UNSUPPORTED;
+}
+
+int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
+                          int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
+                          int64_t idx_total, const int32_t* idx_in, int32_t n_anchor_heads, const int32_t* head_map,
+                          void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)desc; (void)q; (void)k; (void)v; (void)seqlen; (void)q_tile_tokens; (void)k_per_tile; (void)idx_offsets;
+    (void)idx_total; (void)idx_in; (void)n_anchor_heads; (void)head_map; (void)out; (void)workspace;
+    (void)workspace_bytes; (void)hip_stream;
+    return KASCADE_UNSUPPORTED;
+}
+
+}  // extern "C"

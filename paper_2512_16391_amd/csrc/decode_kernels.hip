@@ -1,0 +1,385 @@
+// Decode kernels of the Kascade hot path (gfx950, wave64, HBM-bound).
+//
+//  decode_rows_kernel   one kernel for the three row-streaming jobs of a decode step:
+//      gather mode  - reuse layer / anchor pass 4 (paper Sec. 3.6): rows named by a Top-k
+//                     index list are fetched from K and V and attended (Eq. 1-2 over k keys);
+//      stream mode  - anchor pass 1: every key row is read once, the base-2 logits of the
+//                     G query heads are written out together with per-chunk softmax statistics;
+//                     with V it also accumulates dense attention (layer 0).
+//  decode_merge_kernel  combines per-chunk (max, sum, acc) triples into the output.
+//  decode_pool_kernel   anchor pass 2: softmax from logits + statistics, mean over the GQA
+//                       group (Sec. 3.4).
+//
+// Data movement: a K or V row is 128..512 bytes.  LPR = row_bytes/16 adjacent lanes read one
+// row with one 16-byte load each, so a wave instruction fetches 64/LPR full rows and every
+// fetched byte is used.  Each lane group keeps U rows of K and of V in flight and owns a
+// private online-softmax stream (m, l, acc); streams are merged once per workgroup in LDS.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace kascade {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+template <typename T, int D, int G, bool GATHER, bool WITH_V, bool STORE>
+__global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+    constexpr int EPL = Elem<T>::EPL;
+    constexpr int LPR = D / EPL;            // lanes per row
+    constexpr int RPW = kWave / LPR;        // row groups per wave
+    constexpr int U = 8;                    // rows in flight per row group (LPR is 8, 16 or 32)
+    constexpr int NS = kWavesPerBlock * RPW;  // softmax streams per workgroup
+    constexpr int GB = (G > 4) ? 4 : G;     // heads merged per LDS round
+    static_assert(LPR % U == 0, "row group must hold a whole number of load batches");
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x >> 6;
+    const int c = lane % LPR;
+    const int r = lane / LPR;
+    const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
+    const int n_chunks = plan.n_chunks;
+
+    const int L = a.seqlens[b];
+    int n_rows = L;
+    if constexpr (GATHER) {
+        int kb = a.k_per_seq[b];
+        n_rows = kb < a.k_max ? kb : a.k_max;
+        if (L <= 0) n_rows = 0;
+    }
+    const int begin = chunk_id * plan.chunk;
+    const int end = (begin + plan.chunk < n_rows) ? begin + plan.chunk : n_rows;
+
+    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;   // + g * n_chunks
+
+    if (begin >= end) {   // nothing to do: mark the chunk empty for the merge / pooling passes
+        if (threadIdx.x < G) {
+            float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        if (WITH_V && n_chunks == 1) {   // empty sequence: defined output is zero
+            for (int e = threadIdx.x; e < G * D; e += kBlock) {
+                int g = e / D, col = e % D;
+                T* o = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + g) * s.o_stride[2] + col;
+                if constexpr (sizeof(T) == 4) *o = 0.f; else *o = 0;
+            }
+        }
+        return;
+    }
+
+    const T* Kb = reinterpret_cast<const T*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1] + c * EPL;
+    const T* Vb = reinterpret_cast<const T*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1] + c * EPL;
+    const int64_t row_stride = s.kv_stride[2];
+
+    const int32_t* idx = nullptr;
+    if constexpr (GATHER) {
+        int src = a.head_map ? a.head_map[hk] : hk;
+        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+        idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+    }
+
+    // queries of the group, pre-multiplied by scale*log2(e)
+    float qf[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const T* qp = reinterpret_cast<const T*>(a.q) + b * s.q_stride[0] + (int64_t)(hk * G + g) * s.q_stride[2] + c * EPL;
+        uint4 raw = *reinterpret_cast<const uint4*>(qp);
+        Elem<T>::widen(raw, qf[g]);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qf[g][e] *= s.scale_log2;
+    }
+
+    float m[G], l[G];
+    float acc[WITH_V ? G : 1][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.f; }
+#pragma unroll
+    for (int g = 0; g < (WITH_V ? G : 1); ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+
+    for (int j0 = begin + w * kWave; j0 < end; j0 += kWavesPerBlock * kWave) {
+        int my_row = -1;
+        if constexpr (GATHER) {
+            int i = j0 + lane;
+            if (i < end) my_row = idx[i];
+            if (my_row >= L) my_row = -1;
+        }
+        float keep[STORE ? G : 1];
+#pragma unroll
+        for (int u0 = 0; u0 < LPR; u0 += U) {
+            if (j0 + u0 < end) {   // wave-uniform: the smallest row of this batch is in range
+                uint4 kr[U], vr[WITH_V ? U : 1];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int slot = r * LPR + u0 + u;
+                    int row;
+                    if constexpr (GATHER) {
+                        row = __shfl(my_row, slot);
+                        ok[u] = row >= 0;
+                    } else {
+                        row = j0 + slot;
+                        ok[u] = row < end;
+                    }
+                    row = ok[u] ? row : 0;
+                    kr[u] = *reinterpret_cast<const uint4*>(Kb + (int64_t)row * row_stride);
+                    if constexpr (WITH_V) vr[u] = *reinterpret_cast<const uint4*>(Vb + (int64_t)row * row_stride);
+                }
+                float sc[U][G];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    float kf[EPL];
+                    Elem<T>::widen(kr[u], kf);
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        float d = 0.f;
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+                        d = group_sum<LPR>(d);
+                        sc[u][g] = ok[u] ? d : -INFINITY;
+                    }
+                }
+                if constexpr (STORE) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int g = 0; g < G; ++g)
+                            if (c == u0 + u) keep[g] = sc[u][g];
+                }
+                // online softmax (base 2) of this lane group's stream
+                float alpha[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float mx = sc[0][g];
+#pragma unroll
+                    for (int u = 1; u < U; ++u) mx = fmaxf(mx, sc[u][g]);
+                    const float mnew = fmaxf(m[g], mx);
+                    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+                    alpha[g] = __builtin_amdgcn_exp2f(m[g] - msafe);
+                    float psum = 0.f;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        sc[u][g] = __builtin_amdgcn_exp2f(sc[u][g] - msafe);
+                        psum += sc[u][g];
+                    }
+                    l[g] = fmaf(l[g], alpha[g], psum);
+                    m[g] = mnew;
+                }
+                if constexpr (WITH_V) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha[g];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        float vf[EPL];
+                        Elem<T>::widen(vr[u], vf);
+#pragma unroll
+                        for (int g = 0; g < G; ++g)
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(sc[u][g], vf[e], acc[g][e]);
+                    }
+                }
+            }
+        }
+        if constexpr (STORE) {
+            const int j = j0 + lane;
+            if (j < end) {
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    a.logits[((int64_t)b * s.Hq + hk * G + g) * a.logit_pitch + j] = keep[g];
+            }
+        }
+    }
+
+    // ---- merge the NS streams of the workgroup ----------------------------------
+    __shared__ float sm_m[NS][G];
+    __shared__ float sm_l[NS][G];
+    __shared__ float sm_acc[WITH_V ? NS : 1][GB][WITH_V ? D : 1];
+    const int sid = w * RPW + r;
+    if (c == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) { sm_m[sid][g] = m[g]; sm_l[sid][g] = l[g]; }
+    }
+#pragma unroll
+    for (int gb = 0; gb < G; gb += GB) {
+        if constexpr (WITH_V) {
+            if (gb > 0) __syncthreads();
+#pragma unroll
+            for (int g = 0; g < GB; ++g)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) sm_acc[sid][g][c * EPL + e] = acc[gb + g][e];
+        }
+        __syncthreads();
+        constexpr int NE = WITH_V ? GB * D : GB;
+        for (int e = threadIdx.x; e < NE; e += kBlock) {
+            const int g = WITH_V ? e / D : e;
+            const int col = WITH_V ? e % D : 0;
+            float M = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < NS; ++t) M = fmaxf(M, sm_m[t][gb + g]);
+            const float Ms = (M == -INFINITY) ? 0.f : M;
+            float lsum = 0.f, val = 0.f;
+#pragma unroll
+            for (int t = 0; t < NS; ++t) {
+                const float wgt = __builtin_amdgcn_exp2f(sm_m[t][gb + g] - Ms);
+                lsum = fmaf(wgt, sm_l[t][gb + g], lsum);
+                if constexpr (WITH_V) val = fmaf(wgt, sm_acc[t][g][col], val);
+            }
+            const int h = hk * G + gb + g;
+            const int64_t pidx = ((int64_t)(b * s.Hq + h)) * n_chunks + chunk_id;
+            if (WITH_V && n_chunks == 1) {
+                const float o = lsum > 0.f ? val / lsum : 0.f;
+                T* op = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2] + col;
+                if constexpr (sizeof(T) == 4) *op = o; else *op = (T)f32_to_bf16_bits(o);
+            } else if constexpr (WITH_V) {
+                a.part_acc[pidx * D + col] = val;
+            }
+            if (col == 0) {
+                a.part_ml[pidx * 2 + 0] = M;
+                a.part_ml[pidx * 2 + 1] = lsum;
+            }
+        }
+    }
+}
+
+// grid (Hq, B), block D threads: out[b,h,:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c
+template <typename T, int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(Shape s, int n_chunks, const float* __restrict__ part_ml,
+                                                         const float* __restrict__ part_acc, void* out) {
+    const int h = blockIdx.x, b = blockIdx.y, col = threadIdx.x;
+    const int64_t base = ((int64_t)(b * s.Hq + h)) * n_chunks;
+    float M = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[(base + c) * 2]);
+    float lsum = 0.f, val = 0.f;
+    if (M != -INFINITY) {
+        for (int c = 0; c < n_chunks; ++c) {
+            const float mc = part_ml[(base + c) * 2];
+            if (mc == -INFINITY) continue;
+            const float wgt = __builtin_amdgcn_exp2f(mc - M);
+            lsum = fmaf(wgt, part_ml[(base + c) * 2 + 1], lsum);
+            val = fmaf(wgt, part_acc[(base + c) * D + col], val);
+        }
+    }
+    const float o = lsum > 0.f ? val / lsum : 0.f;
+    T* op = reinterpret_cast<T*>(out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2] + col;
+    if constexpr (sizeof(T) == 4) *op = o; else *op = (T)f32_to_bf16_bits(o);
+}
+
+// grid (ceil(max_seqlen/1024), Hkv, B), block 256: four consecutive keys per thread.
+template <int G>
+__global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, const int32_t* __restrict__ seqlens,
+                                                             const float* __restrict__ logits, int64_t logit_pitch,
+                                                             const float* __restrict__ part_ml, float* __restrict__ pooled,
+                                                             int64_t pooled_pitch) {
+    const int b = blockIdx.z, hk = blockIdx.y;
+    const int L = seqlens[b];
+    const int j = (blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (blockIdx.x * kBlock * 4 >= L) return;   // uniform per workgroup
+    __shared__ float sh_M[G], sh_inv[G];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int g = w; g < G; g += kWavesPerBlock) {
+        const float* ml = part_ml + ((int64_t)(b * s.Hq + hk * G + g)) * n_chunks * 2;
+        float M = -INFINITY;
+        for (int c = lane; c < n_chunks; c += kWave) M = fmaxf(M, ml[c * 2]);
+        M = wave_max(M);
+        float lsum = 0.f;
+        for (int c = lane; c < n_chunks; c += kWave) {
+            const float mc = ml[c * 2];
+            if (mc != -INFINITY) lsum = fmaf(__builtin_amdgcn_exp2f(mc - M), ml[c * 2 + 1], lsum);
+        }
+        lsum = wave_sum(lsum);
+        if (lane == 0) { sh_M[g] = M; sh_inv[g] = 1.f / (lsum * (float)G); }
+    }
+    __syncthreads();
+    if (j >= L) return;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float4 sv = *reinterpret_cast<const float4*>(logits + ((int64_t)b * s.Hq + hk * G + g) * logit_pitch + j);
+        const float M = sh_M[g], inv = sh_inv[g];
+        p0 = fmaf(__builtin_amdgcn_exp2f(sv.x - M), inv, p0);
+        p1 = fmaf(__builtin_amdgcn_exp2f(sv.y - M), inv, p1);
+        p2 = fmaf(__builtin_amdgcn_exp2f(sv.z - M), inv, p2);
+        p3 = fmaf(__builtin_amdgcn_exp2f(sv.w - M), inv, p3);
+    }
+    float* dst = pooled + ((int64_t)b * s.Hkv + hk) * pooled_pitch + j;
+    if (j + 3 < L) {
+        *reinterpret_cast<float4*>(dst) = make_float4(p0, p1, p2, p3);
+    } else {
+        dst[0] = p0;
+        if (j + 1 < L) dst[1] = p1;
+        if (j + 2 < L) dst[2] = p2;
+    }
+}
+
+template <typename T, int D, int G>
+hipError_t launch_rows_tdg(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather,
+                           bool with_v, bool store, hipStream_t st) {
+    dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kBlock);
+    if (gather) {
+        hipLaunchKernelGGL((decode_rows_kernel<T, D, G, true, true, false>), grid, block, 0, st, s, plan, a);
+    } else if (with_v) {
+        hipLaunchKernelGGL((decode_rows_kernel<T, D, G, false, true, true>), grid, block, 0, st, s, plan, a);
+    } else {
+        hipLaunchKernelGGL((decode_rows_kernel<T, D, G, false, false, true>), grid, block, 0, st, s, plan, a);
+    }
+    (void)store;
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_rows_td(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather,
+                          bool with_v, bool store, hipStream_t st) {
+    switch (s.G) {
+        case 1: return launch_rows_tdg<T, D, 1>(s, plan, a, gather, with_v, store, st);
+        case 2: return launch_rows_tdg<T, D, 2>(s, plan, a, gather, with_v, store, st);
+        case 4: return launch_rows_tdg<T, D, 4>(s, plan, a, gather, with_v, store, st);
+        case 8: return launch_rows_tdg<T, D, 8>(s, plan, a, gather, with_v, store, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather,
+                              bool with_v, bool store_logits, hipStream_t st) {
+    if (s.dtype == 0) {
+        if (s.D == 64) return launch_rows_td<float, 64>(s, plan, a, gather, with_v, store_logits, st);
+        if (s.D == 128) return launch_rows_td<float, 128>(s, plan, a, gather, with_v, store_logits, st);
+    } else {
+        if (s.D == 64) return launch_rows_td<bf16_t, 64>(s, plan, a, gather, with_v, store_logits, st);
+        if (s.D == 128) return launch_rows_td<bf16_t, 128>(s, plan, a, gather, with_v, store_logits, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_ml, const float* part_acc,
+                               void* out, hipStream_t st) {
+    dim3 grid(s.Hq, s.B);
+    if (s.dtype == 0 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<float, 64>), grid, dim3(64), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 0 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), grid, dim3(128), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 1 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), grid, dim3(64), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 1 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), grid, dim3(128), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_pool(const Shape& s, int n_chunks, const int32_t* seqlens, const float* logits,
+                              int64_t logit_pitch, const float* part_ml, float* pooled, int64_t pooled_pitch,
+                              int max_seqlen, hipStream_t st) {
+    dim3 grid((max_seqlen + kBlock * 4 - 1) / (kBlock * 4), s.Hkv, s.B), block(kBlock);
+    switch (s.G) {
+        case 1: hipLaunchKernelGGL((decode_pool_kernel<1>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
+        case 2: hipLaunchKernelGGL((decode_pool_kernel<2>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
+        case 4: hipLaunchKernelGGL((decode_pool_kernel<4>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
+        case 8: hipLaunchKernelGGL((decode_pool_kernel<8>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace kascade

@@ -1,0 +1,83 @@
+// Host-side launch interface between the C ABI (api.hip) and the kernel files.
+// Everything here is internal to the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace kascade {
+
+struct Shape {
+    int B, Hq, Hkv, D, G;
+    int dtype;              // 0 fp32, 1 bf16
+    float scale_log2;       // softmax scale * log2(e): all softmax arithmetic is base 2
+    int64_t q_stride[3];
+    int64_t kv_stride[3];
+    int64_t o_stride[3];
+};
+
+// ---- decode ------------------------------------------------------------------
+// One launch plan for the row-streaming kernel: `chunk` rows per workgroup,
+// `n_chunks` workgroups per (sequence, key head).
+struct DecodePlan {
+    int chunk;
+    int n_chunks;
+};
+
+struct DecodeRowsArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const int32_t* seqlens;
+    const int32_t* k_per_seq;     // gather mode: rows per (b, hk); null in stream mode
+    const int32_t* idx;           // gather mode: [B, n_src_heads, k_max]
+    const int32_t* head_map;      // gather mode: [Hkv] or null
+    int32_t k_max;
+    int32_t n_src_heads;
+    float* logits;                // stream mode: [B, Hq, logit_pitch] base-2 scaled logits
+    int64_t logit_pitch;
+    float* part_ml;               // [B, Hq, n_chunks, 2]  (max, sum of 2^(s-max)) per chunk
+    float* part_acc;              // [B, Hq, n_chunks, D]  sum of 2^(s-max) * V, or null (no V)
+    void* out;                    // final output, written directly when n_chunks == 1 and V is read
+};
+
+// gather = true: rows come from the index list (reuse layer); false: rows 0..L-1 (anchor pass 1)
+hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a,
+                              bool gather, bool with_v, bool store_logits, hipStream_t st);
+
+// Merge the per-chunk partial results into the final output [B, Hq, D].
+hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_ml,
+                               const float* part_acc, void* out, hipStream_t st);
+
+// Anchor pass 2: softmax from the logits and per-chunk stats, mean over the GQA group.
+hipError_t launch_decode_pool(const Shape& s, int n_chunks, const int32_t* seqlens, const float* logits,
+                              int64_t logit_pitch, const float* part_ml, float* pooled,
+                              int64_t pooled_pitch, int max_seqlen, hipStream_t st);
+
+// ---- Top-k select -------------------------------------------------------------
+// Segment descriptor modes:
+//   decode : segment (b, hk): scores at pooled + (b*Hkv+hk)*pitch, length seqlens[b],
+//            k = k_per_seq[b], out at idx_out + (b*Hkv+hk)*k_max, padded with -1 to k_max.
+//   prefill: segment (t, hk): scores at pooled + hk*pooled_pitch + seg_offsets[t], length t*T,
+//            k = k_per_tile[t], out at idx_out + hk*idx_total + idx_offsets[t].
+struct TopkArgs {
+    const float* scores;
+    int32_t* idx_out;
+    // decode
+    const int32_t* seqlens;
+    const int32_t* k_per_seq;
+    int64_t pitch;
+    int32_t k_max;
+    int32_t recent_window;
+    // prefill
+    const int32_t* k_per_tile;
+    const int64_t* idx_offsets;
+    int64_t idx_total;
+    int64_t pooled_pitch;
+    int32_t tile_tokens;
+    int32_t n_tiles;
+};
+hipError_t launch_topk_decode(const Shape& s, const TopkArgs& a, hipStream_t st);
+hipError_t launch_topk_prefill(const Shape& s, const TopkArgs& a, hipStream_t st);
+
+}  // namespace kascade
