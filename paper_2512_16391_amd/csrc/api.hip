@@ -100,7 +100,8 @@ DecodeReuseWs carve_decode_reuse(const Shape& s, const DecodePlan& plan, void* w
 }
 
 struct DecodeAnchorWs {
-    float* logits; float* pooled; float* st_ml; float* st_acc; int64_t pitch; DecodeReuseWs gather; size_t bytes;
+    float* logits; float* pooled; float* st_ml; float* st_acc; uint32_t* hist11; int64_t pitch;
+    DecodeReuseWs gather; size_t bytes;
 };
 DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, const DecodePlan& gather,
                                    int64_t max_seqlen, void* ws) {
@@ -112,6 +113,7 @@ DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, con
     const size_t rows = (size_t)s.B * s.Hq * stream.n_chunks;
     r.st_ml = c.take<float>(rows * 2);
     r.st_acc = c.take<float>(rows * s.D);
+    r.hist11 = c.take<uint32_t>((size_t)s.B * s.Hkv * 2048);
     r.gather = carve_decode_reuse(s, gather, ws, c.used);
     r.bytes = r.gather.bytes;
     return r;
@@ -203,7 +205,7 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
     DecodeRowsArgs a = {};
     a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens;
     a.logits = ws.logits; a.logit_pitch = ws.pitch;
-    a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = out;
+    a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = out; a.hist11 = ws.hist11;
     st = hip_status(launch_decode_rows(s, sp, a, false, dense, true, stream));
     if (st != KASCADE_OK) return st;
     if (dense && sp.n_chunks > 1) {
@@ -211,12 +213,15 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
         if (st != KASCADE_OK) return st;
     }
     // pass 2: softmax + mean over the GQA group
-    st = hip_status(launch_decode_pool(s, sp.n_chunks, seqlens, ws.logits, ws.pitch, ws.st_ml, ws.pooled, ws.pitch,
-                                       max_seqlen, stream));
+    DecodePoolArgs pa = {};
+    pa.seqlens = seqlens; pa.k_per_seq = k_per_seq; pa.k_max = k_max; pa.recent_window = recent_window;
+    pa.logits = ws.logits; pa.logit_pitch = ws.pitch; pa.part_ml = ws.st_ml; pa.pooled = ws.pooled;
+    pa.pooled_pitch = ws.pitch; pa.hist11 = ws.hist11; pa.max_seqlen = max_seqlen;
+    st = hip_status(launch_decode_pool(s, sp.n_chunks, pa, stream));
     if (st != KASCADE_OK) return st;
     // pass 3: Top-k per (sequence, key head)
     TopkArgs t = {};
-    t.scores = ws.pooled; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
+    t.scores = ws.pooled; t.hist11 = ws.hist11; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
     t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window;
     st = hip_status(launch_topk_decode(s, t, stream));
     if (st != KASCADE_OK || dense) return st;

@@ -53,6 +53,13 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
 
     const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;   // + g * n_chunks
 
+    if constexpr (!GATHER) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
+        if (chunk_id == 0 && a.hist11) {
+            uint32_t* h = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
+            for (int i = threadIdx.x; i < 2048; i += kBlock) h[i] = 0u;
+        }
+    }
+
     if (begin >= end) {   // nothing to do: mark the chunk empty for the merge / pooling passes
         if (threadIdx.x < G) {
             float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
@@ -270,19 +277,24 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(Shape s, int n_chunks, 
 }
 
 // grid (ceil(max_seqlen/1024), Hkv, B), block 256: four consecutive keys per thread.
+// Writes the pooled scores and counts the Top-k candidates (positions before the forced
+// recent window) by the top 11 value bits of their score.
 template <int G>
-__global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, const int32_t* __restrict__ seqlens,
-                                                             const float* __restrict__ logits, int64_t logit_pitch,
-                                                             const float* __restrict__ part_ml, float* __restrict__ pooled,
-                                                             int64_t pooled_pitch) {
+__global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, DecodePoolArgs a) {
     const int b = blockIdx.z, hk = blockIdx.y;
-    const int L = seqlens[b];
-    const int j = (blockIdx.x * kBlock + threadIdx.x) * 4;
+    const int L = a.seqlens[b];
     if (blockIdx.x * kBlock * 4 >= L) return;   // uniform per workgroup
+    int k = a.k_per_seq[b];
+    k = k < 0 ? 0 : (k > L ? L : k);
+    k = k > a.k_max ? a.k_max : k;
+    const int n_cand = L - (a.recent_window < k ? a.recent_window : k);
+    const int j = (blockIdx.x * kBlock + threadIdx.x) * 4;
     __shared__ float sh_M[G], sh_inv[G];
+    __shared__ uint32_t lh[2048];
+    for (int i = threadIdx.x; i < 2048; i += kBlock) lh[i] = 0u;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     for (int g = w; g < G; g += kWavesPerBlock) {
-        const float* ml = part_ml + ((int64_t)(b * s.Hq + hk * G + g)) * n_chunks * 2;
+        const float* ml = a.part_ml + ((int64_t)(b * s.Hq + hk * G + g)) * n_chunks * 2;
         float M = -INFINITY;
         for (int c = lane; c < n_chunks; c += kWave) M = fmaxf(M, ml[c * 2]);
         M = wave_max(M);
@@ -295,24 +307,33 @@ __global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chun
         if (lane == 0) { sh_M[g] = M; sh_inv[g] = 1.f / (lsum * (float)G); }
     }
     __syncthreads();
-    if (j >= L) return;
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+    float p[4] = {0.f, 0.f, 0.f, 0.f};
+    if (j < L) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const float4 sv = *reinterpret_cast<const float4*>(logits + ((int64_t)b * s.Hq + hk * G + g) * logit_pitch + j);
-        const float M = sh_M[g], inv = sh_inv[g];
-        p0 = fmaf(__builtin_amdgcn_exp2f(sv.x - M), inv, p0);
-        p1 = fmaf(__builtin_amdgcn_exp2f(sv.y - M), inv, p1);
-        p2 = fmaf(__builtin_amdgcn_exp2f(sv.z - M), inv, p2);
-        p3 = fmaf(__builtin_amdgcn_exp2f(sv.w - M), inv, p3);
+        for (int g = 0; g < G; ++g) {
+            const float4 sv = *reinterpret_cast<const float4*>(a.logits + ((int64_t)b * s.Hq + hk * G + g) * a.logit_pitch + j);
+            const float M = sh_M[g], inv = sh_inv[g];
+            p[0] = fmaf(__builtin_amdgcn_exp2f(sv.x - M), inv, p[0]);
+            p[1] = fmaf(__builtin_amdgcn_exp2f(sv.y - M), inv, p[1]);
+            p[2] = fmaf(__builtin_amdgcn_exp2f(sv.z - M), inv, p[2]);
+            p[3] = fmaf(__builtin_amdgcn_exp2f(sv.w - M), inv, p[3]);
+        }
+        float* dst = a.pooled + ((int64_t)b * s.Hkv + hk) * a.pooled_pitch + j;
+        if (j + 3 < L) {
+            *reinterpret_cast<float4*>(dst) = make_float4(p[0], p[1], p[2], p[3]);
+        } else {
+            dst[0] = p[0];
+            if (j + 1 < L) dst[1] = p[1];
+            if (j + 2 < L) dst[2] = p[2];
+        }
     }
-    float* dst = pooled + ((int64_t)b * s.Hkv + hk) * pooled_pitch + j;
-    if (j + 3 < L) {
-        *reinterpret_cast<float4*>(dst) = make_float4(p0, p1, p2, p3);
-    } else {
-        dst[0] = p0;
-        if (j + 1 < L) dst[1] = p1;
-        if (j + 2 < L) dst[2] = p2;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) hist_add(lh, (__float_as_uint(p[e]) >> 20) & 2047u, j + e < n_cand);
+    __syncthreads();
+    uint32_t* gh = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
+    for (int i = threadIdx.x; i < 2048; i += kBlock) {
+        const uint32_t c = lh[i];
+        if (c) atomicAdd(&gh[i], c);
     }
 }
 
@@ -368,15 +389,13 @@ hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_m
     return hipGetLastError();
 }
 
-hipError_t launch_decode_pool(const Shape& s, int n_chunks, const int32_t* seqlens, const float* logits,
-                              int64_t logit_pitch, const float* part_ml, float* pooled, int64_t pooled_pitch,
-                              int max_seqlen, hipStream_t st) {
-    dim3 grid((max_seqlen + kBlock * 4 - 1) / (kBlock * 4), s.Hkv, s.B), block(kBlock);
+hipError_t launch_decode_pool(const Shape& s, int n_chunks, const DecodePoolArgs& a, hipStream_t st) {
+    dim3 grid((a.max_seqlen + kBlock * 4 - 1) / (kBlock * 4), s.Hkv, s.B), block(kBlock);
     switch (s.G) {
-        case 1: hipLaunchKernelGGL((decode_pool_kernel<1>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
-        case 2: hipLaunchKernelGGL((decode_pool_kernel<2>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
-        case 4: hipLaunchKernelGGL((decode_pool_kernel<4>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
-        case 8: hipLaunchKernelGGL((decode_pool_kernel<8>), grid, block, 0, st, s, n_chunks, seqlens, logits, logit_pitch, part_ml, pooled, pooled_pitch); break;
+        case 1: hipLaunchKernelGGL((decode_pool_kernel<1>), grid, block, 0, st, s, n_chunks, a); break;
+        case 2: hipLaunchKernelGGL((decode_pool_kernel<2>), grid, block, 0, st, s, n_chunks, a); break;
+        case 4: hipLaunchKernelGGL((decode_pool_kernel<4>), grid, block, 0, st, s, n_chunks, a); break;
+        case 8: hipLaunchKernelGGL((decode_pool_kernel<8>), grid, block, 0, st, s, n_chunks, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

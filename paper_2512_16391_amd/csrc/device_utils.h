@@ -82,6 +82,19 @@ __device__ __forceinline__ float group_max(float x) {
 __device__ __forceinline__ float wave_sum(float x) { return group_sum<64>(x); }
 __device__ __forceinline__ float wave_max(float x) { return group_max<64>(x); }
 
+// hist[digit] += 1 for active lanes; lanes that share the first active lane's digit are
+// combined into one LDS atomic (guards against thousands of equal scores hitting one bin).
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t digit, bool active) {
+    const uint64_t act = __ballot(active);
+    if (act == 0) return;
+    const int lane = threadIdx.x & 63;
+    const int leader = __ffsll((unsigned long long)act) - 1;
+    const uint32_t d0 = __shfl(digit, leader);
+    const uint64_t same = __ballot(active && digit == d0);
+    if (lane == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+    if (active && digit != d0) atomicAdd(&hist[digit], 1u);
+}
+
 // exp(x) through the hardware exp2
 __device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 

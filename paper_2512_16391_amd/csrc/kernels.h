@@ -39,6 +39,7 @@ struct DecodeRowsArgs {
     float* part_ml;               // [B, Hq, n_chunks, 2]  (max, sum of 2^(s-max)) per chunk
     float* part_acc;              // [B, Hq, n_chunks, D]  sum of 2^(s-max) * V, or null (no V)
     void* out;                    // final output, written directly when n_chunks == 1 and V is read
+    uint32_t* hist11;             // stream mode: [B, Hkv, 2048] Top-k histogram, zeroed here for pass 2
 };
 
 // gather = true: rows come from the index list (reuse layer); false: rows 0..L-1 (anchor pass 1)
@@ -50,9 +51,22 @@ hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_m
                                const float* part_acc, void* out, hipStream_t st);
 
 // Anchor pass 2: softmax from the logits and per-chunk stats, mean over the GQA group.
-hipError_t launch_decode_pool(const Shape& s, int n_chunks, const int32_t* seqlens, const float* logits,
-                              int64_t logit_pitch, const float* part_ml, float* pooled,
-                              int64_t pooled_pitch, int max_seqlen, hipStream_t st);
+// Also counts, per (sequence, key head), the pooled scores of the Top-k candidates by their top
+// 11 value bits into hist11 [B, Hkv, 2048] (first radix round of the selection).
+struct DecodePoolArgs {
+    const int32_t* seqlens;
+    const int32_t* k_per_seq;
+    int32_t k_max;
+    int32_t recent_window;
+    const float* logits;
+    int64_t logit_pitch;
+    const float* part_ml;
+    float* pooled;
+    int64_t pooled_pitch;
+    uint32_t* hist11;
+    int max_seqlen;
+};
+hipError_t launch_decode_pool(const Shape& s, int n_chunks, const DecodePoolArgs& a, hipStream_t st);
 
 // ---- Top-k select -------------------------------------------------------------
 // Segment descriptor modes:
@@ -62,6 +76,7 @@ hipError_t launch_decode_pool(const Shape& s, int n_chunks, const int32_t* seqle
 //            k = k_per_tile[t], out at idx_out + hk*idx_total + idx_offsets[t].
 struct TopkArgs {
     const float* scores;
+    const uint32_t* hist11;       // decode: precomputed first-round histogram, or null
     int32_t* idx_out;
     // decode
     const int32_t* seqlens;
