@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the Kascade hot path on one MI355X.
+
+One "step" = one pass of the hot path over one batch of seeded synthetic input:
+  decode  - the Llama-3.1-8B-shaped configuration (32 query / 8 key heads, d 128, bf16,
+            batch 8, 32768-token contiguous KV cache per sequence, k = 10 %): one anchor
+            layer followed by three reuse layers, each layer with its own Q/K/V;
+  prefill - (when the prefill kernels are built) batch 1, 32768 tokens causal, same heads,
+            tiles of 32 tokens x 4 heads, k_t = 10 % of the prefix (min 256): one anchor
+            layer followed by three reuse layers.
+All inputs are resident in HBM before the timed region; nothing is allocated inside it.
+
+Prints ONE JSON line.  `value` is the decode attention time per layer (the headline metric's
+first component); HBM GB/s of the reuse gather and prefill TFLOP/s ride along in extra keys.
+Per-kernel durations come from HIP events recorded by the library around each launch on the
+launch stream, inside the timed region.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--cpu-sample-seqs", type=int, default=8)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_16391_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    binding.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---------------- decode workload (resident, preallocated) ----------------
+    wl = workloads.config2(device=dev)
+    B, Hq, Hkv, d = wl.B, wl.Hq, wl.Hkv, wl.d
+    L, kmax = wl.Lmax, wl.k_max
+    seqlens = torch.tensor(wl.seqlens, dtype=torch.int32, device=dev)
+    kps = torch.tensor(wl.k_per_seq, dtype=torch.int32, device=dev)
+    idx = torch.empty(B, Hkv, kmax, dtype=torch.int32, device=dev)
+    outs = [torch.empty_like(l.q) for l in wl.layers]
+    desc = binding.decode_desc(wl.layers[0].q, wl.layers[0].k)
+    ws_bytes = max(binding.kascade_workspace_bytes(binding.OP_DECODE_ANCHOR, desc, L, kmax),
+                   binding.kascade_workspace_bytes(binding.OP_DECODE_REUSE, desc, L, kmax))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def decode_step(out_mode=binding.KASCADE_OUT_SPARSE):
+        a = wl.layers[0]
+        binding.kascade_decode_anchor(a.q, a.k, a.v, seqlens, kps, L, kmax, 0, out_mode, idx, outs[0], ws)
+        for i in range(1, len(wl.layers)):
+            r = wl.layers[i]
+            binding.kascade_decode_reuse(r.q, r.k, r.v, seqlens, kps, kmax, idx, None, outs[i], ws)
+
+    # ---------------- prefill workload ----------------
+    prefill = None
+    if not args.no_prefill:
+        try:
+            from bench_prefill import PrefillBench  # built with the prefill kernels
+            prefill = PrefillBench(dev)
+        except ImportError:
+            prefill = None
+
+    def step():
+        decode_step()
+        if prefill is not None:
+            prefill.step()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    binding.kascade_profile_enable(True)
+    binding.kascade_profile_reset()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    dec_ms = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev[0].record()
+        decode_step()
+        ev[1].record()
+        if prefill is not None:
+            prefill.step()
+        ev[1].synchronize()
+        dec_ms += ev[0].elapsed_time(ev[1])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = binding.kascade_profile_read()
+    binding.kascade_profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    n_layers = len(wl.layers)
+    dec_us_per_layer = dec_ms * 1e3 / args.steps / n_layers
+
+    def avg_us(name):
+        return prof[name][0] * 1e3 / prof[name][1] if name in prof else None
+
+    # algorithmic bytes per launch (bf16 rows of d elements, int32 indices, Q and O)
+    row_pairs = sum(wl.k_per_seq) * Hkv
+    gather_bytes = row_pairs * (2 * d * 2 + 4) + 2 * B * Hq * d * 2
+    stream_bytes = sum(wl.seqlens) * Hkv * d * 2 + sum(wl.seqlens) * Hq * 4 + B * Hq * d * 2
+    t_gather, t_stream = avg_us("decode_gather"), avg_us("decode_stream")
+    kernels_us = {k: round(v[0] * 1e3 / v[1], 2) for k, v in prof.items()}
+    # dominant kernel of the decode step by total device time
+    roofline = {"kernel": "decode_stream", "bound": "hbm", "achieved": round(stream_bytes / t_stream / 1e3, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(stream_bytes / t_stream / 1e3 / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes": stream_bytes, "avg_kernel_us": round(t_stream, 2)}
+    roofline_reuse = {"kernel": "decode_gather", "bound": "hbm", "achieved": round(gather_bytes / t_gather / 1e3, 1),
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gather_bytes / t_gather / 1e3 / HBM_PEAK_GBS, 4),
+                      "traffic": None, "algorithmic_bytes": gather_bytes, "avg_kernel_us": round(t_gather, 2)}
+
+    rec = {
+        "metric": "sparse decode attn us/layer + HBM GB/s; prefill attn TFLOPS at 32K ctx",
+        "value": round(dec_us_per_layer, 2), "unit": "us/layer (decode, mean of 1 anchor + 3 reuse layers)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name + " k=%d (10%%), 1 anchor + 3 reuse layers" % kmax
+                   + ("; " + prefill.name if prefill is not None else ""),
+                   "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "context": L, "k": kmax},
+        "decode_tokens_per_s": round(B / (dec_us_per_layer * n_layers * 1e-6), 1),
+        "decode_reuse_hbm_GBps": roofline_reuse["achieved"],
+        "kernel_us": kernels_us,
+        "roofline": roofline,
+        "roofline_reuse": roofline_reuse,
+    }
+    if prefill is not None:
+        rec.update(prefill.report(prof, MFMA_BF16_PEAK_TFLOPS))
+
+    # anchor with dense output (layer 0) measured outside the timed region, for the paper's
+    # per-layer weighting (1 dense-output anchor, 4 anchors, 27 reuse layers of 32)
+    a = wl.layers[0]
+    tt = []
+    for mode in (binding.KASCADE_OUT_DENSE, binding.KASCADE_OUT_SPARSE):
+        for _ in range(3):
+            binding.kascade_decode_anchor(a.q, a.k, a.v, seqlens, kps, L, kmax, 0, mode, idx, outs[0], ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            binding.kascade_decode_anchor(a.q, a.k, a.v, seqlens, kps, L, kmax, 0, mode, idx, outs[0], ws)
+        e1.record()
+        e1.synchronize()
+        tt.append(e0.elapsed_time(e1) * 1e3 / 20)
+    r1 = wl.layers[1]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(21):
+        r = wl.layers[1 + i % 3]
+        binding.kascade_decode_reuse(r.q, r.k, r.v, seqlens, kps, kmax, idx, None, outs[1 + i % 3], ws)
+    e1.record()
+    e1.synchronize()
+    t_reuse = e0.elapsed_time(e1) * 1e3 / 21
+    rec["decode_layer_us"] = {"anchor_dense_out": round(tt[0], 2), "anchor_sparse_out": round(tt[1], 2),
+                              "reuse": round(t_reuse, 2),
+                              "paper_weighted_avg_32_layers_5_anchors": round((tt[0] + 4 * tt[1] + 27 * t_reuse) / 32, 2)}
+
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_seqs)
+    print(json.dumps(rec), flush=True)
+
+
+def _blas_threads():
+    """Threads numpy's BLAS (the oracle's matrix products) actually runs with."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"]
+        return int(max(n)) if n else 1
+    except Exception:
+        return 1
+
+
+def cpu_baseline(wl, n_seqs):
+    """The fp64 oracle, as it stands, on a bounded sample of the decode workload: the first
+    `n_seqs` sequences of the batch through the same four layers.  Scaled to the full batch."""
+    import numpy as np
+    import torch
+    from oracle import kascade_oracle as ko
+
+    n_seqs = min(n_seqs, wl.B)
+    f = lambda t: t.to("cpu").to(torch.float32).to(torch.float64).numpy()
+    scale = ko.default_scale(wl.d)
+    dt = 0.0
+    for b in range(n_seqs):
+        Lb, kb = wl.seqlens[b], wl.k_per_seq[b]
+        # widening the device bits to fp64 is input plumbing, not oracle work: not timed
+        host = [(f(l.q[b]), f(l.k[b, :, :Lb]), f(l.v[b, :, :Lb])) for l in wl.layers]
+        t0 = time.perf_counter()
+        q, k, v = host[0]
+        idx, _ = ko.decode_anchor_indices(q, k, scale, kb, wl.recent_window)
+        ko.sparse_decode(q, k, v, idx, scale)
+        for q, k, v in host[1:]:
+            ko.sparse_decode(q, k, v, idx, scale)
+        dt += time.perf_counter() - t0
+        del host
+    us_per_layer = dt * 1e6 / len(wl.layers) * (wl.B / n_seqs)
+    return {"value": round(us_per_layer, 1), "unit": "us/layer (decode, scaled to the full batch)",
+            "cores": _blas_threads(), "kind": "oracle",
+            "sample": f"{n_seqs} of {wl.B} sequences, all heads, 1 anchor + 3 reuse layers, {dt:.2f} s measured"}
+
+
+if __name__ == "__main__":
+    main()

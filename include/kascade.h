@@ -149,6 +149,20 @@ size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max
 /* Static, NUL-terminated description of a status code. */
 const char* kascade_status_string(int32_t status);
 
+/*
+ * Measurement aid (not part of the method): per-kernel device time through HIP events.
+ * kascade_profile_enable(1) makes every later kernel launch of the library record a start and
+ * a stop event on the call's stream; events are created on demand (so do not enable it under
+ * stream capture) and destroyed by kascade_profile_enable(0).  kascade_profile_read waits for
+ * the recorded events of kernel `kernel` (0 <= kernel < kascade_profile_kernels()), and returns
+ * its name, the summed elapsed milliseconds and the number of launches since the last
+ * kascade_profile_reset().  With profiling off (the default) the library creates no events.
+ */
+int kascade_profile_enable(int32_t on);
+int kascade_profile_reset(void);
+int32_t kascade_profile_kernels(void);
+int kascade_profile_read(int32_t kernel, const char** name, double* total_ms, int64_t* launches);
+
 /* Library version, "major.minor". */
 const char* kascade_version(void);
 

@@ -24,6 +24,7 @@ OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE = 0, 1, 2
 EXPORTS = [
     "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
+    "kascade_profile_enable", "kascade_profile_reset", "kascade_profile_kernels", "kascade_profile_read",
 ]
 
 
@@ -70,6 +71,15 @@ def load_library(path: Optional[str] = None):
     lib.kascade_status_string.restype = ctypes.c_char_p
     lib.kascade_version.argtypes = []
     lib.kascade_version.restype = ctypes.c_char_p
+    lib.kascade_profile_enable.argtypes = [i32]
+    lib.kascade_profile_enable.restype = ctypes.c_int
+    lib.kascade_profile_reset.argtypes = []
+    lib.kascade_profile_reset.restype = ctypes.c_int
+    lib.kascade_profile_kernels.argtypes = []
+    lib.kascade_profile_kernels.restype = i32
+    lib.kascade_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(i64)]
+    lib.kascade_profile_read.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -80,6 +90,27 @@ def status_string(status: int) -> str:
 
 def version() -> str:
     return load_library().kascade_version().decode()
+
+
+def kascade_profile_enable(on: bool) -> None:
+    _check(load_library().kascade_profile_enable(1 if on else 0), "kascade_profile_enable")
+
+
+def kascade_profile_reset() -> None:
+    _check(load_library().kascade_profile_reset(), "kascade_profile_reset")
+
+
+def kascade_profile_read() -> dict:
+    """{kernel name: (total_ms, launches)} for kernels launched since the last reset."""
+    lib = load_library()
+    res = {}
+    for kid in range(lib.kascade_profile_kernels()):
+        name, ms, n = ctypes.c_char_p(), ctypes.c_double(), ctypes.c_int64()
+        _check(lib.kascade_profile_read(kid, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(n)),
+               "kascade_profile_read")
+        if n.value:
+            res[name.value.decode()] = (ms.value, n.value)
+    return res
 
 
 def _dtype_code(t: torch.Tensor) -> int:

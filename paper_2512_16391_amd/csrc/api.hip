@@ -4,6 +4,10 @@
 
 #include <math.h>
 #include <stdlib.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
 
 #include "kernels.h"
 
@@ -121,11 +125,85 @@ DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, con
 
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
+// ---- optional per-kernel timing (measurement aid, off by default) -----------------
+// When enabled every kernel launch is bracketed by two hipEvents on the call's stream.
+// Events are created on demand and kept until profiling is disabled; with profiling off
+// the library creates nothing.
+enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP2,
+                K_PF_TOPK, K_PF_SPARSE, K_COUNT };
+const char* const kKernelNames[K_COUNT] = {
+    "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
+    "prefill_sweep1", "prefill_sweep2", "prefill_topk", "prefill_sparse"};
+
+struct ProfRec { int kid; hipEvent_t start, stop; };
+struct Profiler {
+    bool on = false;
+    std::vector<ProfRec> recs;
+    std::vector<hipEvent_t> free_events;
+    std::mutex mu;
+    hipEvent_t get() {
+        if (!free_events.empty()) { hipEvent_t e = free_events.back(); free_events.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+} g_prof;
+
+template <typename F>
+int timed(int kid, hipStream_t st, F&& launch) {
+    if (!g_prof.on) return hip_status(launch());
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    ProfRec r{kid, g_prof.get(), g_prof.get()};
+    if (r.start) (void)hipEventRecord(r.start, st);
+    const int rc = hip_status(launch());
+    if (r.stop) (void)hipEventRecord(r.stop, st);
+    if (r.start && r.stop) g_prof.recs.push_back(r);
+    return rc;
+}
+
 }  // namespace
 
 extern "C" {
 
 const char* kascade_version(void) { return "0.1"; }
+
+int kascade_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    g_prof.on = on != 0;
+    if (!g_prof.on) {
+        for (auto& r : g_prof.recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        for (auto e : g_prof.free_events) (void)hipEventDestroy(e);
+        g_prof.recs.clear();
+        g_prof.free_events.clear();
+    }
+    return KASCADE_OK;
+}
+
+int kascade_profile_reset(void) {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    for (auto& r : g_prof.recs) { g_prof.free_events.push_back(r.start); g_prof.free_events.push_back(r.stop); }
+    g_prof.recs.clear();
+    return KASCADE_OK;
+}
+
+int32_t kascade_profile_kernels(void) { return K_COUNT; }
+
+int kascade_profile_read(int32_t kernel, const char** name, double* total_ms, int64_t* launches) {
+    if (kernel < 0 || kernel >= K_COUNT || !name || !total_ms || !launches) return KASCADE_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    *name = kKernelNames[kernel];
+    *total_ms = 0.0;
+    *launches = 0;
+    for (auto& r : g_prof.recs) {
+        if (r.kid != kernel) continue;
+        if (hipEventSynchronize(r.stop) != hipSuccess) return KASCADE_HIP_ERROR;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return KASCADE_HIP_ERROR;
+        *total_ms += ms;
+        *launches += 1;
+    }
+    return KASCADE_OK;
+}
 
 const char* kascade_status_string(int32_t status) {
     switch (status) {
@@ -175,9 +253,10 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
     a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens; a.k_per_seq = k_per_seq;
     a.idx = idx_in; a.head_map = head_map; a.k_max = k_max; a.n_src_heads = n_anchor_heads;
     a.part_ml = ws.part_ml; a.part_acc = ws.part_acc; a.out = out;
-    st = hip_status(launch_decode_rows(s, plan, a, true, true, false, stream));
+    st = timed(K_GATHER, stream, [&] { return launch_decode_rows(s, plan, a, true, true, false, stream); });
     if (st != KASCADE_OK) return st;
-    if (plan.n_chunks > 1) st = hip_status(launch_decode_merge(s, plan.n_chunks, ws.part_ml, ws.part_acc, out, stream));
+    if (plan.n_chunks > 1)
+        st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, plan.n_chunks, ws.part_ml, ws.part_acc, out, stream); });
     return st;
 }
 
@@ -206,10 +285,10 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
     a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens;
     a.logits = ws.logits; a.logit_pitch = ws.pitch;
     a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = out; a.hist11 = ws.hist11;
-    st = hip_status(launch_decode_rows(s, sp, a, false, dense, true, stream));
+    st = timed(dense ? K_STREAM_V : K_STREAM, stream, [&] { return launch_decode_rows(s, sp, a, false, dense, true, stream); });
     if (st != KASCADE_OK) return st;
     if (dense && sp.n_chunks > 1) {
-        st = hip_status(launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream));
+        st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream); });
         if (st != KASCADE_OK) return st;
     }
     // pass 2: softmax + mean over the GQA group
@@ -217,22 +296,23 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
     pa.seqlens = seqlens; pa.k_per_seq = k_per_seq; pa.k_max = k_max; pa.recent_window = recent_window;
     pa.logits = ws.logits; pa.logit_pitch = ws.pitch; pa.part_ml = ws.st_ml; pa.pooled = ws.pooled;
     pa.pooled_pitch = ws.pitch; pa.hist11 = ws.hist11; pa.max_seqlen = max_seqlen;
-    st = hip_status(launch_decode_pool(s, sp.n_chunks, pa, stream));
+    st = timed(K_POOL, stream, [&] { return launch_decode_pool(s, sp.n_chunks, pa, stream); });
     if (st != KASCADE_OK) return st;
     // pass 3: Top-k per (sequence, key head)
     TopkArgs t = {};
     t.scores = ws.pooled; t.hist11 = ws.hist11; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
     t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window;
-    st = hip_status(launch_topk_decode(s, t, stream));
+    st = timed(K_TOPK, stream, [&] { return launch_topk_decode(s, t, stream); });
     if (st != KASCADE_OK || dense) return st;
     // pass 4: attention over the fresh index set
     DecodeRowsArgs g = {};
     g.q = q; g.k = k_cache; g.v = v_cache; g.seqlens = seqlens; g.k_per_seq = k_per_seq;
     g.idx = idx_out; g.head_map = nullptr; g.k_max = k_max; g.n_src_heads = s.Hkv;
     g.part_ml = ws.gather.part_ml; g.part_acc = ws.gather.part_acc; g.out = out;
-    st = hip_status(launch_decode_rows(s, gp, g, true, true, false, stream));
+    st = timed(K_GATHER, stream, [&] { return launch_decode_rows(s, gp, g, true, true, false, stream); });
     if (st != KASCADE_OK) return st;
-    if (gp.n_chunks > 1) st = hip_status(launch_decode_merge(s, gp.n_chunks, ws.gather.part_ml, ws.gather.part_acc, out, stream));
+    if (gp.n_chunks > 1)
+        st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, gp.n_chunks, ws.gather.part_ml, ws.gather.part_acc, out, stream); });
     return st;
 }
 
