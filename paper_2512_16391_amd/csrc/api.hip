@@ -123,17 +123,29 @@ DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, con
     return r;
 }
 
+struct PrefillWs { float* stats; float* pooled; int64_t pooled_pitch; size_t bytes; };
+PrefillWs carve_prefill_anchor(const Shape& s, int64_t S, int T, void* ws) {
+    Carver c(ws);
+    PrefillWs r;
+    const int64_t n_tiles = (S + T - 1) / T;
+    r.pooled_pitch = round_up_i((int64_t)T * n_tiles * (n_tiles - 1) / 2 + 4, 4);
+    r.stats = c.take<float>((size_t)s.Hq * S * 2);
+    r.pooled = c.take<float>((size_t)s.Hkv * r.pooled_pitch);
+    r.bytes = c.used;
+    return r;
+}
+
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
 // ---- optional per-kernel timing (measurement aid, off by default) -----------------
 // When enabled every kernel launch is bracketed by two hipEvents on the call's stream.
 // Events are created on demand and kept until profiling is disabled; with profiling off
 // the library creates nothing.
-enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP2,
+enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
                 K_PF_TOPK, K_PF_SPARSE, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
-    "prefill_sweep1", "prefill_sweep2", "prefill_topk", "prefill_sparse"};
+    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
@@ -222,8 +234,12 @@ size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max
     const bool prefill = op == KASCADE_OP_PREFILL_ANCHOR || op == KASCADE_OP_PREFILL_REUSE;
     if (check_desc(desc, prefill) != KASCADE_OK || max_seqlen <= 0 || k_or_idx_total < 0) return 0;
     const Shape s = make_shape(desc);
-    (void)q_tile_tokens;
     switch (op) {
+        case KASCADE_OP_PREFILL_ANCHOR:
+            if (q_tile_tokens <= 0) return 0;
+            return carve_prefill_anchor(s, max_seqlen, q_tile_tokens, nullptr).bytes;
+        case KASCADE_OP_PREFILL_REUSE:
+            return 0;
         case KASCADE_OP_DECODE_REUSE:
             return carve_decode_reuse(s, plan_gather(s, k_or_idx_total), nullptr).bytes;
         case KASCADE_OP_DECODE_ANCHOR:
@@ -316,23 +332,86 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
     return st;
 }
 
+}  // extern "C"
+
+namespace {
+
+int check_prefill(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
+                  int32_t T, const int32_t* k_per_tile, const int64_t* idx_offsets, int64_t idx_total,
+                  const void* idx, const void* out) {
+    int st = check_desc(desc, true);
+    if (st != KASCADE_OK) return st;
+    if (!q || !k || !v || !k_per_tile || !idx_offsets || !out) return KASCADE_INVALID_ARG;
+    if (seqlen <= 0 || T <= 0 || idx_total < 0) return KASCADE_INVALID_ARG;
+    if (idx_total > 0 && !idx) return KASCADE_INVALID_ARG;
+    if (desc->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    // a query tile is 128 (token, head) rows: T tokens times the G heads of a key head
+    if ((int64_t)T * (desc->n_q_heads / desc->n_kv_heads) != 128) return KASCADE_UNSUPPORTED;
+    if ((desc->o_stride[1] * 2) % 8 || (desc->o_stride[2] * 2) % 8) return KASCADE_MISALIGNED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || (reinterpret_cast<uintptr_t>(out) & 7u)) return KASCADE_MISALIGNED;
+    return KASCADE_OK;
+}
+
+PrefillArgs prefill_args(const void* q, const void* k, const void* v, void* out, int32_t seqlen, int32_t T,
+                         const int32_t* k_per_tile, const int64_t* idx_offsets, int64_t idx_total) {
+    PrefillArgs a = {};
+    a.q = q; a.k = k; a.v = v; a.out = out; a.seqlen = seqlen; a.tile_tokens = T;
+    a.n_tiles = (seqlen + T - 1) / T;
+    a.k_per_tile = k_per_tile; a.idx_offsets = idx_offsets; a.idx_total = idx_total;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
 int kascade_prefill_anchor(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
                            int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
                            int64_t idx_total, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
                            size_t workspace_bytes, void* hip_stream) {
-    (void)desc; (void)q; (void)k; (void)v; (void)seqlen; (void)q_tile_tokens; (void)k_per_tile; (void)idx_offsets;
-    (void)idx_total; (void)out_mode; (void)idx_out; (void)out; (void)workspace; (void)workspace_bytes; (void)hip_stream;
-    return KASCADE_UNSUPPORTED;
+    int st = check_prefill(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, idx_out, out);
+    if (st != KASCADE_OK) return st;
+    if (out_mode != KASCADE_OUT_DENSE && out_mode != KASCADE_OUT_SPARSE) return KASCADE_INVALID_ARG;
+    const Shape s = make_shape(desc);
+    const PrefillWs ws = carve_prefill_anchor(s, seqlen, q_tile_tokens, workspace);
+    if (!workspace || workspace_bytes < ws.bytes) return KASCADE_WORKSPACE_TOO_SMALL;
+    if (!aligned16(workspace)) return KASCADE_MISALIGNED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool dense = out_mode == KASCADE_OUT_DENSE;
+
+    PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
+    a.stats = ws.stats; a.pooled = ws.pooled; a.pooled_pitch = ws.pooled_pitch;
+    // pass 1: causal scores -> row statistics (layer 0: plus the dense output)
+    st = timed(dense ? K_PF_SWEEP1_V : K_PF_SWEEP1, stream, [&] { return launch_prefill_attend(s, a, false, dense, stream); });
+    if (st != KASCADE_OK) return st;
+    // pass 2: recompute scores over the prefix, normalise, pool the tile's rows
+    st = timed(K_PF_SWEEP2, stream, [&] { return launch_prefill_pool(s, a, stream); });
+    if (st != KASCADE_OK) return st;
+    // pass 3: Top-k per (tile, key head)
+    TopkArgs t = {};
+    t.scores = ws.pooled; t.idx_out = idx_out; t.k_per_tile = k_per_tile; t.idx_offsets = idx_offsets;
+    t.idx_total = idx_total; t.pooled_pitch = ws.pooled_pitch; t.tile_tokens = q_tile_tokens; t.n_tiles = a.n_tiles;
+    st = timed(K_PF_TOPK, stream, [&] { return launch_topk_prefill(s, t, stream); });
+    if (st != KASCADE_OK || dense) return st;
+    // pass 4: sparse attention over the fresh sets
+    a.stats = nullptr; a.idx = idx_out; a.head_map = nullptr; a.n_src_heads = s.Hkv;
+    return timed(K_PF_SPARSE, stream, [&] { return launch_prefill_attend(s, a, true, true, stream); });
 }
 
 int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
                           int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
                           int64_t idx_total, const int32_t* idx_in, int32_t n_anchor_heads, const int32_t* head_map,
                           void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)desc; (void)q; (void)k; (void)v; (void)seqlen; (void)q_tile_tokens; (void)k_per_tile; (void)idx_offsets;
-    (void)idx_total; (void)idx_in; (void)n_anchor_heads; (void)head_map; (void)out; (void)workspace;
-    (void)workspace_bytes; (void)hip_stream;
-    return KASCADE_UNSUPPORTED;
+    (void)workspace; (void)workspace_bytes;   // this op needs no scratch memory
+    int st = check_prefill(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, idx_in, out);
+    if (st != KASCADE_OK) return st;
+    if (n_anchor_heads <= 0) return KASCADE_INVALID_ARG;
+    if (!head_map && n_anchor_heads != desc->n_kv_heads) return KASCADE_INVALID_ARG;
+    const Shape s = make_shape(desc);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
+    a.idx = idx_in; a.head_map = head_map; a.n_src_heads = n_anchor_heads;
+    return timed(K_PF_SPARSE, stream, [&] { return launch_prefill_attend(s, a, true, true, stream); });
 }
 
 }  // extern "C"

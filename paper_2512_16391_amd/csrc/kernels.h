@@ -93,6 +93,27 @@ struct TopkArgs {
     int32_t n_tiles;
 };
 hipError_t launch_topk_decode(const Shape& s, const TopkArgs& a, hipStream_t st);
+
+// ---- prefill -----------------------------------------------------------------------
+struct PrefillArgs {
+    const void* q;                // [S, Hq, D] per q_stride
+    const void* k;                // [Hkv, S, D] per kv_stride
+    const void* v;
+    void* out;                    // [S, Hq, D] per o_stride (attend kernels with V)
+    float* stats;                 // [Hq, S, 2] row (max, sum) in base-2 scaled units; null = not written
+    float* pooled;                // pool kernel: [Hkv, pooled_pitch], tile t at T*t*(t-1)/2
+    int64_t pooled_pitch;
+    const int32_t* idx;           // sparse: [n_src_heads, idx_total]
+    const int64_t* idx_offsets;   // [n_tiles + 1]
+    const int32_t* k_per_tile;    // [n_tiles]
+    const int32_t* head_map;      // [Hkv] or null
+    int64_t idx_total;
+    int32_t n_src_heads;
+    int32_t seqlen, tile_tokens, n_tiles;
+};
+// sparse = false: all keys up to the diagonal (causal); with_v = false computes statistics only
+hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st);
+hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t st);
 hipError_t launch_topk_prefill(const Shape& s, const TopkArgs& a, hipStream_t st);
 
 }  // namespace kascade

@@ -1,0 +1,407 @@
+// Prefill kernels of the Kascade hot path (gfx950, bf16 MFMA 32x32x16, fp32 softmax).
+//
+// A query tile is T consecutive tokens times the G query heads of one key head = 128 rows
+// (paper Sec. 3.4).  One workgroup of four waves owns one (tile, key head); wave w owns rows
+// 32w..32w+31, row rho = g*T + token_in_tile.  Keys are processed in blocks of 64 staged
+// through LDS: K row-major, V transposed, both XOR-swizzled so that the 16-byte MFMA operand
+// reads are bank-conflict free.
+//
+//  prefill_attend_kernel  flash-style attention over a key list:
+//      dense  - all keys up to the diagonal, causal (anchor pass 1, Sec. 3.6): emits the row
+//               statistics (max, sum) and, for layer 0, the dense output;
+//      sparse - the tile's Top-k index list plus its diagonal block (reuse layers / pass 4).
+//      Scores are computed transposed (S^T = K Q^T) so that a lane owns one query row and the
+//      row max / row sum are in-lane reductions; O^T = V^T P^T accumulates in the same layout.
+//  prefill_pool_kernel    anchor pass 2: recomputes S = Q K^T over the strict prefix,
+//      normalises with the known statistics and sums the tile's 128 rows per key
+//      (post-softmax pooling, Sec. 3.4).  Here a lane owns one key column, so the row sum is
+//      again in-lane.
+#include <limits.h>
+
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace kascade {
+
+namespace {
+
+constexpr int kPB = 256;          // threads per workgroup
+constexpr int kPW = kPB / kWave;  // waves
+constexpr int BK = 64;            // keys per block
+constexpr int kTileRows = 128;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+// MFMA 32x32x16 output: lane (col = lane%32, half = lane/32), register r holds row
+// (r/4)*8 + half*4 + r%4.  perm_key maps an operand row/col index rho to the key slot that
+// makes register r of half h hold key slot (r/8)*16 + h*8 + r%8, i.e. eight consecutive keys
+// per group of eight registers - the order the P^T operand of the second MFMA needs.
+__device__ __forceinline__ int perm_key(int rho) {
+    const int r = (rho >> 3) * 4 + (rho & 3);
+    const int h = (rho >> 2) & 1;
+    return (r >> 3) * 16 + h * 8 + (r & 7);
+}
+
+// K tile: [BK][D] bf16, 16-byte chunks XOR-swizzled by key bits {0,1,3}
+template <int D>
+__device__ __forceinline__ int k_off(int key, int chunk) {
+    const int f = (key & 3) | ((key >> 1) & 4);
+    return key * (D * 2) + ((chunk ^ f) << 4);
+}
+// V^T tile: [D][BK] bf16 (128-byte rows), 16-byte key groups XOR-swizzled by d
+__device__ __forceinline__ int vt_off(int d, int key) {
+    return d * (BK * 2) + ((((key >> 3) ^ (d & 7) ^ ((d >> 3) & 7)) & 7) << 4) + ((key & 7) << 1);
+}
+
+__device__ __forceinline__ bf16x8_t lds_frag(const unsigned char* p) {
+    return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p));
+}
+
+__device__ __forceinline__ bf16x8_t pack_p(const f32x16_t& s, int base) {
+    bf16x8_t r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (__bf16)s[base + e];
+    return r;
+}
+
+// Global -> register -> LDS staging of one block of 64 key slots.
+template <int D, bool WITH_V>
+struct BlockLoader {
+    static constexpr int PPR = D / 8;          // 16-byte pieces per row
+    static constexpr int RPP = kPB / PPR;      // rows per pass
+    static constexpr int PASSES = BK / RPP;
+    uint4 kr[PASSES];
+    uint4 vr[WITH_V ? PASSES : 1];
+    int pos[PASSES];
+
+    template <typename PosFn>
+    __device__ __forceinline__ void issue(const bf16_t* Kb, const bf16_t* Vb, int64_t row_stride, PosFn&& fn) {
+        const int piece = threadIdx.x % PPR, r0 = threadIdx.x / PPR;
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const int p = fn(i * RPP + r0);   // key position or -1
+            pos[i] = p;
+            const int64_t row = p < 0 ? 0 : p;
+            kr[i] = *reinterpret_cast<const uint4*>(Kb + row * row_stride + piece * 8);
+            if constexpr (WITH_V) vr[i] = *reinterpret_cast<const uint4*>(Vb + row * row_stride + piece * 8);
+        }
+    }
+    // returns true if this thread staged an invalid slot
+    __device__ __forceinline__ bool commit(unsigned char* smK, unsigned char* smVt, int* smPos) {
+        const int piece = threadIdx.x % PPR, r0 = threadIdx.x / PPR;
+        bool bad = false;
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const int slot = i * RPP + r0;
+            *reinterpret_cast<uint4*>(smK + k_off<D>(slot, piece)) = kr[i];
+            if constexpr (WITH_V) {
+                const uint32_t wv[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint16_t hv = (uint16_t)(wv[e >> 1] >> ((e & 1) * 16));
+                    *reinterpret_cast<uint16_t*>(smVt + vt_off(piece * 8 + e, slot)) = hv;
+                }
+            }
+            if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
+            bad |= pos[i] < 0;
+        }
+        return bad;
+    }
+};
+
+struct RowMap {   // which (token, head) a tile row is
+    int token, head;
+    bool ok;
+};
+__device__ __forceinline__ RowMap map_row(int rho, int t, int T, int hk, int G, int S) {
+    RowMap m;
+    m.token = t * T + rho % T;
+    m.head = hk * G + rho / T;
+    m.ok = m.token < S;
+    return m;
+}
+
+template <int D, bool SPARSE, bool WITH_V>
+__global__ __launch_bounds__(kPB) void prefill_attend_kernel(Shape s, PrefillArgs a) {
+    constexpr int KSTEPS = D / 16, DBLK = D / 32;
+    __shared__ __align__(16) unsigned char smK[BK * D * 2];
+    __shared__ __align__(16) unsigned char smVt[WITH_V ? D * BK * 2 : 16];
+    __shared__ int smPos[BK];
+    __shared__ int smFlag[2];
+
+    const int hk = blockIdx.x % s.Hkv;
+    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;   // long tiles first
+    const int T = a.tile_tokens, S = a.seqlen;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int q = lane & 31, h = lane >> 5;
+    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
+    const int q_token = rm.ok ? rm.token : INT_MAX - 1;
+    const float c = s.scale_log2;
+
+    const int prefix = t * T;
+    const int diag_end = (prefix + T < S) ? prefix + T : S;
+    int n_sparse = 0, nb_gather = 0, n_blocks;
+    const int32_t* idx = nullptr;
+    if constexpr (SPARSE) {
+        int kt = a.k_per_tile[t];
+        n_sparse = kt < 0 ? 0 : (kt > prefix ? prefix : kt);
+        nb_gather = (n_sparse + BK - 1) / BK;
+        n_blocks = nb_gather + (diag_end - prefix + BK - 1) / BK;
+        int src = a.head_map ? a.head_map[hk] : hk;
+        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+        idx = a.idx + (int64_t)src * a.idx_total + a.idx_offsets[t];
+    } else {
+        n_blocks = (diag_end + BK - 1) / BK;
+    }
+
+    const bf16_t* Kb = reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1];
+    const bf16_t* Vb = reinterpret_cast<const bf16_t*>(a.v) + hk * s.kv_stride[1];
+    const int64_t row_stride = s.kv_stride[2];
+
+    auto pos_of = [&](int kb, int slot) -> int {
+        if constexpr (SPARSE) {
+            if (kb < nb_gather) {
+                const int j = kb * BK + slot;
+                if (j >= n_sparse) return -1;
+                const int p = idx[j];
+                return (p >= 0 && p < prefix) ? p : -1;
+            }
+            const int p = prefix + (kb - nb_gather) * BK + slot;
+            return p < diag_end ? p : -1;
+        } else {
+            const int p = kb * BK + slot;
+            return p < diag_end ? p : -1;
+        }
+    };
+
+    // query fragments (B operand of S^T = K Q^T): row q of this wave, 8 elements per k-step
+    bf16x8_t qf[KSTEPS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16_t acc_o[WITH_V ? DBLK : 1];
+#pragma unroll
+    for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+
+    if (threadIdx.x < 2) smFlag[threadIdx.x] = 0;
+
+    BlockLoader<D, WITH_V> ld;
+    ld.issue(Kb, Vb, row_stride, [&](int slot) { return pos_of(0, slot); });
+
+    const int key0 = perm_key(q), key1 = 32 + key0;
+
+    for (int kb = 0; kb < n_blocks; ++kb) {
+        __syncthreads();   // previous block fully consumed
+        if (ld.commit(smK, smVt, smPos)) smFlag[kb & 1] = 1;
+        __syncthreads();
+        if (kb + 1 < n_blocks) ld.issue(Kb, Vb, row_stride, [&](int slot) { return pos_of(kb + 1, slot); });
+        if (threadIdx.x == 0) smFlag[(kb + 1) & 1] = 0;
+
+        // S^T block: rows = 64 keys (two MFMA tiles), cols = this wave's 32 queries
+        f32x16_t s0, s1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const bf16x8_t a0 = lds_frag(smK + k_off<D>(key0, kk * 2 + h));
+            const bf16x8_t a1 = lds_frag(smK + k_off<D>(key1, kk * 2 + h));
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[kk], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[kk], s1, 0, 0, 0);
+        }
+        // mask: causal inside / beyond the diagonal, and invalid slots
+        bool need_mask = smFlag[kb & 1] != 0;
+        if constexpr (SPARSE) need_mask |= kb >= nb_gather;
+        else need_mask |= (kb + 1) * BK > prefix;
+        if (need_mask) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int slot = (r >> 3) * 16 + h * 8 + (r & 7);
+                if (smPos[slot] > q_token) s0[r] = -INFINITY;
+                if (smPos[32 + slot] > q_token) s1[r] = -INFINITY;
+            }
+        }
+        // online softmax, base 2; this lane owns query row q (other half-wave holds the other keys)
+        float mx = s0[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
+        mx *= c;
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        float rs = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));
+            s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));
+            rs += s0[r] + s1[r];
+        }
+        rs += __shfl_xor(rs, 32);
+        l_run = fmaf(l_run, alpha, rs);
+        m_run = m_new;
+
+        if constexpr (WITH_V) {
+#pragma unroll
+            for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+            bf16x8_t pf[4];
+            pf[0] = pack_p(s0, 0); pf[1] = pack_p(s0, 8); pf[2] = pack_p(s1, 0); pf[3] = pack_p(s1, 8);
+#pragma unroll
+            for (int i = 0; i < DBLK; ++i) {
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const bf16x8_t va = lds_frag(smVt + vt_off(i * 32 + q, st * 16 + h * 8));
+                    acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[st], acc_o[i], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    if (!rm.ok) return;
+    if (a.stats && h == 0) {
+        float* st = a.stats + ((int64_t)rm.head * S + rm.token) * 2;
+        st[0] = m_run;
+        st[1] = l_run;
+    }
+    if constexpr (WITH_V) {
+        const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+        bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + (int64_t)rm.token * s.o_stride[1] + (int64_t)rm.head * s.o_stride[2];
+#pragma unroll
+        for (int i = 0; i < DBLK; ++i) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d0 = i * 32 + r4 * 8 + h * 4;
+                uint2 pk;
+                pk.x = pack_bf16(acc_o[i][r4 * 4 + 0] * inv, acc_o[i][r4 * 4 + 1] * inv);
+                pk.y = pack_bf16(acc_o[i][r4 * 4 + 2] * inv, acc_o[i][r4 * 4 + 3] * inv);
+                *reinterpret_cast<uint2*>(op + d0) = pk;
+            }
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kPB) void prefill_pool_kernel(Shape s, PrefillArgs a) {
+    constexpr int KSTEPS = D / 16;
+    __shared__ __align__(16) unsigned char smK[BK * D * 2];
+    __shared__ int smPos[BK];
+    __shared__ float smPart[kPW][BK];
+
+    const int hk = blockIdx.x % s.Hkv;
+    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
+    const int T = a.tile_tokens, S = a.seqlen;
+    const int prefix = t * T;
+    if (prefix == 0) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int q = lane & 31, h = lane >> 5;
+    const float c = s.scale_log2;
+    const int diag_end = (prefix + T < S) ? prefix + T : S;
+    const float inv_rows = 1.f / (float)((diag_end - prefix) * s.G);
+    const int n_blocks = (prefix + BK - 1) / BK;
+
+    const bf16_t* Kb = reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1];
+    const int64_t row_stride = s.kv_stride[2];
+
+    // A operand: query row q of this wave
+    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
+    bf16x8_t qf[KSTEPS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    // statistics of the 16 query rows whose scores land in this lane's registers
+    float m_r[16], inv_r[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const RowMap rr = map_row(w * 32 + (r >> 2) * 8 + h * 4 + (r & 3), t, T, hk, s.G, S);
+        m_r[r] = 0.f; inv_r[r] = 0.f;
+        if (rr.ok) {
+            const float* st = a.stats + ((int64_t)rr.head * S + rr.token) * 2;
+            m_r[r] = st[0];
+            inv_r[r] = inv_rows / st[1];
+        }
+    }
+
+    BlockLoader<D, false> ld;
+    auto pos_of = [&](int kb, int slot) -> int { const int p = kb * BK + slot; return p < prefix ? p : -1; };
+    ld.issue(Kb, nullptr, row_stride, [&](int slot) { return pos_of(0, slot); });
+    const int key0 = perm_key(q), key1 = 32 + key0;
+    float* dst = a.pooled + hk * a.pooled_pitch + (int64_t)T * t * (t - 1) / 2;
+
+    for (int kb = 0; kb < n_blocks; ++kb) {
+        __syncthreads();
+        ld.commit(smK, nullptr, smPos);
+        __syncthreads();
+        if (kb + 1 < n_blocks) ld.issue(Kb, nullptr, row_stride, [&](int slot) { return pos_of(kb + 1, slot); });
+
+        f32x16_t s0, s1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const bf16x8_t b0 = lds_frag(smK + k_off<D>(key0, kk * 2 + h));
+            const bf16x8_t b1 = lds_frag(smK + k_off<D>(key1, kk * 2 + h));
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b0, s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b1, s1, 0, 0, 0);
+        }
+        float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            c0 = fmaf(__builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_r[r])), inv_r[r], c0);
+            c1 = fmaf(__builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_r[r])), inv_r[r], c1);
+        }
+        c0 += __shfl_xor(c0, 32);
+        c1 += __shfl_xor(c1, 32);
+        if (h == 0) { smPart[w][key0] = c0; smPart[w][key1] = c1; }
+        __syncthreads();
+        if (threadIdx.x < BK) {
+            const int j = kb * BK + threadIdx.x;
+            if (j < prefix) dst[j] = (smPart[0][threadIdx.x] + smPart[1][threadIdx.x]) + (smPart[2][threadIdx.x] + smPart[3][threadIdx.x]);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
+    dim3 grid(a.n_tiles * s.Hkv), block(kPB);
+#define KASCADE_LAUNCH_ATTEND(DD)                                                                                      \
+    if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true>), grid, block, 0, st, s, a);                 \
+    else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true>), grid, block, 0, st, s, a);           \
+    else hipLaunchKernelGGL((prefill_attend_kernel<DD, false, false>), grid, block, 0, st, s, a);
+    if (s.D == 128) { KASCADE_LAUNCH_ATTEND(128) }
+    else if (s.D == 64) { KASCADE_LAUNCH_ATTEND(64) }
+    else return hipErrorInvalidValue;
+#undef KASCADE_LAUNCH_ATTEND
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t st) {
+    dim3 grid(a.n_tiles * s.Hkv), block(kPB);
+    if (s.D == 128) hipLaunchKernelGGL((prefill_pool_kernel<128>), grid, block, 0, st, s, a);
+    else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_kernel<64>), grid, block, 0, st, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace kascade

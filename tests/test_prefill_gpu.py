@@ -1,0 +1,181 @@
+"""GPU parity of the prefill entry points against the CPU oracle, tile by tile."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kascade_oracle as ko
+from paper_2512_16391_amd import binding, workloads
+from parity_utils import TOL_OUT, check_index_set, f64, max_abs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+BF16 = torch.bfloat16
+
+
+def dev_i32(x):
+    return torch.tensor(x, dtype=torch.int32, device=DEV)
+
+
+def dev_i64(x):
+    return torch.tensor(x, dtype=torch.int64, device=DEV)
+
+
+def random_prefill(seed, S, Hq, Hkv, d):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(S, Hq, d, generator=g).to(BF16)
+    k = torch.randn(Hkv, S, d, generator=g).to(BF16)
+    v = torch.randn(Hkv, S, d, generator=g).to(BF16)
+    return q, k, v
+
+
+def offsets(k_per_tile):
+    off = [0]
+    for kt in k_per_tile:
+        off.append(off[-1] + kt)
+    return off
+
+
+def run_anchor(q, k, v, T, k_per_tile, out_mode, tiles=None, where=""):
+    """Runs kascade_prefill_anchor and checks the listed tiles (all by default)."""
+    S, Hq, d = q.shape
+    Hkv = k.shape[0]
+    off = offsets(k_per_tile)
+    idx, out = binding.kascade_prefill_anchor(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(k_per_tile), dev_i64(off),
+                                              off[-1], out_mode=out_mode)
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    o = f64(out)
+    Q, Kp, Vp = f64(q), f64(k), f64(v)
+    scale = ko.default_scale(d)
+    n_tiles = len(k_per_tile)
+    swaps, worst = 0, 0.0
+    for t in (tiles if tiles is not None else range(n_tiles)):
+        kt = k_per_tile[t]
+        lo, hi = ko.tile_bounds(t, T, S)
+        sets = [idx[h, off[t]:off[t] + kt] for h in range(Hkv)]
+        if kt > 0:
+            idx_ref, a = ko.prefill_anchor_indices_tile(Q, Kp, t, T, scale, kt)
+            for h in range(Hkv):
+                swaps += check_index_set(sets[h], idx_ref[h], a[h], where=f"{where} tile {t} head {h}")
+        if out_mode == binding.KASCADE_OUT_DENSE:
+            ref = ko.prefill_dense_tile(Q, Kp, Vp, t, T, scale)
+        else:
+            ref = ko.prefill_sparse_tile(Q, Kp, Vp, t, T, sets, scale)
+        worst = max(worst, max_abs(o[lo:hi], ref))
+    print(f"  {where}: swaps {swaps}, max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[BF16]
+    return idx, out
+
+
+@pytest.mark.parametrize("S,Hq,Hkv,d,T", [
+    (300, 8, 2, 128, 32),      # ragged last tile (12 tokens), G = 4
+    (260, 2, 2, 64, 128),      # G = 1, tiles of 128 tokens
+    (200, 4, 2, 128, 64),      # G = 2
+    (100, 8, 1, 64, 16),       # G = 8, tiles of 16 tokens
+])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_prefill_anchor_small(S, Hq, Hkv, d, T, out_mode):
+    print(f"case prefill anchor S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} out_mode={out_mode}", flush=True)
+    q, k, v = random_prefill(S, S, Hq, Hkv, d)
+    kpt = workloads.prefill_budgets(S, T, 100, 24)
+    run_anchor(q, k, v, T, kpt, out_mode, where=f"S{S}")
+
+
+def test_prefill_anchor_tile_reduces_to_dense_when_k_covers_prefix():
+    # k_t = whole prefix for every tile: the sparse output must equal dense causal attention
+    S, Hq, Hkv, d, T = 256, 8, 2, 128, 32
+    q, k, v = random_prefill(7, S, Hq, Hkv, d)
+    kpt = [t * T for t in range(S // T)]
+    off = offsets(kpt)
+    idx, out = binding.kascade_prefill_anchor(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                              out_mode=binding.KASCADE_OUT_SPARSE)
+    _, dense = binding.kascade_prefill_anchor(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                              out_mode=binding.KASCADE_OUT_DENSE)
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    for t in range(S // T):
+        for h in range(Hkv):
+            np.testing.assert_array_equal(idx[h, off[t]:off[t + 1]], np.arange(t * T))
+    Q, Kp, Vp = f64(q), f64(k), f64(v)
+    for t in range(S // T):
+        ref = ko.prefill_dense_tile(Q, Kp, Vp, t, T, ko.default_scale(d))
+        assert max_abs(f64(out)[t * T:(t + 1) * T], ref) <= TOL_OUT[BF16]
+        assert max_abs(f64(dense)[t * T:(t + 1) * T], ref) <= TOL_OUT[BF16]
+
+
+def test_prefill_reuse_head_map_and_ignored_entries():
+    S, Hq, Hkv, d, T = 330, 16, 4, 128, 32
+    q, k, v = random_prefill(11, S, Hq, Hkv, d)
+    n_tiles = (S + T - 1) // T
+    rs = np.random.default_rng(12)
+    n_anchor = 2
+    hm = [1, 0, 0, 1]
+    kpt = [min(t * T, 40) for t in range(n_tiles)]
+    off = offsets(kpt)
+    idx = np.full((n_anchor, max(off[-1], 1)), -1, dtype=np.int32)
+    sets = {}
+    for t in range(n_tiles):
+        sets[t] = []
+        for h in range(n_anchor):
+            kt = kpt[t]
+            if kt == 0:
+                sets[t].append(np.zeros(0, np.int64))
+                continue
+            good = rs.permutation(rs.choice(t * T, kt - 2 if kt > 2 else kt, replace=False))     # unordered
+            row = np.concatenate([good[:1], [-1, t * T + 5][: kt - good.size], good[1:]])           # 2 entries to ignore
+            idx[h, off[t]:off[t] + kt] = row
+            sets[t].append(good)
+    out = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                        torch.from_numpy(idx).to(DEV), head_map=dev_i32(hm))
+    torch.cuda.synchronize()
+    Q, Kp, Vp = f64(q), f64(k), f64(v)
+    o = f64(out)
+    worst = 0.0
+    for t in range(n_tiles):
+        lo, hi = ko.tile_bounds(t, T, S)
+        ref = ko.prefill_sparse_tile(Q, Kp, Vp, t, T, sets[t], ko.default_scale(d), head_map=hm)
+        worst = max(worst, max_abs(o[lo:hi], ref))
+    print(f"  reuse max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[BF16]
+    # deterministic
+    out2 = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                         torch.from_numpy(idx).to(DEV), head_map=dev_i32(hm))
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+def test_prefill_config4_shape_reduced_length():
+    """Config-4 recipe (32/8 heads, d 128, T = 32, 10 % with a floor of 256, planted hitters) at
+    S = 4096: anchor then a reuse layer, every tile against the oracle."""
+    print("case prefill cfg4 reduced", flush=True)
+    wl = workloads.config4(device="cpu", n_layers=2, S=4096)
+    a, r = wl.layers
+    tiles = list(range(0, wl.n_tiles, 5)) + [7, 8, 9, 79, 80, 81, wl.n_tiles - 1]    # includes the k_min boundary
+    idx, _ = run_anchor(a.q, a.k, a.v, wl.T, wl.k_per_tile, binding.KASCADE_OUT_SPARSE, tiles=sorted(set(tiles)),
+                        where="cfg4-S4096 anchor")
+    off = wl.idx_offsets
+    out = binding.kascade_prefill_reuse(r.q.to(DEV), r.k.to(DEV), r.v.to(DEV), wl.T, dev_i32(wl.k_per_tile),
+                                        dev_i64(off), off[-1], torch.from_numpy(idx).to(DEV))
+    torch.cuda.synchronize()
+    Q, Kp, Vp = f64(r.q), f64(r.k), f64(r.v)
+    o = f64(out)
+    worst = 0.0
+    for t in sorted(set(tiles)):
+        sets = [idx[h, off[t]:off[t + 1]] for h in range(wl.Hkv)]
+        ref = ko.prefill_sparse_tile(Q, Kp, Vp, t, wl.T, sets, ko.default_scale(wl.d))
+        worst = max(worst, max_abs(o[t * wl.T:(t + 1) * wl.T], ref))
+    print(f"  cfg4-S4096 reuse max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[BF16]
+
+
+def test_prefill_rejects_unsupported():
+    q, k, v = random_prefill(1, 64, 8, 2, 128)
+    kpt, off = [0, 0], [0, 0, 0]
+    with pytest.raises(binding.KascadeError) as e:      # T * G must be 128
+        binding.kascade_prefill_anchor(q.to(DEV), k.to(DEV), v.to(DEV), 16, dev_i32([0] * 4), dev_i64([0] * 5), 0)
+    assert e.value.status == -2
+    with pytest.raises(binding.KascadeError) as e:      # fp32 prefill is not built
+        binding.kascade_prefill_anchor(q.float().to(DEV), k.float().to(DEV), v.float().to(DEV), 32, dev_i32(kpt),
+                                       dev_i64(off), 0)
+    assert e.value.status == -2
