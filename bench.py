@@ -79,11 +79,7 @@ def main():
     # ---------------- prefill workload ----------------
     prefill = None
     if not args.no_prefill:
-        try:
-            from bench_prefill import PrefillBench  # built with the prefill kernels
-            prefill = PrefillBench(dev)
-        except ImportError:
-            prefill = None
+        prefill = PrefillBench(dev)
 
     def step():
         decode_step()
@@ -181,6 +177,67 @@ def main():
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_seqs)
     print(json.dumps(rec), flush=True)
+
+
+class PrefillBench:
+    """Config 4: batch 1, 32768 tokens causal, 32/8 heads, d 128, bf16, tiles of 32 tokens x 4
+    heads, k_t = 10 % of the prefix (min 256); one anchor layer (sparse output) + three reuse
+    layers, each with its own Q/K/V."""
+
+    def __init__(self, dev, S=32768, T=32):
+        import torch
+        from paper_2512_16391_amd import binding, workloads
+        self.binding = binding
+        wl = workloads.config4(device=dev, S=S, T=T)
+        self.wl = wl
+        self.name = wl.name + " k_t=10% (min 256), 1 anchor + 3 reuse layers"
+        off = wl.idx_offsets
+        self.idx_total = off[-1]
+        self.kpt = torch.tensor(wl.k_per_tile, dtype=torch.int32, device=dev)
+        self.off = torch.tensor(off, dtype=torch.int64, device=dev)
+        self.idx = torch.empty(wl.Hkv, self.idx_total, dtype=torch.int32, device=dev)
+        self.outs = [torch.empty_like(l.q) for l in wl.layers]
+        desc = binding.prefill_desc(wl.layers[0].q, wl.layers[0].k)
+        need = binding.kascade_workspace_bytes(binding.OP_PREFILL_ANCHOR, desc, S, self.idx_total, T)
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        # MFMA-class FLOP the method needs (each causal QK^T sweep = U)
+        d, Hq = wl.d, wl.Hq
+        self.U = float(S) * S * d * Hq
+        self.sparse_flop = 4.0 * d * Hq * sum(min(T, S - t * T) * (kt + (min(T, S - t * T) + 1) / 2.0)
+                                              for t, kt in enumerate(wl.k_per_tile))
+
+    def step(self):
+        b, wl = self.binding, self.wl
+        a = wl.layers[0]
+        b.kascade_prefill_anchor(a.q, a.k, a.v, wl.T, self.kpt, self.off, self.idx_total, b.KASCADE_OUT_SPARSE,
+                                 self.idx, self.outs[0], self.ws)
+        for i in range(1, len(wl.layers)):
+            r = wl.layers[i]
+            b.kascade_prefill_reuse(r.q, r.k, r.v, wl.T, self.kpt, self.off, self.idx_total, self.idx, None, None,
+                                    self.outs[i], self.ws)
+
+    def report(self, prof, peak_tflops):
+        def us(name):
+            return prof[name][0] * 1e3 / prof[name][1] if name in prof else None
+        t1, t2, tk, ts = us("prefill_sweep1"), us("prefill_sweep2"), us("prefill_topk"), us("prefill_sparse")
+        anchor_us = t1 + t2 + tk + ts
+        anchor_flop = 2 * self.U + self.sparse_flop
+        tf = lambda flop, t_us: flop / (t_us * 1e-6) / 1e12
+        sweep_tf = tf(self.U, max(t1, t2))
+        return {
+            "prefill_anchor_ms": round(anchor_us / 1e3, 3), "prefill_reuse_ms": round(ts / 1e3, 3),
+            "prefill_anchor_tflops": round(tf(anchor_flop, anchor_us), 1),
+            "prefill_reuse_tflops": round(tf(self.sparse_flop, ts), 1),
+            "prefill_tokens_per_s": round(self.wl.S / ((anchor_us + 3 * ts) * 1e-6), 1),
+            "roofline_prefill": {"kernel": "prefill_sweep2" if t2 >= t1 else "prefill_sweep1", "bound": "mfma",
+                                 "achieved": round(sweep_tf, 1), "peak": peak_tflops, "unit": "TFLOP/s",
+                                 "frac": round(sweep_tf / peak_tflops, 4), "traffic": None,
+                                 "algorithmic_flop": self.U, "avg_kernel_us": round(max(t1, t2), 1)},
+            "roofline_prefill_anchor": {"bound": "mfma", "achieved": round(tf(anchor_flop, anchor_us), 1),
+                                        "peak": peak_tflops, "unit": "TFLOP/s",
+                                        "frac": round(tf(anchor_flop, anchor_us) / peak_tflops, 4),
+                                        "algorithmic_flop": anchor_flop, "out_mode": "sparse"},
+        }
 
 
 def _blas_threads():
