@@ -33,6 +33,7 @@ constexpr int kTileRows = 128;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // one 16-byte piece in flight
 
 // MFMA 32x32x16 output: lane (col = lane%32, half = lane/32), register r holds row
 // (r/4)*8 + half*4 + r%4.  perm_key maps an operand row/col index rho to the key slot that
@@ -66,50 +67,55 @@ __device__ __forceinline__ bf16x8_t pack_p(const f32x16_t& s, int base) {
     return r;
 }
 
-// Global -> register -> LDS staging of one block of 64 key slots.
-template <int D, bool WITH_V>
-struct BlockLoader {
+// Global -> register -> LDS staging of one block of 64 key slots.  A row of D bf16 is D/8
+// 16-byte pieces; thread tid owns piece tid % PPR of rows tid / PPR + i * RPP.
+template <int D> struct Stage {
     static constexpr int PPR = D / 8;          // 16-byte pieces per row
     static constexpr int RPP = kPB / PPR;      // rows per pass
     static constexpr int PASSES = BK / RPP;
-    uint4 kr[PASSES];
-    uint4 vr[WITH_V ? PASSES : 1];
-    int pos[PASSES];
-
-    template <typename PosFn>
-    __device__ __forceinline__ void issue(const bf16_t* Kb, const bf16_t* Vb, int64_t row_stride, PosFn&& fn) {
-        const int piece = threadIdx.x % PPR, r0 = threadIdx.x / PPR;
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const int p = fn(i * RPP + r0);   // key position or -1
-            pos[i] = p;
-            const int64_t row = p < 0 ? 0 : p;
-            kr[i] = *reinterpret_cast<const uint4*>(Kb + row * row_stride + piece * 8);
-            if constexpr (WITH_V) vr[i] = *reinterpret_cast<const uint4*>(Vb + row * row_stride + piece * 8);
-        }
-    }
-    // returns true if this thread staged an invalid slot
-    __device__ __forceinline__ bool commit(unsigned char* smK, unsigned char* smVt, int* smPos) {
-        const int piece = threadIdx.x % PPR, r0 = threadIdx.x / PPR;
-        bool bad = false;
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const int slot = i * RPP + r0;
-            *reinterpret_cast<uint4*>(smK + k_off<D>(slot, piece)) = kr[i];
-            if constexpr (WITH_V) {
-                const uint32_t wv[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint16_t hv = (uint16_t)(wv[e >> 1] >> ((e & 1) * 16));
-                    *reinterpret_cast<uint16_t*>(smVt + vt_off(piece * 8 + e, slot)) = hv;
-                }
-            }
-            if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
-            bad |= pos[i] < 0;
-        }
-        return bad;
-    }
 };
+
+template <int D, bool WITH_V>
+__device__ __forceinline__ void stage_issue(u32x4_t (&kr)[Stage<D>::PASSES], u32x4_t (&vr)[Stage<D>::PASSES],
+                                            const int (&pos)[Stage<D>::PASSES], const bf16_t* Kb, const bf16_t* Vb,
+                                            int64_t row_stride) {
+    const int piece = threadIdx.x % Stage<D>::PPR;
+#pragma unroll
+    for (int i = 0; i < Stage<D>::PASSES; ++i) {
+        const int64_t row = pos[i] < 0 ? 0 : pos[i];
+        kr[i] = *reinterpret_cast<const u32x4_t*>(Kb + row * row_stride + piece * 8);
+        if constexpr (WITH_V) vr[i] = *reinterpret_cast<const u32x4_t*>(Vb + row * row_stride + piece * 8);
+    }
+}
+
+// returns true if this thread staged an invalid slot
+template <int D, bool WITH_V>
+__device__ __forceinline__ bool stage_commit(const u32x4_t (&kr)[Stage<D>::PASSES], const u32x4_t (&vr)[Stage<D>::PASSES],
+                                             const int (&pos)[Stage<D>::PASSES], unsigned char* smK,
+                                             unsigned char* smVt, int* smPos) {
+    const int piece = threadIdx.x % Stage<D>::PPR, r0 = threadIdx.x / Stage<D>::PPR;
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < Stage<D>::PASSES; ++i) {
+        const int slot = i * Stage<D>::RPP + r0;
+        *reinterpret_cast<u32x4_t*>(smK + k_off<D>(slot, piece)) = kr[i];
+        if constexpr (WITH_V) {
+            const u32x4_t v = vr[i];
+            const int d0 = piece * 8;
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 0, slot)) = (uint16_t)(v.x);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 1, slot)) = (uint16_t)(v.x >> 16);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 2, slot)) = (uint16_t)(v.y);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 3, slot)) = (uint16_t)(v.y >> 16);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 4, slot)) = (uint16_t)(v.z);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 5, slot)) = (uint16_t)(v.z >> 16);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 6, slot)) = (uint16_t)(v.w);
+            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 7, slot)) = (uint16_t)(v.w >> 16);
+        }
+        if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
+        bad |= pos[i] < 0;
+    }
+    return bad;
+}
 
 struct RowMap {   // which (token, head) a tile row is
     int token, head;
@@ -160,21 +166,23 @@ __global__ __launch_bounds__(kPB) void prefill_attend_kernel(Shape s, PrefillArg
     const bf16_t* Vb = reinterpret_cast<const bf16_t*>(a.v) + hk * s.kv_stride[1];
     const int64_t row_stride = s.kv_stride[2];
 
-    auto pos_of = [&](int kb, int slot) -> int {
-        if constexpr (SPARSE) {
-            if (kb < nb_gather) {
-                const int j = kb * BK + slot;
-                if (j >= n_sparse) return -1;
-                const int p = idx[j];
-                return (p >= 0 && p < prefix) ? p : -1;
-            }
-            const int p = prefix + (kb - nb_gather) * BK + slot;
-            return p < diag_end ? p : -1;
-        } else {
-            const int p = kb * BK + slot;
-            return p < diag_end ? p : -1;
-        }
-    };
+    constexpr int PASSES = Stage<D>::PASSES;
+    const int slot0 = threadIdx.x / Stage<D>::PPR;
+    // key position of this thread's staging slots in block kb (-1 = no key)
+#define KASCADE_BLOCK_POS(kb_, pos_)                                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                                  \
+        const int slot_ = i_ * Stage<D>::RPP + slot0;                                        \
+        int p_;                                                                              \
+        if (SPARSE && (kb_) < nb_gather) {                                                   \
+            const int j_ = (kb_) * BK + slot_;                                               \
+            p_ = j_ < n_sparse ? idx[j_] : -1;                                               \
+            if (p_ >= prefix) p_ = -1;                                                       \
+        } else {                                                                             \
+            p_ = (SPARSE ? prefix + ((kb_) - nb_gather) * BK : (kb_) * BK) + slot_;          \
+            if (p_ >= diag_end) p_ = -1;                                                     \
+        }                                                                                    \
+        pos_[i_] = p_;                                                                       \
+    }
 
     // query fragments (B operand of S^T = K Q^T): row q of this wave, 8 elements per k-step
     bf16x8_t qf[KSTEPS];
@@ -197,16 +205,21 @@ __global__ __launch_bounds__(kPB) void prefill_attend_kernel(Shape s, PrefillArg
 
     if (threadIdx.x < 2) smFlag[threadIdx.x] = 0;
 
-    BlockLoader<D, WITH_V> ld;
-    ld.issue(Kb, Vb, row_stride, [&](int slot) { return pos_of(0, slot); });
+    u32x4_t kr[PASSES], vr[PASSES];
+    int pos[PASSES];
+    KASCADE_BLOCK_POS(0, pos)
+    stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
 
     const int key0 = perm_key(q), key1 = 32 + key0;
 
     for (int kb = 0; kb < n_blocks; ++kb) {
         __syncthreads();   // previous block fully consumed
-        if (ld.commit(smK, smVt, smPos)) smFlag[kb & 1] = 1;
+        if (stage_commit<D, WITH_V>(kr, vr, pos, smK, smVt, smPos)) smFlag[kb & 1] = 1;
         __syncthreads();
-        if (kb + 1 < n_blocks) ld.issue(Kb, Vb, row_stride, [&](int slot) { return pos_of(kb + 1, slot); });
+        if (kb + 1 < n_blocks) {
+            KASCADE_BLOCK_POS(kb + 1, pos)
+            stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
+        }
         if (threadIdx.x == 0) smFlag[(kb + 1) & 1] = 0;
 
         // S^T block: rows = 64 keys (two MFMA tiles), cols = this wave's 32 queries
@@ -272,6 +285,7 @@ __global__ __launch_bounds__(kPB) void prefill_attend_kernel(Shape s, PrefillArg
         }
     }
 
+#undef KASCADE_BLOCK_POS
     if (!rm.ok) return;
     if (a.stats && h == 0) {
         float* st = a.stats + ((int64_t)rm.head * S + rm.token) * 2;
@@ -342,17 +356,25 @@ __global__ __launch_bounds__(kPB) void prefill_pool_kernel(Shape s, PrefillArgs 
         }
     }
 
-    BlockLoader<D, false> ld;
-    auto pos_of = [&](int kb, int slot) -> int { const int p = kb * BK + slot; return p < prefix ? p : -1; };
-    ld.issue(Kb, nullptr, row_stride, [&](int slot) { return pos_of(0, slot); });
+    constexpr int PASSES = Stage<D>::PASSES;
+    const int slot0 = threadIdx.x / Stage<D>::PPR;
+    u32x4_t kr[PASSES], vr[PASSES];
+    int pos[PASSES];
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) { const int p = i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
+    stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
     const int key0 = perm_key(q), key1 = 32 + key0;
     float* dst = a.pooled + hk * a.pooled_pitch + (int64_t)T * t * (t - 1) / 2;
 
     for (int kb = 0; kb < n_blocks; ++kb) {
         __syncthreads();
-        ld.commit(smK, nullptr, smPos);
+        stage_commit<D, false>(kr, vr, pos, smK, nullptr, smPos);
         __syncthreads();
-        if (kb + 1 < n_blocks) ld.issue(Kb, nullptr, row_stride, [&](int slot) { return pos_of(kb + 1, slot); });
+        if (kb + 1 < n_blocks) {
+#pragma unroll
+            for (int i = 0; i < PASSES; ++i) { const int p = (kb + 1) * BK + i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
+            stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
+        }
 
         f32x16_t s0, s1;
 #pragma unroll
