@@ -15,6 +15,8 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
     "-ffp-contract=fast",
+    # keep MFMA accumulators in VGPRs: the softmax reads them right away, AGPR copies cost VALU slots
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

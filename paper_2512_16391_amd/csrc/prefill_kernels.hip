@@ -75,16 +75,17 @@ template <int D> struct Stage {
     static constexpr int PASSES = BK / RPP;
 };
 
+// Kb / Vb: base of this key head (uniform); offsets are 32-bit byte offsets (a head's rows span < 4 GiB)
 template <int D, bool WITH_V>
 __device__ __forceinline__ void stage_issue(u32x4_t (&kr)[Stage<D>::PASSES], u32x4_t (&vr)[Stage<D>::PASSES],
                                             const int (&pos)[Stage<D>::PASSES], const bf16_t* Kb, const bf16_t* Vb,
-                                            int64_t row_stride) {
-    const int piece = threadIdx.x % Stage<D>::PPR;
+                                            uint32_t row_bytes) {
+    const uint32_t piece_off = (threadIdx.x % Stage<D>::PPR) * 16;
 #pragma unroll
     for (int i = 0; i < Stage<D>::PASSES; ++i) {
-        const int64_t row = pos[i] < 0 ? 0 : pos[i];
-        kr[i] = *reinterpret_cast<const u32x4_t*>(Kb + row * row_stride + piece * 8);
-        if constexpr (WITH_V) vr[i] = *reinterpret_cast<const u32x4_t*>(Vb + row * row_stride + piece * 8);
+        const uint32_t off = (uint32_t)(pos[i] < 0 ? 0 : pos[i]) * row_bytes + piece_off;
+        kr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Kb) + off);
+        if constexpr (WITH_V) vr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Vb) + off);
     }
 }
 
@@ -130,7 +131,7 @@ __device__ __forceinline__ RowMap map_row(int rho, int t, int T, int hk, int G, 
 }
 
 template <int D, bool SPARSE, bool WITH_V>
-__global__ __launch_bounds__(kPB) void prefill_attend_kernel(Shape s, PrefillArgs a) {
+__global__ __launch_bounds__(kPB, 2) void prefill_attend_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     __shared__ __align__(16) unsigned char smK[BK * D * 2];
     __shared__ __align__(16) unsigned char smVt[WITH_V ? D * BK * 2 : 16];
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(kPB) void prefill_attend_kernel(Shape s, PrefillArg
 
     const bf16_t* Kb = reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1];
     const bf16_t* Vb = reinterpret_cast<const bf16_t*>(a.v) + hk * s.kv_stride[1];
-    const int64_t row_stride = s.kv_stride[2];
+    const uint32_t row_stride = (uint32_t)s.kv_stride[2] * 2u;   // bytes
 
     constexpr int PASSES = Stage<D>::PASSES;
     const int slot0 = threadIdx.x / Stage<D>::PPR;
@@ -329,7 +330,7 @@ __global__ __launch_bounds__(kPB) void prefill_pool_kernel(Shape s, PrefillArgs 
     const int n_blocks = (prefix + BK - 1) / BK;
 
     const bf16_t* Kb = reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1];
-    const int64_t row_stride = s.kv_stride[2];
+    const uint32_t row_stride = (uint32_t)s.kv_stride[2] * 2u;   // bytes
 
     // A operand: query row q of this wave
     const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
