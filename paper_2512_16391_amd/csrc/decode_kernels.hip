@@ -24,6 +24,80 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 
+// Workgroup-level merge of NS online-softmax streams (one per lane group) through LDS, then
+// either the final output (single chunk) or this chunk's partial (max, sum, acc) triple.
+template <typename T, int D, int G, int NS, int EPL, bool WITH_V>
+__device__ __forceinline__ void merge_streams(const Shape& s, const DecodeRowsArgs& a, int n_chunks, int chunk_id, int b,
+                                              int hk, int sid, int c, const float (&m)[G], const float (&l)[G],
+                                              const float (&acc)[WITH_V ? G : 1][EPL]) {
+    constexpr int GB = (G > 4) ? 4 : G;     // heads merged per LDS round
+    __shared__ float sm_m[NS][G];
+    __shared__ float sm_l[NS][G];
+    __shared__ float sm_acc[WITH_V ? NS : 1][GB][WITH_V ? D : 1];
+    if (c == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) { sm_m[sid][g] = m[g]; sm_l[sid][g] = l[g]; }
+    }
+#pragma unroll
+    for (int gb = 0; gb < G; gb += GB) {
+        if constexpr (WITH_V) {
+            if (gb > 0) __syncthreads();
+#pragma unroll
+            for (int g = 0; g < GB; ++g)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) sm_acc[sid][g][c * EPL + e] = acc[gb + g][e];
+        }
+        __syncthreads();
+        constexpr int NE = WITH_V ? GB * D : GB;
+        for (int e = threadIdx.x; e < NE; e += kBlock) {
+            const int g = WITH_V ? e / D : e;
+            const int col = WITH_V ? e % D : 0;
+            float M = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < NS; ++t) M = fmaxf(M, sm_m[t][gb + g]);
+            const float Ms = (M == -INFINITY) ? 0.f : M;
+            float lsum = 0.f, val = 0.f;
+#pragma unroll
+            for (int t = 0; t < NS; ++t) {
+                const float wgt = __builtin_amdgcn_exp2f(sm_m[t][gb + g] - Ms);
+                lsum = fmaf(wgt, sm_l[t][gb + g], lsum);
+                if constexpr (WITH_V) val = fmaf(wgt, sm_acc[t][g][col], val);
+            }
+            const int h = hk * G + gb + g;
+            const int64_t pidx = ((int64_t)(b * s.Hq + h)) * n_chunks + chunk_id;
+            if (WITH_V && n_chunks == 1) {
+                const float o = lsum > 0.f ? val / lsum : 0.f;
+                T* op = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2] + col;
+                if constexpr (sizeof(T) == 4) *op = o; else *op = (T)f32_to_bf16_bits(o);
+            } else if constexpr (WITH_V) {
+                a.part_acc[pidx * D + col] = val;
+            }
+            if (col == 0) {
+                a.part_ml[pidx * 2 + 0] = M;
+                a.part_ml[pidx * 2 + 1] = lsum;
+            }
+        }
+    }
+}
+
+// An empty chunk: mark it for the merge / pooling passes (and define the output of an empty set).
+template <typename T, int D, int G, bool WITH_V>
+__device__ __forceinline__ void write_empty_chunk(const Shape& s, const DecodeRowsArgs& a, int n_chunks, int chunk_id, int b, int hk) {
+    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
+    if (threadIdx.x < G) {
+        float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
+        ml[0] = -INFINITY;
+        ml[1] = 0.f;
+    }
+    if (WITH_V && n_chunks == 1) {
+        for (int e = threadIdx.x; e < G * D; e += kBlock) {
+            const int g = e / D, col = e % D;
+            T* o = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + g) * s.o_stride[2] + col;
+            if constexpr (sizeof(T) == 4) *o = 0.f; else *o = 0;
+        }
+    }
+}
+
 template <typename T, int D, int G, bool GATHER, bool WITH_V, bool STORE>
 __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int EPL = Elem<T>::EPL;
@@ -31,7 +105,6 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
     constexpr int RPW = kWave / LPR;        // row groups per wave
     constexpr int U = 8;                    // rows in flight per row group (LPR is 8, 16 or 32)
     constexpr int NS = kWavesPerBlock * RPW;  // softmax streams per workgroup
-    constexpr int GB = (G > 4) ? 4 : G;     // heads merged per LDS round
     static_assert(LPR % U == 0, "row group must hold a whole number of load batches");
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -51,8 +124,6 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
     const int begin = chunk_id * plan.chunk;
     const int end = (begin + plan.chunk < n_rows) ? begin + plan.chunk : n_rows;
 
-    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;   // + g * n_chunks
-
     if constexpr (!GATHER) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
         if (chunk_id == 0 && a.hist11) {
             uint32_t* h = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
@@ -60,19 +131,8 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
         }
     }
 
-    if (begin >= end) {   // nothing to do: mark the chunk empty for the merge / pooling passes
-        if (threadIdx.x < G) {
-            float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
-            ml[0] = -INFINITY;
-            ml[1] = 0.f;
-        }
-        if (WITH_V && n_chunks == 1) {   // empty sequence: defined output is zero
-            for (int e = threadIdx.x; e < G * D; e += kBlock) {
-                int g = e / D, col = e % D;
-                T* o = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + g) * s.o_stride[2] + col;
-                if constexpr (sizeof(T) == 4) *o = 0.f; else *o = 0;
-            }
-        }
+    if (begin >= end) {   // nothing to do
+        write_empty_chunk<T, D, G, WITH_V>(s, a, n_chunks, chunk_id, b, hk);
         return;
     }
 
@@ -202,78 +262,265 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
         }
     }
 
-    // ---- merge the NS streams of the workgroup ----------------------------------
-    __shared__ float sm_m[NS][G];
-    __shared__ float sm_l[NS][G];
-    __shared__ float sm_acc[WITH_V ? NS : 1][GB][WITH_V ? D : 1];
-    const int sid = w * RPW + r;
-    if (c == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) { sm_m[sid][g] = m[g]; sm_l[sid][g] = l[g]; }
-    }
-#pragma unroll
-    for (int gb = 0; gb < G; gb += GB) {
-        if constexpr (WITH_V) {
-            if (gb > 0) __syncthreads();
-#pragma unroll
-            for (int g = 0; g < GB; ++g)
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) sm_acc[sid][g][c * EPL + e] = acc[gb + g][e];
-        }
-        __syncthreads();
-        constexpr int NE = WITH_V ? GB * D : GB;
-        for (int e = threadIdx.x; e < NE; e += kBlock) {
-            const int g = WITH_V ? e / D : e;
-            const int col = WITH_V ? e % D : 0;
-            float M = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < NS; ++t) M = fmaxf(M, sm_m[t][gb + g]);
-            const float Ms = (M == -INFINITY) ? 0.f : M;
-            float lsum = 0.f, val = 0.f;
-#pragma unroll
-            for (int t = 0; t < NS; ++t) {
-                const float wgt = __builtin_amdgcn_exp2f(sm_m[t][gb + g] - Ms);
-                lsum = fmaf(wgt, sm_l[t][gb + g], lsum);
-                if constexpr (WITH_V) val = fmaf(wgt, sm_acc[t][g][col], val);
-            }
-            const int h = hk * G + gb + g;
-            const int64_t pidx = ((int64_t)(b * s.Hq + h)) * n_chunks + chunk_id;
-            if (WITH_V && n_chunks == 1) {
-                const float o = lsum > 0.f ? val / lsum : 0.f;
-                T* op = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2] + col;
-                if constexpr (sizeof(T) == 4) *op = o; else *op = (T)f32_to_bf16_bits(o);
-            } else if constexpr (WITH_V) {
-                a.part_acc[pidx * D + col] = val;
-            }
-            if (col == 0) {
-                a.part_ml[pidx * 2 + 0] = M;
-                a.part_ml[pidx * 2 + 1] = lsum;
-            }
-        }
-    }
+    merge_streams<T, D, G, NS, EPL, WITH_V>(s, a, n_chunks, chunk_id, b, hk, w * RPW + r, c, m, l, acc);
 }
 
-// grid (Hq, B), block D threads: out[b,h,:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c
-template <typename T, int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(Shape s, int n_chunks, const float* __restrict__ part_ml,
-                                                         const float* __restrict__ part_acc, void* out) {
-    const int h = blockIdx.x, b = blockIdx.y, col = threadIdx.x;
-    const int64_t base = ((int64_t)(b * s.Hq + h)) * n_chunks;
-    float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[(base + c) * 2]);
-    float lsum = 0.f, val = 0.f;
-    if (M != -INFINITY) {
-        for (int c = 0; c < n_chunks; ++c) {
-            const float mc = part_ml[(base + c) * 2];
-            if (mc == -INFINITY) continue;
-            const float wgt = __builtin_amdgcn_exp2f(mc - M);
-            lsum = fmaf(wgt, part_ml[(base + c) * 2 + 1], lsum);
-            val = fmaf(wgt, part_acc[(base + c) * D + col], val);
+// ---- bf16 row kernel: reuse-layer gather and anchor pass 1 (paper Sec. 3.6) -------------------
+// Same data movement and modes as decode_rows_kernel, tuned for the HBM-bound bf16 case:
+//  * two register buffers of U = 4 K rows (+ 4 V rows) per lane group: the loads of the next
+//    batch are issued before the current batch is consumed, so a wave always has requests in flight;
+//  * q.k through v_dot2c_f32_bf16 on the raw bf16 pairs (no widening), P.V through the same
+//    instruction on (row u, row u+1) pairs interleaved with v_perm_b32, P rounded to bf16;
+//  * the running maximum is updated lazily: accumulators are rescaled only in batches where
+//    some stream's maximum actually moved.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t x, uint32_t y, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, x), __builtin_bit_cast(bf16x2_t, y), acc, false);
+}
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+    bf16x2_t r;
+    r[0] = (__bf16)lo; r[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+template <int D, int G, bool GATHER, bool WITH_V, bool STORE>
+__global__ __launch_bounds__(kBlock) void decode_rows_bf16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+    constexpr int EPL = 8;
+    constexpr int LPR = D / EPL;
+    constexpr int RPW = kWave / LPR;
+    constexpr int U = 4;
+    constexpr int NB = LPR / U;               // batches per 64-row group (even)
+    constexpr int NS = kWavesPerBlock * RPW;
+    static_assert(NB % 2 == 0, "double buffering walks the batches in pairs");
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = threadIdx.x >> 6;
+    const int c = lane % LPR;
+    const int r = lane / LPR;
+    const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
+    const int n_chunks = plan.n_chunks;
+
+    const int L = a.seqlens[b];
+    int n_rows = L;
+    if constexpr (GATHER) {
+        n_rows = a.k_per_seq[b];
+        n_rows = n_rows < a.k_max ? n_rows : a.k_max;
+        if (L <= 0) n_rows = 0;
+    } else {
+        if (chunk_id == 0 && a.hist11) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
+            uint32_t* hg = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
+            for (int i = threadIdx.x; i < 2048; i += kBlock) hg[i] = 0u;
         }
     }
-    const float o = lsum > 0.f ? val / lsum : 0.f;
-    T* op = reinterpret_cast<T*>(out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2] + col;
-    if constexpr (sizeof(T) == 4) *op = o; else *op = (T)f32_to_bf16_bits(o);
+    const int begin = chunk_id * plan.chunk;
+    const int end = (begin + plan.chunk < n_rows) ? begin + plan.chunk : n_rows;
+    if (begin >= end) {
+        write_empty_chunk<bf16_t, D, G, WITH_V>(s, a, n_chunks, chunk_id, b, hk);
+        return;
+    }
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
+    const uint32_t lane_off = c * 16;
+
+    const int32_t* idx = nullptr;
+    if constexpr (GATHER) {
+        int src = a.head_map ? a.head_map[hk] : hk;
+        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+        idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+    }
+
+    // raw bf16 pairs of the group's queries (this lane's 8 elements); the scale is applied to the dot
+    uint32_t q2[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + b * s.q_stride[0] + (int64_t)(hk * G + g) * s.q_stride[2] + c * EPL;
+        const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(qp);
+        q2[g][0] = raw.x; q2[g][1] = raw.y; q2[g][2] = raw.z; q2[g][3] = raw.w;
+    }
+    const float scale = s.scale_log2;
+
+    float m[G], l[G], acc[WITH_V ? G : 1][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) { m[g] = -INFINITY; l[g] = 0.f; }
+#pragma unroll
+    for (int g = 0; g < (WITH_V ? G : 1); ++g)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+
+    u32x4_t kA[U], vA[WITH_V ? U : 1], kB[U], vB[WITH_V ? U : 1];
+    uint32_t okA = 0, okB = 0;
+    float keep[STORE ? G : 1];
+
+    auto fetch_idx = [&](int j0) -> int {
+        if constexpr (GATHER) {
+            const int i = j0 + lane;
+            int row = (i < end) ? idx[i] : -1;
+            return row >= L ? -1 : row;
+        } else {
+            return j0;   // stream mode: rows are j0 + slot
+        }
+    };
+#define KASCADE_ISSUE(kbuf, vbuf, okv, rows_, u0_)                                                     \
+    {                                                                                                  \
+        okv = 0;                                                                                       \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                \
+            int row_;                                                                                  \
+            bool valid_;                                                                               \
+            if constexpr (GATHER) { row_ = __shfl(rows_, r * LPR + (u0_) + u); valid_ = row_ >= 0; }   \
+            else { row_ = (rows_) + r * LPR + (u0_) + u; valid_ = row_ < end; }                        \
+            okv |= (valid_ ? 1u : 0u) << u;                                                            \
+            const uint64_t off_ = (uint64_t)(valid_ ? row_ : 0) * row_bytes + lane_off;                \
+            kbuf[u] = *reinterpret_cast<const u32x4_t*>(Kb + off_);                                    \
+            if constexpr (WITH_V) vbuf[u] = *reinterpret_cast<const u32x4_t*>(Vb + off_);              \
+        }                                                                                              \
+    }
+#define KASCADE_COMPUTE(kbuf, vbuf, okv, u0_)                                                          \
+    {                                                                                                  \
+        float sc[U][G];                                                                                \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                \
+            _Pragma("unroll") for (int g = 0; g < G; ++g) {                                            \
+                float d_ = dot2_bf16(kbuf[u].x, q2[g][0], 0.f);                                        \
+                d_ = dot2_bf16(kbuf[u].y, q2[g][1], d_);                                               \
+                d_ = dot2_bf16(kbuf[u].z, q2[g][2], d_);                                               \
+                d_ = dot2_bf16(kbuf[u].w, q2[g][3], d_);                                               \
+                d_ = group_sum<LPR>(d_);                                                               \
+                sc[u][g] = ((okv >> u) & 1u) ? d_ * scale : -INFINITY;                                 \
+                if constexpr (STORE) { if (c == (u0_) + u) keep[g] = sc[u][g]; }                       \
+            }                                                                                          \
+        }                                                                                              \
+        float mnew[G];                                                                                 \
+        bool moved_ = false;                                                                           \
+        _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                \
+            float mx_ = fmaxf(fmaxf(sc[0][g], sc[1][g]), fmaxf(sc[2][g], sc[3][g]));                   \
+            mnew[g] = fmaxf(m[g], mx_);                                                                \
+            moved_ |= mnew[g] != m[g];                                                                 \
+        }                                                                                              \
+        if (__any(moved_)) {                                                                           \
+            _Pragma("unroll") for (int g = 0; g < G; ++g) {                                            \
+                const float ms_ = (mnew[g] == -INFINITY) ? 0.f : mnew[g];                              \
+                const float al_ = __builtin_amdgcn_exp2f(m[g] - ms_);                                  \
+                l[g] *= al_;                                                                           \
+                if constexpr (WITH_V) { _Pragma("unroll") for (int e = 0; e < EPL; ++e) acc[g][e] *= al_; } \
+                m[g] = mnew[g];                                                                        \
+            }                                                                                          \
+        }                                                                                              \
+        _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                \
+            const float ms_ = (m[g] == -INFINITY) ? 0.f : m[g];                                        \
+            _Pragma("unroll") for (int u = 0; u < U; ++u) {                                            \
+                sc[u][g] = __builtin_amdgcn_exp2f(sc[u][g] - ms_);                                     \
+                l[g] += sc[u][g];                                                                      \
+            }                                                                                          \
+        }                                                                                              \
+        if constexpr (WITH_V) {                                                                        \
+            _Pragma("unroll") for (int u = 0; u < U; u += 2) {                                         \
+                uint32_t vp_[EPL];                                                                     \
+                vp_[0] = __builtin_amdgcn_perm(vbuf[u + 1].x, vbuf[u].x, 0x05040100u);                 \
+                vp_[1] = __builtin_amdgcn_perm(vbuf[u + 1].x, vbuf[u].x, 0x07060302u);                 \
+                vp_[2] = __builtin_amdgcn_perm(vbuf[u + 1].y, vbuf[u].y, 0x05040100u);                 \
+                vp_[3] = __builtin_amdgcn_perm(vbuf[u + 1].y, vbuf[u].y, 0x07060302u);                 \
+                vp_[4] = __builtin_amdgcn_perm(vbuf[u + 1].z, vbuf[u].z, 0x05040100u);                 \
+                vp_[5] = __builtin_amdgcn_perm(vbuf[u + 1].z, vbuf[u].z, 0x07060302u);                 \
+                vp_[6] = __builtin_amdgcn_perm(vbuf[u + 1].w, vbuf[u].w, 0x05040100u);                 \
+                vp_[7] = __builtin_amdgcn_perm(vbuf[u + 1].w, vbuf[u].w, 0x07060302u);                 \
+                _Pragma("unroll") for (int g = 0; g < G; ++g) {                                        \
+                    const uint32_t pp_ = pack2_bf16(sc[u][g], sc[u + 1][g]);                           \
+                    _Pragma("unroll") for (int e = 0; e < EPL; ++e) acc[g][e] = dot2_bf16(vp_[e], pp_, acc[g][e]); \
+                }                                                                                      \
+            }                                                                                          \
+        }                                                                                              \
+    }
+
+    int j0 = begin + w * kWave;
+    int rows_cur = -1;
+    if (j0 < end) {
+        rows_cur = fetch_idx(j0);
+        KASCADE_ISSUE(kA, vA, okA, rows_cur, 0)
+    }
+    for (; j0 < end; j0 += kWavesPerBlock * kWave) {
+        const int j0n = j0 + kWavesPerBlock * kWave;
+        int rows_next = -1;
+        if (j0n < end) rows_next = fetch_idx(j0n);
+#pragma unroll
+        for (int bi = 0; bi < NB; bi += 2) {
+            const bool haveB = j0 + (bi + 1) * U < end;           // wave-uniform
+            if (haveB) KASCADE_ISSUE(kB, vB, okB, rows_cur, (bi + 1) * U)
+            KASCADE_COMPUTE(kA, vA, okA, bi * U)                   // batch bi always has its first row in range
+            if (bi + 2 < NB) {
+                if (j0 + (bi + 2) * U < end) KASCADE_ISSUE(kA, vA, okA, rows_cur, (bi + 2) * U)
+                else okA = 0;
+            } else if (j0n < end) {
+                KASCADE_ISSUE(kA, vA, okA, rows_next, 0)
+            }
+            if (haveB) KASCADE_COMPUTE(kB, vB, okB, (bi + 1) * U)
+            if (bi + 2 < NB && j0 + (bi + 2) * U >= end) break;   // nothing left in this 64-row group
+        }
+        if constexpr (STORE) {
+            const int j = j0 + lane;
+            if (j < end) {
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    a.logits[((int64_t)b * s.Hq + hk * G + g) * a.logit_pitch + j] = keep[g];
+            }
+        }
+        rows_cur = rows_next;
+    }
+#undef KASCADE_ISSUE
+#undef KASCADE_COMPUTE
+    merge_streams<bf16_t, D, G, NS, EPL, WITH_V>(s, a, n_chunks, chunk_id, b, hk, w * RPW + r, c, m, l, acc);
+}
+
+// grid (Hq, B), one wave per (sequence, query head):
+//   out[b,h,:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c,   M = max_c m_c.
+// Lanes first share the chunk statistics (one chunk per lane, all loads in flight at once),
+// then each lane owns D/64 output columns and walks the chunks with independent loads.
+template <typename T, int D>
+__global__ __launch_bounds__(kWave) void decode_merge_kernel(Shape s, int n_chunks, const float* __restrict__ part_ml,
+                                                             const float* __restrict__ part_acc, void* out) {
+    constexpr int CPL = D / kWave;   // columns per lane (1 or 2)
+    const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const int64_t base = ((int64_t)(b * s.Hq + h)) * n_chunks;
+    float M = -INFINITY;
+    for (int c = lane; c < n_chunks; c += kWave) M = fmaxf(M, part_ml[(base + c) * 2]);
+    M = wave_max(M);
+    float lsum = 0.f;
+    float val[CPL];
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) val[e] = 0.f;
+    if (M != -INFINITY) {
+        for (int c = lane; c < n_chunks; c += kWave) {
+            const float mc = part_ml[(base + c) * 2];
+            if (mc != -INFINITY) lsum = fmaf(__builtin_amdgcn_exp2f(mc - M), part_ml[(base + c) * 2 + 1], lsum);
+        }
+        lsum = wave_sum(lsum);
+        for (int c0 = 0; c0 < n_chunks; c0 += 8) {
+            float mc[8], x[8][CPL];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + u < n_chunks ? c0 + u : n_chunks - 1;
+                mc[u] = c0 + u < n_chunks ? part_ml[(base + c) * 2] : -INFINITY;
+#pragma unroll
+                for (int e = 0; e < CPL; ++e) x[u][e] = part_acc[(base + c) * D + e * kWave + lane];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (mc[u] != -INFINITY) {
+                    const float wgt = __builtin_amdgcn_exp2f(mc[u] - M);
+#pragma unroll
+                    for (int e = 0; e < CPL; ++e) val[e] = fmaf(wgt, x[u][e], val[e]);
+                }
+            }
+        }
+    }
+    T* op = reinterpret_cast<T*>(out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2];
+#pragma unroll
+    for (int e = 0; e < CPL; ++e) {
+        const float o = lsum > 0.f ? val[e] / lsum : 0.f;
+        if constexpr (sizeof(T) == 4) op[e * kWave + lane] = o; else op[e * kWave + lane] = (T)f32_to_bf16_bits(o);
+    }
 }
 
 // grid (ceil(max_seqlen/1024), Hkv, B), block 256: four consecutive keys per thread.
@@ -364,16 +611,39 @@ hipError_t launch_rows_td(const Shape& s, const DecodePlan& plan, const DecodeRo
     return hipErrorInvalidValue;
 }
 
+template <int D, int G>
+hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather, bool with_v,
+                               hipStream_t st) {
+    dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kBlock);
+    if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false>), grid, block, 0, st, s, plan, a);
+    else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, false, true>), grid, block, 0, st, s, plan, a);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_rows_bf16(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather, bool with_v,
+                            hipStream_t st) {
+    switch (s.G) {
+        case 1: return launch_rows_bf16_dg<D, 1>(s, plan, a, gather, with_v, st);
+        case 2: return launch_rows_bf16_dg<D, 2>(s, plan, a, gather, with_v, st);
+        case 4: return launch_rows_bf16_dg<D, 4>(s, plan, a, gather, with_v, st);
+        case 8: return launch_rows_bf16_dg<D, 8>(s, plan, a, gather, with_v, st);
+    }
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
 
 hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather,
                               bool with_v, bool store_logits, hipStream_t st) {
+    if (s.dtype == 1) {
+        if (s.D == 64) return launch_rows_bf16<64>(s, plan, a, gather, with_v, st);
+        if (s.D == 128) return launch_rows_bf16<128>(s, plan, a, gather, with_v, st);
+    }
     if (s.dtype == 0) {
         if (s.D == 64) return launch_rows_td<float, 64>(s, plan, a, gather, with_v, store_logits, st);
         if (s.D == 128) return launch_rows_td<float, 128>(s, plan, a, gather, with_v, store_logits, st);
-    } else {
-        if (s.D == 64) return launch_rows_td<bf16_t, 64>(s, plan, a, gather, with_v, store_logits, st);
-        if (s.D == 128) return launch_rows_td<bf16_t, 128>(s, plan, a, gather, with_v, store_logits, st);
     }
     return hipErrorInvalidValue;
 }
@@ -381,10 +651,10 @@ hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const Deco
 hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_ml, const float* part_acc,
                                void* out, hipStream_t st) {
     dim3 grid(s.Hq, s.B);
-    if (s.dtype == 0 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<float, 64>), grid, dim3(64), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 0 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), grid, dim3(128), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 1 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), grid, dim3(64), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 1 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), grid, dim3(128), 0, st, s, n_chunks, part_ml, part_acc, out);
+    if (s.dtype == 0 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<float, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 0 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 1 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 1 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -4,7 +4,9 @@
 //   1. radix select in three rounds (11 + 10 + 10 bits from the top) with LDS histograms: finds
 //      the bit pattern THR of the k-th largest score and how many scores equal to THR still
 //      belong to the set.  The first-round histogram can be handed in precomputed (the decode
-//      pooling pass builds it while it writes the scores).
+//      pooling pass builds it while it writes the scores).  After round 1 the scores of the
+//      threshold bucket (a few thousand at most, unless many scores are equal) are copied to
+//      LDS in one sweep and rounds 2-3 run there; memory is swept again only in the fallback.
 //   2. ordered compaction by position: keeps every score > THR and the first `need_eq`
 //      scores == THR, which gives ascending output and "lower index wins" among ties.
 #include "device_utils.h"
@@ -52,18 +54,62 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* w
     return before + inc - x;
 }
 
+constexpr int kEPT = 16;            // consecutive scores per thread per sweep step (four 16-byte loads)
+constexpr int kCandCap = 8192;      // scores of the threshold bucket kept in LDS for rounds 2 and 3
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+// Sixteen consecutive scores starting at i0 (zero beyond n).
+__device__ __forceinline__ void load16(const uint32_t* bits, int n, int i0, bool aligned, uint32_t (&u)[kEPT]) {
+    if (aligned && i0 + kEPT <= n) {
+        const u32x4_t* p = reinterpret_cast<const u32x4_t*>(bits + i0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const u32x4_t v = p[q];
+            u[4 * q + 0] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < kEPT; ++e) u[e] = (i0 + e < n) ? bits[i0 + e] : 0u;
+    }
+}
+
+// One radix round over `cnt` values held in LDS: finds the digit (bits shift+9..shift of the
+// values whose higher bits equal `want_hi`) that holds the rem-th largest, updates rem.
+__device__ __forceinline__ uint32_t lds_round(const uint32_t* cand, uint32_t cnt, int shift, bool check_hi, uint32_t want_hi,
+                                              uint32_t* hist, uint32_t* wave_tot, uint32_t* sh_digit, uint32_t* sh_rem,
+                                              uint32_t& rem) {
+    const int tid = threadIdx.x;
+    hist[tid] = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < cnt; base += kTopkBlock) {
+        const uint32_t i = base + tid;
+        const uint32_t v = i < cnt ? cand[i] : 0u;
+        hist_add(hist, (v >> shift) & 1023u, i < cnt && (!check_hi || (v >> 10) == want_hi));
+    }
+    __syncthreads();
+    const uint32_t here = hist[1023 - tid];
+    uint32_t tot;
+    const uint32_t above = block_exclusive_scan(here, wave_tot, &tot);
+    if (above < rem && above + here >= rem) { *sh_digit = 1023 - tid; *sh_rem = rem - above; }
+    __syncthreads();
+    rem = *sh_rem;
+    return *sh_digit;
+}
+
 __device__ __forceinline__ void select_segment(const Segment& sg) {
     __shared__ uint32_t hist[2048];
+    __shared__ uint32_t cand[kCandCap];
     __shared__ uint32_t wave_tot[kTopkWaves];
-    __shared__ uint32_t sh_digit, sh_rem;
+    __shared__ uint32_t sh_digit, sh_rem, sh_cnt, cand_n;
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t* bits = reinterpret_cast<const uint32_t*>(sg.scores);
     const int n = sg.n;
+    const bool aligned = (reinterpret_cast<uintptr_t>(bits) & 15u) == 0;
+    const uint64_t lt = (1ull << lane) - 1ull;
 
     if (sg.k_sel > 0) {
         uint32_t rem = (uint32_t)sg.k_sel;
-        uint32_t prefix = 0, mask = 0;
         // ---- round 1: bits 30..20 (bit 31 is the sign, always 0) ---------------------
         if (sg.hist11) {
             hist[tid] = sg.hist11[tid];
@@ -71,70 +117,107 @@ __device__ __forceinline__ void select_segment(const Segment& sg) {
         } else {
             hist[tid] = 0; hist[tid + 1024] = 0;
             __syncthreads();
-            for (int base = 0; base < n; base += kTopkBlock * 4) {
-                uint32_t u[4]; bool in[4];
+            for (int base = 0; base < n; base += kTopkBlock * kEPT) {
+                const int i0 = base + tid * kEPT;
+                uint32_t u[kEPT];
+                load16(bits, n, i0, aligned, u);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { const int i = base + e * kTopkBlock + tid; in[e] = i < n; u[e] = in[e] ? bits[i] : 0u; }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) hist_add(hist, (u[e] >> 20) & 2047u, in[e]);
+                for (int e = 0; e < kEPT; ++e) hist_add(hist, (u[e] >> 20) & 2047u, i0 + e < n);
             }
         }
+        if (tid == 0) cand_n = 0;
         __syncthreads();
         {
             // thread t owns bins 2047-2t and 2046-2t; prefix in thread order = count above
             const uint32_t hi = hist[2047 - 2 * tid], lo = hist[2046 - 2 * tid];
             uint32_t tot;
             const uint32_t above = block_exclusive_scan(hi + lo, wave_tot, &tot);
-            if (above < rem && above + hi >= rem) { sh_digit = 2047 - 2 * tid; sh_rem = rem - above; }
-            else if (above + hi < rem && above + hi + lo >= rem) { sh_digit = 2046 - 2 * tid; sh_rem = rem - above - hi; }
+            if (above < rem && above + hi >= rem) { sh_digit = 2047 - 2 * tid; sh_rem = rem - above; sh_cnt = hi; }
+            else if (above + hi < rem && above + hi + lo >= rem) { sh_digit = 2046 - 2 * tid; sh_rem = rem - above - hi; sh_cnt = lo; }
         }
         __syncthreads();
-        prefix = sh_digit << 20; mask = 0x7ffu << 20; rem = sh_rem;
-        // ---- rounds 2 and 3: bits 19..10, then 9..0 ------------------------------------
+        const uint32_t d1 = sh_digit;
+        const uint32_t cnt1 = sh_cnt;
+        rem = sh_rem;
+        uint32_t thr;
+        if (cnt1 <= (uint32_t)kCandCap) {
+            // ---- gather the threshold bucket's low 20 bits into LDS (one sweep), rounds 2-3 there ----
+            for (int base = 0; base < n; base += kTopkBlock * kEPT) {
+                const int i0 = base + tid * kEPT;
+                uint32_t u[kEPT];
+                load16(bits, n, i0, aligned, u);
 #pragma unroll
-        for (int shift = 10; shift >= 0; shift -= 10) {
-            hist[tid] = 0;
-            __syncthreads();
-            for (int base = 0; base < n; base += kTopkBlock * 4) {
-                uint32_t u[4]; bool in[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { const int i = base + e * kTopkBlock + tid; in[e] = i < n; u[e] = in[e] ? bits[i] : 0u; }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) hist_add(hist, (u[e] >> shift) & 1023u, in[e] && (u[e] & mask) == prefix);
+                for (int e = 0; e < kEPT; ++e) {
+                    const bool is_c = i0 + e < n && ((u[e] >> 20) & 2047u) == d1;
+                    const uint64_t mk = __ballot(is_c);
+                    if (mk) {
+                        const int first = __ffsll((unsigned long long)mk) - 1;
+                        uint32_t at = 0;
+                        if (lane == first) at = atomicAdd(&cand_n, (uint32_t)__popcll(mk));
+                        at = __shfl(at, first);
+                        const uint32_t slot = at + (uint32_t)__popcll(mk & lt);
+                        if (is_c && slot < (uint32_t)kCandCap) cand[slot] = u[e] & 0xfffffu;
+                    }
+                }
             }
             __syncthreads();
-            const uint32_t here = hist[1023 - tid];
-            uint32_t tot;
-            const uint32_t above = block_exclusive_scan(here, wave_tot, &tot);
-            if (above < rem && above + here >= rem) { sh_digit = 1023 - tid; sh_rem = rem - above; }
-            __syncthreads();
-            prefix |= sh_digit << shift; mask |= 1023u << shift; rem = sh_rem;
+            const uint32_t cnt = cand_n < (uint32_t)kCandCap ? cand_n : (uint32_t)kCandCap;
+            const uint32_t d2 = lds_round(cand, cnt, 10, false, 0u, hist, wave_tot, &sh_digit, &sh_rem, rem);
+            const uint32_t d3 = lds_round(cand, cnt, 0, true, d2, hist, wave_tot, &sh_digit, &sh_rem, rem);
+            thr = (d1 << 20) | (d2 << 10) | d3;
+        } else {
+            // ---- very many scores share the threshold bucket (e.g. thousands of zeros): sweep memory ----
+            uint32_t prefix = d1 << 20, mask = 0x7ffu << 20;
+#pragma unroll
+            for (int shift = 10; shift >= 0; shift -= 10) {
+                hist[tid] = 0;
+                __syncthreads();
+                for (int base = 0; base < n; base += kTopkBlock * kEPT) {
+                    const int i0 = base + tid * kEPT;
+                    uint32_t u[kEPT];
+                    load16(bits, n, i0, aligned, u);
+#pragma unroll
+                    for (int e = 0; e < kEPT; ++e) hist_add(hist, (u[e] >> shift) & 1023u, i0 + e < n && (u[e] & mask) == prefix);
+                }
+                __syncthreads();
+                const uint32_t here = hist[1023 - tid];
+                uint32_t tot;
+                const uint32_t above = block_exclusive_scan(here, wave_tot, &tot);
+                if (above < rem && above + here >= rem) { sh_digit = 1023 - tid; sh_rem = rem - above; }
+                __syncthreads();
+                prefix |= sh_digit << shift; mask |= 1023u << shift; rem = sh_rem;
+            }
+            thr = prefix;
         }
-        const uint32_t thr = prefix;
         const uint32_t need_eq = rem;   // >= 1
 
-        // ---- ordered compaction: four consecutive positions per thread ---------------
+        // ---- ordered compaction: sixteen consecutive positions per thread -----------
         uint32_t run_gt = 0, run_eq = 0;
-        for (int base = 0; base < n; base += kTopkBlock * 4) {
-            const int i0 = base + tid * 4;
-            uint32_t u[4]; bool in[4];
+        for (int base = 0; base < n; base += kTopkBlock * kEPT) {
+            const int i0 = base + tid * kEPT;
+            uint32_t u[kEPT];
+            load16(bits, n, i0, aligned, u);
+            uint32_t gtm = 0, eqm = 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { in[e] = i0 + e < n; u[e] = in[e] ? bits[i0 + e] : 0u; }
-            uint32_t cg = 0, ce = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { cg += (in[e] && u[e] > thr); ce += (in[e] && u[e] == thr); }
-            // counts per iteration are at most 4096 each: pack both into one scan
+            for (int e = 0; e < kEPT; ++e) {
+                const bool in = i0 + e < n;
+                gtm |= (uint32_t)(in && u[e] > thr) << e;
+                eqm |= (uint32_t)(in && u[e] == thr) << e;
+            }
+            // counts per step are at most 16384 each: pack both into one scan
             uint32_t tot;
-            const uint32_t ex = block_exclusive_scan(cg | (ce << 16), wave_tot, &tot);
+            const uint32_t ex = block_exclusive_scan((uint32_t)__popc(gtm) | ((uint32_t)__popc(eqm) << 16), wave_tot, &tot);
             uint32_t gt_before = run_gt + (ex & 0xffffu), eq_before = run_eq + (ex >> 16);
+            if ((gtm | eqm) != 0 && (gtm != 0 || eq_before < need_eq)) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool gt = in[e] && u[e] > thr, eq = in[e] && u[e] == thr;
-                if (gt || (eq && eq_before < need_eq)) {
-                    const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
-                    sg.out[pos] = i0 + e;
+                for (int e = 0; e < kEPT; ++e) {
+                    const bool gt = (gtm >> e) & 1u, eq = (eqm >> e) & 1u;
+                    if (gt || (eq && eq_before < need_eq)) {
+                        const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+                        sg.out[pos] = i0 + e;
+                    }
+                    gt_before += gt; eq_before += eq;
                 }
-                gt_before += gt; eq_before += eq;
             }
             run_gt += tot & 0xffffu; run_eq += tot >> 16;
         }
