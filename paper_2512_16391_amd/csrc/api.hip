@@ -64,9 +64,9 @@ Shape make_shape(const kascade_desc* d) {
 }
 
 // rows per workgroup for `n_rows` rows in each of `pairs` (sequence, key head) problems
-DecodePlan plan_rows(int64_t n_rows, int pairs, int min_chunk, int max_chunks, const char* env_name) {
+DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk, int max_chunks, const char* env_name) {
     DecodePlan p;
-    int64_t want = (kTargetBlocks + pairs - 1) / pairs;
+    int64_t want = (target_blocks + pairs - 1) / pairs;
     if (want < 1) want = 1;
     int64_t chunk = round_up_i((n_rows + want - 1) / want, 256);
     if (chunk < min_chunk) chunk = min_chunk;
@@ -79,8 +79,10 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int min_chunk, int max_chunks, c
     if (p.n_chunks < 1) p.n_chunks = 1;
     return p;
 }
-DecodePlan plan_gather(const Shape& s, int64_t k_max) { return plan_rows(k_max, s.B * s.Hkv, 256, 64, "KASCADE_GATHER_CHUNK"); }
-DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 256, 256, "KASCADE_STREAM_CHUNK"); }
+// gather: about four workgroups per compute unit.  stream: many more, smaller workgroups - with
+// ragged sequence lengths whole chunks fall away and few large workgroups leave a long tail.
+DecodePlan plan_gather(const Shape& s, int64_t k_max) { return plan_rows(k_max, s.B * s.Hkv, kTargetBlocks, 256, 64, "KASCADE_GATHER_CHUNK"); }
+DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 16 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
 
 struct Carver {
     char* base; size_t used;

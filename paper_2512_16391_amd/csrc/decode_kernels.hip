@@ -24,6 +24,11 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / kWave;
 
+__device__ __forceinline__ int rows_per_chunk(int n_rows, int n_chunks) {
+    const int c = (n_rows + n_chunks - 1) / n_chunks;
+    return (c + 63) & ~63;
+}
+
 // Workgroup-level merge of NS online-softmax streams (one per lane group) through LDS, then
 // either the final output (single chunk) or this chunk's partial (max, sum, acc) triple.
 template <typename T, int D, int G, int NS, int EPL, bool WITH_V>
@@ -121,8 +126,12 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
         n_rows = kb < a.k_max ? kb : a.k_max;
         if (L <= 0) n_rows = 0;
     }
-    const int begin = chunk_id * plan.chunk;
-    const int end = (begin + plan.chunk < n_rows) ? begin + plan.chunk : n_rows;
+    // gather: the rows of this (sequence, head) are split evenly over the n_chunks workgroups;
+    // stream: fixed chunk length (short sequences leave their last workgroups empty, which is cheaper
+    // than many small workgroups)
+    const int chunk = GATHER ? rows_per_chunk(n_rows, n_chunks) : plan.chunk;
+    const int begin = chunk_id * chunk;
+    const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
 
     if constexpr (!GATHER) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
         if (chunk_id == 0 && a.hist11) {
@@ -314,8 +323,12 @@ __global__ __launch_bounds__(kBlock) void decode_rows_bf16_kernel(Shape s, Decod
             for (int i = threadIdx.x; i < 2048; i += kBlock) hg[i] = 0u;
         }
     }
-    const int begin = chunk_id * plan.chunk;
-    const int end = (begin + plan.chunk < n_rows) ? begin + plan.chunk : n_rows;
+    // gather: the rows of this (sequence, head) are split evenly over the n_chunks workgroups;
+    // stream: fixed chunk length (short sequences leave their last workgroups empty, which is cheaper
+    // than many small workgroups)
+    const int chunk = GATHER ? rows_per_chunk(n_rows, n_chunks) : plan.chunk;
+    const int begin = chunk_id * chunk;
+    const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
     if (begin >= end) {
         write_empty_chunk<bf16_t, D, G, WITH_V>(s, a, n_chunks, chunk_id, b, hk);
         return;
