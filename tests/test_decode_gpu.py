@@ -246,3 +246,70 @@ def test_decode_config2_shape_reduced_batch():
     err = max_abs(f64(out), ref)
     print(f"  cfg2 reuse max-abs {err:.3e}", flush=True)
     assert err <= TOL_OUT[wl.dtype]
+
+
+# --------------------------------------------------------------------------- full-size configurations
+
+def test_decode_config2_full_size():
+    """The benchmark configuration itself (batch 8, 32768 tokens, k = 3277), generated on the GPU
+    exactly as bench.py does, in bench.py's launch configuration: anchor (sparse output) then the
+    three reuse layers.  Every sequence, every head, every index set against the oracle."""
+    print("case config2 full size", flush=True)
+    wl = workloads.config2(device=DEV)
+    sl, kp = i32(wl.seqlens), i32(wl.k_per_seq)
+    a = wl.layers[0]
+    idx_d, out_a = binding.kascade_decode_anchor(a.q, a.k, a.v, sl, kp, wl.Lmax, wl.k_max)
+    outs = [binding.kascade_decode_reuse(r.q, r.k, r.v, sl, kp, wl.k_max, idx_d) for r in wl.layers[1:]]
+    torch.cuda.synchronize()
+    idx = idx_d.cpu().numpy()
+    scale = ko.default_scale(wl.d)
+    kk = wl.k_per_seq[0]
+    swaps, worst = 0, 0.0
+    for b in range(wl.B):
+        qb, kb, vb = f64(a.q[b]), f64(a.k[b]), f64(a.v[b])
+        idx_ref, pooled = ko.decode_anchor_indices(qb, kb, scale, kk)
+        for h in range(wl.Hkv):
+            swaps += check_index_set(idx[b, h, :kk], idx_ref[h], pooled[h], where=f"cfg2 b{b} h{h}")
+        sets = [idx[b, h, :kk] for h in range(wl.Hkv)]
+        worst = max(worst, max_abs(f64(out_a[b]), ko.sparse_decode(qb, kb, vb, sets, scale)))
+        for r, o in zip(wl.layers[1:], outs):
+            worst = max(worst, max_abs(f64(o[b]), ko.sparse_decode(f64(r.q[b]), f64(r.k[b]), f64(r.v[b]), sets, scale)))
+        print(f"  cfg2 full b{b}: swaps so far {swaps}, worst max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[wl.dtype]
+
+
+def test_decode_config3_full_size_sampled():
+    """Bandwidth-stress configuration (batch 32, ragged 65536..131072 tokens, k = 5 %, 64 recent
+    tokens forced): run at full size, check the shortest, the longest and one middle sequence
+    (all heads) against the oracle, and structural properties for every sequence."""
+    print("case config3 full size", flush=True)
+    wl = workloads.config3(device=DEV, n_layers=2)
+    sl, kp = i32(wl.seqlens), i32(wl.k_per_seq)
+    a, r = wl.layers
+    W = wl.recent_window
+    idx_d, out_a = binding.kascade_decode_anchor(a.q, a.k, a.v, sl, kp, wl.Lmax, wl.k_max, recent_window=W)
+    out_r = binding.kascade_decode_reuse(r.q, r.k, r.v, sl, kp, wl.k_max, idx_d)
+    torch.cuda.synchronize()
+    idx = idx_d.cpu().numpy()
+    # properties at any size: set size, order, range, forced window, padding
+    for b in range(wl.B):
+        L, kb = wl.seqlens[b], wl.k_per_seq[b]
+        for h in range(wl.Hkv):
+            row = idx[b, h]
+            assert (np.diff(row[:kb]) > 0).all() and row[0] >= 0 and row[kb - 1] == L - 1
+            assert (row[kb - W:kb] == np.arange(L - W, L)).all()
+            assert (row[kb:] == -1).all()
+    order = np.argsort(wl.seqlens)
+    scale = ko.default_scale(wl.d)
+    worst, swaps = 0.0, 0
+    for b in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):
+        L, kb = wl.seqlens[b], wl.k_per_seq[b]
+        qb, kc, vc = f64(a.q[b]), f64(a.k[b, :, :L]), f64(a.v[b, :, :L])
+        idx_ref, pooled = ko.decode_anchor_indices(qb, kc, scale, kb, W)
+        for h in range(wl.Hkv):
+            swaps += check_index_set(idx[b, h, :kb], idx_ref[h], pooled[h], n_forced=W, where=f"cfg3 b{b} h{h}")
+        sets = [idx[b, h, :kb] for h in range(wl.Hkv)]
+        worst = max(worst, max_abs(f64(out_a[b]), ko.sparse_decode(qb, kc, vc, sets, scale)))
+        worst = max(worst, max_abs(f64(out_r[b]), ko.sparse_decode(f64(r.q[b]), f64(r.k[b, :, :L]), f64(r.v[b, :, :L]), sets, scale)))
+        print(f"  cfg3 b{b} L={L} k={kb}: swaps {swaps}, worst max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[wl.dtype]

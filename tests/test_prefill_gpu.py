@@ -179,3 +179,41 @@ def test_prefill_rejects_unsupported():
         binding.kascade_prefill_anchor(q.float().to(DEV), k.float().to(DEV), v.float().to(DEV), 32, dev_i32(kpt),
                                        dev_i64(off), 0)
     assert e.value.status == -2
+
+
+def test_prefill_config4_full_size_sampled():
+    """The prefill benchmark configuration itself (S = 32768, T = 32, 32/8 heads, d 128), generated on
+    the GPU as bench.py does: anchor (sparse output) then one reuse layer; sampled tiles (first
+    tiles, the k_min boundary, the last tile, a few in between) against the oracle, all heads."""
+    print("case prefill cfg4 full size", flush=True)
+    wl = workloads.config4(device=DEV, n_layers=2)
+    a, r = wl.layers
+    off = wl.idx_offsets
+    kpt_d, off_d = dev_i32(wl.k_per_tile), dev_i64(off)
+    idx_d, out_a = binding.kascade_prefill_anchor(a.q, a.k, a.v, wl.T, kpt_d, off_d, off[-1])
+    out_r = binding.kascade_prefill_reuse(r.q, r.k, r.v, wl.T, kpt_d, off_d, off[-1], idx_d)
+    torch.cuda.synchronize()
+    idx = idx_d.cpu().numpy()
+    tiles = [0, 1, 2, 8, 79, 80, 81, 300, 511, 777, wl.n_tiles - 1]
+    scale = ko.default_scale(wl.d)
+    Qa, Ka, Va = f64(a.q), f64(a.k), f64(a.v)
+    Qr, Kr, Vr = f64(r.q), f64(r.k), f64(r.v)
+    oa, orr = f64(out_a), f64(out_r)
+    swaps, worst = 0, 0.0
+    for t in tiles:
+        kt = wl.k_per_tile[t]
+        lo, hi = t * wl.T, (t + 1) * wl.T
+        sets = [idx[h, off[t]:off[t] + kt] for h in range(wl.Hkv)]
+        if kt:
+            idx_ref, pooled = ko.prefill_anchor_indices_tile(Qa, Ka, t, wl.T, scale, kt)
+            for h in range(wl.Hkv):
+                swaps += check_index_set(sets[h], idx_ref[h], pooled[h], where=f"cfg4 tile {t} head {h}")
+        worst = max(worst, max_abs(oa[lo:hi], ko.prefill_sparse_tile(Qa, Ka, Va, t, wl.T, sets, scale)))
+        worst = max(worst, max_abs(orr[lo:hi], ko.prefill_sparse_tile(Qr, Kr, Vr, t, wl.T, sets, scale)))
+        print(f"  cfg4 tile {t} k_t={kt}: swaps {swaps}, worst max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[BF16]
+    # every tile: ascending, in range
+    for t in range(1, wl.n_tiles, 37):
+        for h in range(wl.Hkv):
+            row = idx[h, off[t]:off[t + 1]]
+            assert (np.diff(row) > 0).all() and row[0] >= 0 and row[-1] < t * wl.T
