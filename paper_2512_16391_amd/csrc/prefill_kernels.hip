@@ -45,10 +45,12 @@ __device__ __forceinline__ int perm_key(int rho) {
     return (r >> 3) * 16 + h * 8 + (r & 7);
 }
 
-// K tile: [BK][D] bf16, 16-byte chunks XOR-swizzled by key bits {0,1,3}
+// K tile: [BK][D] bf16 row-major, the 16-byte chunks of a row XOR-swizzled by the key index so
+// that the 16 lanes served together by one LDS read (16 different keys, same chunk) fall into 16
+// different 16-byte slots of the 256-byte bank window (64 banks x 4 bytes).
 template <int D>
 __device__ __forceinline__ int k_off(int key, int chunk) {
-    const int f = (key & 3) | ((key >> 1) & 4);
+    const int f = (D == 128) ? (key & 15) : ((key >> 1) & 7);   // D = 64: two rows share a window
     return key * (D * 2) + ((chunk ^ f) << 4);
 }
 // V^T tile: [D][BK] bf16 (128-byte rows), 16-byte key groups XOR-swizzled by d
