@@ -133,7 +133,7 @@ __device__ __forceinline__ RowMap map_row(int rho, int t, int T, int hk, int G, 
 }
 
 template <int D, bool SPARSE, bool WITH_V>
-__global__ __launch_bounds__(kPB, 2) void prefill_attend_kernel(Shape s, PrefillArgs a) {
+__global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     __shared__ __align__(16) unsigned char smK[BK * D * 2];
     __shared__ __align__(16) unsigned char smVt[WITH_V ? D * BK * 2 : 16];
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(kPB, 2) void prefill_attend_kernel(Shape s, Prefill
 }
 
 template <int D>
-__global__ __launch_bounds__(kPB) void prefill_pool_kernel(Shape s, PrefillArgs a) {
+__global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16;
     __shared__ __align__(16) unsigned char smK[BK * D * 2];
     __shared__ int smPos[BK];
@@ -346,16 +346,16 @@ __global__ __launch_bounds__(kPB) void prefill_pool_kernel(Shape s, PrefillArgs 
             qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
         }
     }
-    // statistics of the 16 query rows whose scores land in this lane's registers
-    float m_r[16], inv_r[16];
+    // per query row whose scores land in this lane's registers: e_r = m + log2(l * rows), so that the
+    // pooled weight of a score is 2^(s c - e_r); rows beyond the sequence get weight 0
+    float e_r[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const RowMap rr = map_row(w * 32 + (r >> 2) * 8 + h * 4 + (r & 3), t, T, hk, s.G, S);
-        m_r[r] = 0.f; inv_r[r] = 0.f;
+        e_r[r] = INFINITY;
         if (rr.ok) {
             const float* st = a.stats + ((int64_t)rr.head * S + rr.token) * 2;
-            m_r[r] = st[0];
-            inv_r[r] = inv_rows / st[1];
+            e_r[r] = st[0] + __builtin_amdgcn_logf(st[1] / inv_rows);
         }
     }
 
@@ -392,8 +392,8 @@ __global__ __launch_bounds__(kPB) void prefill_pool_kernel(Shape s, PrefillArgs 
         float c0 = 0.f, c1 = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            c0 = fmaf(__builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_r[r])), inv_r[r], c0);
-            c1 = fmaf(__builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_r[r])), inv_r[r], c1);
+            c0 += __builtin_amdgcn_exp2f(fmaf(s0[r], c, -e_r[r]));
+            c1 += __builtin_amdgcn_exp2f(fmaf(s1[r], c, -e_r[r]));
         }
         c0 += __shfl_xor(c0, 32);
         c1 += __shfl_xor(c1, 32);
