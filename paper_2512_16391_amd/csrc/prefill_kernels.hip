@@ -58,6 +58,17 @@ __device__ __forceinline__ int vt_off(int d, int key) {
     return d * (BK * 2) + ((((key >> 3) ^ (d & 7) ^ ((d >> 3) & 7)) & 7) << 4) + ((key & 7) << 1);
 }
 
+// max / sum across the two half-waves (lanes i and i+32) on the vector ALU: v_permlane32_swap
+// exchanges the upper half of its first operand with the lower half of the second
+__device__ __forceinline__ float half_swap_max(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ bf16x8_t lds_frag(const unsigned char* p) {
     return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p));
 }
@@ -255,7 +266,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
         mx *= c;
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = half_swap_max(mx);
         const float m_new = fmaxf(m_run, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
@@ -266,7 +277,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));
             rs += s0[r] + s1[r];
         }
-        rs += __shfl_xor(rs, 32);
+        rs = half_swap_sum(rs);
         l_run = fmaf(l_run, alpha, rs);
         m_run = m_new;
 
@@ -395,8 +406,8 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
             c0 += __builtin_amdgcn_exp2f(fmaf(s0[r], c, -e_r[r]));
             c1 += __builtin_amdgcn_exp2f(fmaf(s1[r], c, -e_r[r]));
         }
-        c0 += __shfl_xor(c0, 32);
-        c1 += __shfl_xor(c1, 32);
+        c0 = half_swap_sum(c0);
+        c1 = half_swap_sum(c1);
         if (h == 0) { smPart[w][key0] = c0; smPart[w][key1] = c1; }
         __syncthreads();
         if (threadIdx.x < BK) {
