@@ -102,8 +102,22 @@ __device__ __forceinline__ void stage_issue(u32x4_t (&kr)[Stage<D>::PASSES], u32
     }
 }
 
-// returns true if this thread staged an invalid slot
+// Blocks that lie entirely before the tile (dense sweeps): every slot holds key kb*BK + slot, so
+// the byte offsets just advance by one block and no validity bookkeeping is needed.
 template <int D, bool WITH_V>
+__device__ __forceinline__ void stage_issue_seq(u32x4_t (&kr)[Stage<D>::PASSES], u32x4_t (&vr)[Stage<D>::PASSES],
+                                                uint32_t kb, const bf16_t* Kb, const bf16_t* Vb, uint32_t row_bytes) {
+    const uint32_t base = (kb * BK + threadIdx.x / Stage<D>::PPR) * row_bytes + (threadIdx.x % Stage<D>::PPR) * 16;
+#pragma unroll
+    for (int i = 0; i < Stage<D>::PASSES; ++i) {
+        const uint32_t off = base + (uint32_t)(i * Stage<D>::RPP) * row_bytes;
+        kr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Kb) + off);
+        if constexpr (WITH_V) vr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Vb) + off);
+    }
+}
+
+// returns true if this thread staged an invalid slot
+template <int D, bool WITH_V, bool SEQ = false>
 __device__ __forceinline__ bool stage_commit(const u32x4_t (&kr)[Stage<D>::PASSES], const u32x4_t (&vr)[Stage<D>::PASSES],
                                              const int (&pos)[Stage<D>::PASSES], unsigned char* smK,
                                              unsigned char* smVt, int* smPos) {
@@ -125,8 +139,10 @@ __device__ __forceinline__ bool stage_commit(const u32x4_t (&kr)[Stage<D>::PASSE
             *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 6, slot)) = (uint16_t)(v.w);
             *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 7, slot)) = (uint16_t)(v.w >> 16);
         }
-        if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
-        bad |= pos[i] < 0;
+        if constexpr (!SEQ) {
+            if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
+            bad |= pos[i] < 0;
+        }
     }
     return bad;
 }
@@ -221,16 +237,27 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
 
     u32x4_t kr[PASSES], vr[PASSES];
     int pos[PASSES];
-    KASCADE_BLOCK_POS(0, pos)
-    stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
+    const int n_seq = SPARSE ? 0 : prefix / BK;   // dense: blocks entirely before the tile, all slots valid
+    if (0 < n_seq) {
+        stage_issue_seq<D, WITH_V>(kr, vr, 0, Kb, Vb, row_stride);
+    } else {
+        KASCADE_BLOCK_POS(0, pos)
+        stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
+    }
 
     const int key0 = perm_key(q), key1 = 32 + key0;
 
     for (int kb = 0; kb < n_blocks; ++kb) {
         __syncthreads();   // previous block fully consumed
-        if (stage_commit<D, WITH_V>(kr, vr, pos, smK, smVt, smPos)) smFlag[kb & 1] = 1;
+        if (kb < n_seq) {
+            stage_commit<D, WITH_V, true>(kr, vr, pos, smK, smVt, smPos);
+        } else {
+            if (stage_commit<D, WITH_V>(kr, vr, pos, smK, smVt, smPos)) smFlag[kb & 1] = 1;
+        }
         __syncthreads();
-        if (kb + 1 < n_blocks) {
+        if (kb + 1 < n_seq) {
+            stage_issue_seq<D, WITH_V>(kr, vr, kb + 1, Kb, Vb, row_stride);
+        } else if (kb + 1 < n_blocks) {
             KASCADE_BLOCK_POS(kb + 1, pos)
             stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
         }
@@ -374,17 +401,25 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
     const int slot0 = threadIdx.x / Stage<D>::PPR;
     u32x4_t kr[PASSES], vr[PASSES];
     int pos[PASSES];
+    const int n_seq = prefix / BK;   // blocks without a ragged end
+    if (0 < n_seq) {
+        stage_issue_seq<D, false>(kr, vr, 0, Kb, nullptr, row_stride);
+    } else {
 #pragma unroll
-    for (int i = 0; i < PASSES; ++i) { const int p = i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
-    stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
+        for (int i = 0; i < PASSES; ++i) { const int p = i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
+        stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
+    }
     const int key0 = perm_key(q), key1 = 32 + key0;
     float* dst = a.pooled + hk * a.pooled_pitch + (int64_t)T * t * (t - 1) / 2;
 
     for (int kb = 0; kb < n_blocks; ++kb) {
         __syncthreads();
-        stage_commit<D, false>(kr, vr, pos, smK, nullptr, smPos);
+        if (kb < n_seq) stage_commit<D, false, true>(kr, vr, pos, smK, nullptr, smPos);
+        else stage_commit<D, false>(kr, vr, pos, smK, nullptr, smPos);
         __syncthreads();
-        if (kb + 1 < n_blocks) {
+        if (kb + 1 < n_seq) {
+            stage_issue_seq<D, false>(kr, vr, kb + 1, Kb, nullptr, row_stride);
+        } else if (kb + 1 < n_blocks) {
 #pragma unroll
             for (int i = 0; i < PASSES; ++i) { const int p = (kb + 1) * BK + i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
             stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
