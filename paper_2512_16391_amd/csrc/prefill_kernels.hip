@@ -3,8 +3,8 @@
 // A query tile is T consecutive tokens times the G query heads of one key head = 128 rows
 // (paper Sec. 3.4).  One workgroup of four waves owns one (tile, key head); wave w owns rows
 // 32w..32w+31, row rho = g*T + token_in_tile.  Keys are processed in blocks of 64 staged
-// through LDS: K row-major, V transposed, both XOR-swizzled so that the 16-byte MFMA operand
-// reads are bank-conflict free.
+// through LDS, K and V row-major and XOR-swizzled against bank conflicts; V^T operand fragments come
+// from the transposing LDS read (ds_read_b64_tr_b16).
 //
 //  prefill_attend_kernel  flash-style attention over a key list:
 //      dense  - all keys up to the diagonal, causal (anchor pass 1, Sec. 3.6): emits the row
@@ -53,9 +53,29 @@ __device__ __forceinline__ int k_off(int key, int chunk) {
     const int f = (D == 128) ? (key & 15) : ((key >> 1) & 7);   // D = 64: two rows share a window
     return key * (D * 2) + ((chunk ^ f) << 4);
 }
-// V^T tile: [D][BK] bf16 (128-byte rows), 16-byte key groups XOR-swizzled by d
-__device__ __forceinline__ int vt_off(int d, int key) {
-    return d * (BK * 2) + ((((key >> 3) ^ (d & 7) ^ ((d >> 3) & 7)) & 7) << 4) + ((key & 7) << 1);
+// V tile: [BK][D] bf16 row-major like K.  The MFMA needs V^T fragments (for one d, eight
+// consecutive keys); ds_read_b64_tr_b16 delivers them from the row-major tile: within each group
+// of 16 lanes, lane j points at four consecutive elements of one row, and lane i receives element
+// i%4 of the segments named by lanes i/4, i/4+4, i/4+8, i/4+12.  The 64-byte groups of a row are
+// XOR-swizzled by key%4 so that the four rows one read touches fall into different banks.
+template <int D>
+__device__ __forceinline__ int v_off(int key, int d) {
+    const int f = (D == 128) ? ((key & 3) << 2) : (((key >> 1) & 1) << 2);
+    return key * (D * 2) + ((((d >> 3) ^ f)) << 4) + ((d & 7) << 1);
+}
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+// V^T fragment for MFMA row (lane%32) = d index dblk*32 + lane%32, keys key0 + (lane/32)*8 + 0..7
+template <int D>
+__device__ __forceinline__ bf16x8_t vt_frag(const unsigned char* smV, int dblk, int key0) {
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, a = lane & 3, e = (lane >> 2) & 3;
+    const int key = key0 + (g >> 1) * 8 + e;
+    const int d0 = dblk * 32 + (g & 1) * 16 + 4 * a;
+    typedef s16x4_t __attribute__((address_space(3))) * lds_v4;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smV + v_off<D>(key, d0)));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smV + v_off<D>(key + 4, d0)));
+    struct { s16x4_t lo, hi; } both = {lo, hi};
+    return __builtin_bit_cast(bf16x8_t, both);
 }
 
 // max / sum across the two half-waves (lanes i and i+32) on the vector ALU: v_permlane32_swap
@@ -128,16 +148,8 @@ __device__ __forceinline__ bool stage_commit(const u32x4_t (&kr)[Stage<D>::PASSE
         const int slot = i * Stage<D>::RPP + r0;
         *reinterpret_cast<u32x4_t*>(smK + k_off<D>(slot, piece)) = kr[i];
         if constexpr (WITH_V) {
-            const u32x4_t v = vr[i];
-            const int d0 = piece * 8;
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 0, slot)) = (uint16_t)(v.x);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 1, slot)) = (uint16_t)(v.x >> 16);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 2, slot)) = (uint16_t)(v.y);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 3, slot)) = (uint16_t)(v.y >> 16);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 4, slot)) = (uint16_t)(v.z);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 5, slot)) = (uint16_t)(v.z >> 16);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 6, slot)) = (uint16_t)(v.w);
-            *reinterpret_cast<uint16_t*>(smVt + vt_off(d0 + 7, slot)) = (uint16_t)(v.w >> 16);
+            const int f = (D == 128) ? ((slot & 3) << 2) : (((slot >> 1) & 1) << 2);
+            *reinterpret_cast<u32x4_t*>(smVt + slot * (D * 2) + ((piece ^ f) << 4)) = vr[i];
         }
         if constexpr (!SEQ) {
             if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
@@ -163,7 +175,7 @@ template <int D, bool SPARSE, bool WITH_V>
 __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     __shared__ __align__(16) unsigned char smK[BK * D * 2];
-    __shared__ __align__(16) unsigned char smVt[WITH_V ? D * BK * 2 : 16];
+    __shared__ __align__(16) unsigned char smVt[WITH_V ? BK * D * 2 : 16];   // V tile, row-major
     __shared__ int smPos[BK];
     __shared__ int smFlag[2];
 
@@ -319,7 +331,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             for (int i = 0; i < DBLK; ++i) {
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
-                    const bf16x8_t va = lds_frag(smVt + vt_off(i * 32 + q, st * 16 + h * 8));
+                    const bf16x8_t va = vt_frag<D>(smVt, i, st * 16);
                     acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[st], acc_o[i], 0, 0, 0);
                 }
             }
