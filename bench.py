@@ -86,32 +86,73 @@ def main():
         if prefill is not None:
             prefill.step()
 
+    # one plain 1 GiB device copy: the yardstick that hardware-counter runs (FETCH_SIZE / WRITE_SIZE)
+    # scale their readings by; it is outside every timed region
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
-    binding.kascade_profile_enable(True)
-    binding.kascade_profile_reset()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    dec_ms = 0.0
+    # ---- timed region 1: K whole steps, nothing but the library's own launches -------------------
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ev[0].record()
+    for e0, e1 in evs:
+        e0.record()
         decode_step()
-        ev[1].record()
+        e1.record()
         if prefill is not None:
             prefill.step()
-        ev[1].synchronize()
-        dec_ms += ev[0].elapsed_time(ev[1])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = binding.kascade_profile_read()
-    binding.kascade_profile_enable(False)
-
+    dec_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     n_layers = len(wl.layers)
     dec_us_per_layer = dec_ms * 1e3 / args.steps / n_layers
+
+    # ---- timed region 2: the same K steps with a HIP event pair around every kernel launch --------
+    binding.kascade_profile_enable(True)
+    binding.kascade_profile_reset()
+    torch.cuda.synchronize()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = binding.kascade_profile_read()
+    binding.kascade_profile_enable(False)
+
+    # ---- the decode step as one HIP graph (no launch gaps): replayed K times -----------------------
+    graph_us_per_layer = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            decode_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        ref_outs = [o.clone() for o in outs]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            decode_step()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        same = all(torch.equal(a_, b_) for a_, b_ in zip(ref_outs, outs))
+        reps = max(args.steps, 20)
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(reps):
+            g.replay()
+        g1.record()
+        g1.synchronize()
+        if same:
+            graph_us_per_layer = g0.elapsed_time(g1) * 1e3 / reps / n_layers
+    except Exception as exc:   # graph capture is an extra, never the headline
+        print(f"bench.py: graph replay skipped: {exc}", file=sys.stderr)
 
     def avg_us(name):
         return prof[name][0] * 1e3 / prof[name][1] if name in prof else None
@@ -130,6 +171,10 @@ def main():
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gather_bytes / t_gather / 1e3 / HBM_PEAK_GBS, 4),
                       "traffic": None, "algorithmic_bytes": gather_bytes, "avg_kernel_us": round(t_gather, 2)}
 
+    traffic = load_traffic()
+    roofline["traffic"] = traffic.get("decode_stream")
+    roofline_reuse["traffic"] = traffic.get("decode_gather")
+
     rec = {
         "metric": "sparse decode attn us/layer + HBM GB/s; prefill attn TFLOPS at 32K ctx",
         "value": round(dec_us_per_layer, 2), "unit": "us/layer (decode, mean of 1 anchor + 3 reuse layers)",
@@ -139,6 +184,8 @@ def main():
                    + ("; " + prefill.name if prefill is not None else ""),
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "context": L, "k": kmax},
         "decode_tokens_per_s": round(B / (dec_us_per_layer * n_layers * 1e-6), 1),
+        "decode_us_per_layer_hip_graph": round(graph_us_per_layer, 2) if graph_us_per_layer else None,
+        "kernel_timing": "second timed pass of the same K steps, HIP event pair around every launch",
         "decode_reuse_hbm_GBps": roofline_reuse["achieved"],
         "kernel_us": kernels_us,
         "roofline": roofline,
@@ -238,6 +285,17 @@ class PrefillBench:
                                         "frac": round(tf(anchor_flop, anchor_us) / peak_tflops, 4),
                                         "algorithmic_flop": anchor_flop, "out_mode": "sparse"},
         }
+
+
+def load_traffic():
+    """HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same
+    command (scaled by the 1 GiB copy above); the summary lives in profiles/hbm_traffic.json."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return {k: v.get("bytes_per_launch") for k, v in json.load(f).get("kernels", {}).items()}
+    except (OSError, ValueError):
+        return {}
 
 
 def _blas_threads():
