@@ -157,8 +157,11 @@ const char* kascade_status_string(int32_t status);
  * the recorded events of kernel `kernel` (0 <= kernel < kascade_profile_kernels()), and returns
  * its name, the summed elapsed milliseconds and the number of launches since the last
  * kascade_profile_reset().  With profiling off (the default) the library creates no events.
+ * kascade_profile_calibrate launches `launches` empty kernels bracketed the same way (reported as
+ * kernel "empty_kernel"): the duration an event pair reports for no work at all.
  */
 int kascade_profile_enable(int32_t on);
+int kascade_profile_calibrate(int32_t launches, void* hip_stream);
 int kascade_profile_reset(void);
 int32_t kascade_profile_kernels(void);
 int kascade_profile_read(int32_t kernel, const char** name, double* total_ms, int64_t* launches);

@@ -24,7 +24,7 @@ OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE = 0, 1, 2
 EXPORTS = [
     "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
-    "kascade_profile_enable", "kascade_profile_reset", "kascade_profile_kernels", "kascade_profile_read",
+    "kascade_profile_enable", "kascade_profile_calibrate", "kascade_profile_reset", "kascade_profile_kernels", "kascade_profile_read",
 ]
 
 
@@ -73,6 +73,8 @@ def load_library(path: Optional[str] = None):
     lib.kascade_version.restype = ctypes.c_char_p
     lib.kascade_profile_enable.argtypes = [i32]
     lib.kascade_profile_enable.restype = ctypes.c_int
+    lib.kascade_profile_calibrate.argtypes = [i32, vp]
+    lib.kascade_profile_calibrate.restype = ctypes.c_int
     lib.kascade_profile_reset.argtypes = []
     lib.kascade_profile_reset.restype = ctypes.c_int
     lib.kascade_profile_kernels.argtypes = []
@@ -94,6 +96,10 @@ def version() -> str:
 
 def kascade_profile_enable(on: bool) -> None:
     _check(load_library().kascade_profile_enable(1 if on else 0), "kascade_profile_enable")
+
+
+def kascade_profile_calibrate(launches: int = 50) -> None:
+    _check(load_library().kascade_profile_calibrate(int(launches), _stream()), "kascade_profile_calibrate")
 
 
 def kascade_profile_reset() -> None:

@@ -144,10 +144,10 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // Events are created on demand and kept until profiling is disabled; with profiling off
 // the library creates nothing.
 enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
-                K_PF_TOPK, K_PF_SPARSE, K_COUNT };
+                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
-    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse"};
+    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
@@ -189,6 +189,23 @@ int kascade_profile_enable(int32_t on) {
         for (auto e : g_prof.free_events) (void)hipEventDestroy(e);
         g_prof.recs.clear();
         g_prof.free_events.clear();
+    }
+    return KASCADE_OK;
+}
+
+// An empty kernel bracketed like every other launch: what the event pair itself costs.
+__global__ void kascade_empty_kernel() {}
+
+int kascade_profile_calibrate(int32_t launches, void* hip_stream) {
+    if (launches <= 0) return KASCADE_INVALID_ARG;
+    if (!g_prof.on) return KASCADE_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    for (int i = 0; i < launches; ++i) {
+        const int st = timed(K_NULL, stream, [&] {
+            hipLaunchKernelGGL(kascade_empty_kernel, dim3(1), dim3(64), 0, stream);
+            return hipGetLastError();
+        });
+        if (st != KASCADE_OK) return st;
     }
     return KASCADE_OK;
 }
