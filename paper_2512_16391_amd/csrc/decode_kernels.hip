@@ -294,8 +294,8 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <int D, int G, bool GATHER, bool WITH_V, bool STORE>
-__global__ __launch_bounds__(kBlock) void decode_rows_bf16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+template <int D, int G, bool GATHER, bool WITH_V, bool STORE, bool PIPE>
+__global__ __launch_bounds__(kBlock, (PIPE ? 2 : 4)) void decode_rows_bf16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int EPL = 8;
     constexpr int LPR = D / EPL;
     constexpr int RPW = kWave / LPR;
@@ -448,38 +448,62 @@ __global__ __launch_bounds__(kBlock) void decode_rows_bf16_kernel(Shape s, Decod
     }
 
     int j0 = begin + w * kWave;
-    int rows_cur = -1;
-    if (j0 < end) {
-        rows_cur = fetch_idx(j0);
-        KASCADE_ISSUE(kA, vA, okA, rows_cur, 0)
-    }
-    for (; j0 < end; j0 += kWavesPerBlock * kWave) {
-        const int j0n = j0 + kWavesPerBlock * kWave;
-        int rows_next = -1;
-        if (j0n < end) rows_next = fetch_idx(j0n);
-#pragma unroll
-        for (int bi = 0; bi < NB; bi += 2) {
-            const bool haveB = j0 + (bi + 1) * U < end;           // wave-uniform
-            if (haveB) KASCADE_ISSUE(kB, vB, okB, rows_cur, (bi + 1) * U)
-            KASCADE_COMPUTE(kA, vA, okA, bi * U)                   // batch bi always has its first row in range
-            if (bi + 2 < NB) {
-                if (j0 + (bi + 2) * U < end) KASCADE_ISSUE(kA, vA, okA, rows_cur, (bi + 2) * U)
-                else okA = 0;
-            } else if (j0n < end) {
-                KASCADE_ISSUE(kA, vA, okA, rows_next, 0)
-            }
-            if (haveB) KASCADE_COMPUTE(kB, vB, okB, (bi + 1) * U)
-            if (bi + 2 < NB && j0 + (bi + 2) * U >= end) break;   // nothing left in this 64-row group
+    if constexpr (PIPE) {
+        int rows_cur = -1;
+        if (j0 < end) {
+            rows_cur = fetch_idx(j0);
+            KASCADE_ISSUE(kA, vA, okA, rows_cur, 0)
         }
-        if constexpr (STORE) {
-            const int j = j0 + lane;
-            if (j < end) {
+        for (; j0 < end; j0 += kWavesPerBlock * kWave) {
+            const int j0n = j0 + kWavesPerBlock * kWave;
+            int rows_next = -1;
+            if (j0n < end) rows_next = fetch_idx(j0n);
 #pragma unroll
-                for (int g = 0; g < G; ++g)
-                    a.logits[((int64_t)b * s.Hq + hk * G + g) * a.logit_pitch + j] = keep[g];
+            for (int bi = 0; bi < NB; bi += 2) {
+                const bool haveB = j0 + (bi + 1) * U < end;           // wave-uniform
+                if (haveB) KASCADE_ISSUE(kB, vB, okB, rows_cur, (bi + 1) * U)
+                KASCADE_COMPUTE(kA, vA, okA, bi * U)                   // batch bi always has its first row in range
+                if (bi + 2 < NB) {
+                    if (j0 + (bi + 2) * U < end) KASCADE_ISSUE(kA, vA, okA, rows_cur, (bi + 2) * U)
+                    else okA = 0;
+                } else if (j0n < end) {
+                    KASCADE_ISSUE(kA, vA, okA, rows_next, 0)
+                }
+                if (haveB) KASCADE_COMPUTE(kB, vB, okB, (bi + 1) * U)
+                if (bi + 2 < NB && j0 + (bi + 2) * U >= end) break;   // nothing left in this 64-row group
+            }
+            if constexpr (STORE) {
+                const int j = j0 + lane;
+                if (j < end) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        a.logits[((int64_t)b * s.Hq + hk * G + g) * a.logit_pitch + j] = keep[g];
+                }
+            }
+            rows_cur = rows_next;
+        }
+    } else {
+        // small problems: one register buffer, twice the resident workgroups - every workgroup of the
+        // grid is on the chip at once and latency is hidden across workgroups instead of inside a wave
+        (void)kB; (void)vB; (void)okB;
+        for (; j0 < end; j0 += kWavesPerBlock * kWave) {
+            const int rows_cur = fetch_idx(j0);
+#pragma unroll
+            for (int bi = 0; bi < NB; ++bi) {
+                if (j0 + bi * U < end) {
+                    KASCADE_ISSUE(kA, vA, okA, rows_cur, bi * U)
+                    KASCADE_COMPUTE(kA, vA, okA, bi * U)
+                }
+            }
+            if constexpr (STORE) {
+                const int j = j0 + lane;
+                if (j < end) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        a.logits[((int64_t)b * s.Hq + hk * G + g) * a.logit_pitch + j] = keep[g];
+                }
             }
         }
-        rows_cur = rows_next;
     }
 #undef KASCADE_ISSUE
 #undef KASCADE_COMPUTE
@@ -628,9 +652,12 @@ template <int D, int G>
 hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather, bool with_v,
                                hipStream_t st) {
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kBlock);
-    if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false>), grid, block, 0, st, s, plan, a);
-    else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true>), grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, false, true>), grid, block, 0, st, s, plan, a);
+    // a gather grid that fits on the chip at four workgroups per compute unit runs the unpipelined form
+    const bool small = gather && G <= 4 && (int64_t)plan.n_chunks * s.Hkv * s.B <= 4 * 256;
+    if (gather && small) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false>), grid, block, 0, st, s, plan, a);
+    else if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, true>), grid, block, 0, st, s, plan, a);
+    else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true, true>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, false, true, true>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 
