@@ -227,3 +227,47 @@ def config4(device="cuda", n_layers=4, S=32768, T=32):
     prefix, at least 256."""
     return make_prefill_workload(f"cfg4-prefill-bf16-S{S}-T{T}", 4, n_layers, S, 32, 8, 128,
                                  torch.bfloat16, T, 100, 256, 64, 0.80, device=device)
+
+
+CONFIG5_ANCHORS = (0, 1, 4, 12, 20)
+
+
+def config5_layer_kind(layer: int):
+    """("anchor" | "reuse", index of the anchor layer whose sets the layer uses)."""
+    src = max(a for a in CONFIG5_ANCHORS if a <= layer)
+    return ("anchor" if layer in CONFIG5_ANCHORS else "reuse"), src
+
+
+def config5_prefill(device="cuda", layers=(0, 1, 2, 3), S=131072, T=32, decode_steps=256):
+    """Attention-only stack, 32/8 heads, d128, bf16: causal prefill of S tokens, k_t = 10 % of the prefix,
+    anchors {0, 1, 4, 12, 20}, hitters drifting 15 % per layer.  Returns a PrefillWorkload holding only
+    the requested layers (layer 0 is the dense-output anchor); K/V are allocated with room for
+    `decode_steps` more tokens so that decode steps can append to the same cache."""
+    device = torch.device(device)
+    Hq, Hkv, d = 32, 8, 128
+    G = Hq // Hkv
+    wl = PrefillWorkload(f"cfg5-prefill-bf16-S{S}-T{T}", S, Hq, Hkv, d, torch.bfloat16, T, prefill_budgets(S, T, 100, 0))
+    prev = [None] * Hkv
+    for layer in range(max(layers) + 1):
+        gen = torch.Generator(device=device)
+        gen.manual_seed(layer_seed(BASE_SEED, 5, layer))
+        keep = layer in layers
+        pos_all = []
+        us = []
+        for hk in range(Hkv):
+            us.append(_unit(gen, d, device))
+            prev[hk] = _next_hitters(gen, prev[hk], S, 64, 0.85, device)
+            pos_all.append(prev[hk])
+        if not keep:
+            continue
+        q = torch.randn(S, Hq, d, generator=gen, device=device, dtype=torch.float32)
+        k = torch.zeros(Hkv, S + decode_steps, d, device=device, dtype=torch.bfloat16)
+        v = torch.zeros(Hkv, S + decode_steps, d, device=device, dtype=torch.bfloat16)
+        for hk in range(Hkv):
+            kh = torch.randn(S, d, generator=gen, device=device, dtype=torch.float32)
+            kh[pos_all[hk]] += 3.0 * us[hk]
+            k[hk, :S] = kh.to(torch.bfloat16)
+            v[hk, :S] = torch.randn(S, d, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+            q[:, hk * G:(hk + 1) * G] += us[hk]
+        wl.layers.append(PrefillLayer(q.to(torch.bfloat16), k, v))
+    return wl

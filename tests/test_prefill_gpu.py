@@ -217,3 +217,84 @@ def test_prefill_config4_full_size_sampled():
         for h in range(wl.Hkv):
             row = idx[h, off[t]:off[t + 1]]
             assert (np.diff(row) > 0).all() and row[0] >= 0 and row[-1] < t * wl.T
+
+
+def test_config5_shape_prefill_131072_then_decode():
+    """Largest configuration: 32/8 heads, d 128, bf16, causal prefill of 131072 tokens (k_t = 10 % of
+    the prefix, 4096 tiles, 26.8 M indices per key head, 8.6 GB of pooled scores), layers 0 (dense-output
+    anchor), 1 (anchor) and 2 (reuses layer 1), then two decode steps on the same caches at
+    L = 131073, 131074 (k = 10 %).  Sampled tiles / all decode outputs against the oracle."""
+    print("case cfg5 S=131072", flush=True)
+    S, T, steps = 131072, 32, 2
+    wl = workloads.config5_prefill(device=DEV, layers=(0, 1, 2), S=S, T=T, decode_steps=steps)
+    off = wl.idx_offsets
+    kpt_d, off_d = dev_i32(wl.k_per_tile), dev_i64(off)
+    l0, l1, l2 = wl.layers
+    kv = lambda layer: (layer.k[:, :S], layer.v[:, :S])
+    scale = ko.default_scale(wl.d)
+    tiles = [1, 2047, wl.n_tiles - 1]
+
+    def check_tiles(layer, out, sets_of, dense, where):
+        Q, Kp, Vp = f64(layer.q), f64(layer.k[:, :S]), f64(layer.v[:, :S])
+        o = None
+        worst = 0.0
+        for t in tiles:
+            lo, hi = t * T, (t + 1) * T
+            ref = ko.prefill_dense_tile(Q, Kp, Vp, t, T, scale) if dense else \
+                ko.prefill_sparse_tile(Q, Kp, Vp, t, T, sets_of(t), scale)
+            worst = max(worst, max_abs(f64(out[lo:hi]), ref))
+            print(f"  {where} tile {t}: worst max-abs {worst:.3e}", flush=True)
+        assert worst <= TOL_OUT[BF16]
+        return Q, Kp
+
+    # layer 0: anchor with dense output
+    k0, v0 = kv(l0)
+    idx0, out0 = binding.kascade_prefill_anchor(l0.q, k0, v0, T, kpt_d, off_d, off[-1], out_mode=binding.KASCADE_OUT_DENSE)
+    torch.cuda.synchronize()
+    check_tiles(l0, out0, None, True, "layer0 dense")
+    del idx0, out0
+    # layer 1: anchor with sparse output, index sets against the oracle on the sampled tiles
+    k1, v1 = kv(l1)
+    idx1, out1 = binding.kascade_prefill_anchor(l1.q, k1, v1, T, kpt_d, off_d, off[-1])
+    torch.cuda.synchronize()
+    sets_of = lambda t: [idx1[h, off[t]:off[t + 1]].cpu().numpy() for h in range(wl.Hkv)]
+    Q1, K1 = check_tiles(l1, out1, sets_of, False, "layer1 anchor")
+    swaps = 0
+    for t in tiles:
+        idx_ref, pooled = ko.prefill_anchor_indices_tile(Q1, K1, t, T, scale, wl.k_per_tile[t])
+        got = sets_of(t)
+        for h in range(wl.Hkv):
+            swaps += check_index_set(got[h], idx_ref[h], pooled[h], where=f"cfg5 tile {t} head {h}")
+    print(f"  layer1 index sets: swaps {swaps}", flush=True)
+    del Q1, K1, out1
+    # layer 2: reuse of layer 1's sets
+    k2, v2 = kv(l2)
+    out2 = binding.kascade_prefill_reuse(l2.q, k2, v2, T, kpt_d, off_d, off[-1], idx1)
+    torch.cuda.synchronize()
+    check_tiles(l2, out2, sets_of, False, "layer2 reuse")
+    del out2, idx1
+
+    # decode steps appended to the same caches: layer 1 as anchor, layer 2 reusing its set
+    g = torch.Generator(device=DEV).manual_seed(777)
+    for step in range(steps):
+        L = S + step + 1
+        kk = workloads.budget(L, 100)
+        newq = torch.randn(2, 1, wl.Hq, wl.d, generator=g, device=DEV).to(BF16)
+        for layer in (l1, l2):
+            layer.k[:, L - 1] = torch.randn(wl.Hkv, wl.d, generator=g, device=DEV).to(BF16)
+            layer.v[:, L - 1] = torch.randn(wl.Hkv, wl.d, generator=g, device=DEV).to(BF16)
+        sl, kp = dev_i32([L]), dev_i32([kk])
+        kc1, vc1 = l1.k[None, :, :L], l1.v[None, :, :L]
+        kc2, vc2 = l2.k[None, :, :L], l2.v[None, :, :L]
+        idx_d, o1 = binding.kascade_decode_anchor(newq[0], kc1, vc1, sl, kp, L, kk)
+        o2 = binding.kascade_decode_reuse(newq[1], kc2, vc2, sl, kp, kk, idx_d)
+        torch.cuda.synchronize()
+        idx_np = idx_d.cpu().numpy()
+        idx_ref, pooled = ko.decode_anchor_indices(f64(newq[0, 0]), f64(kc1[0]), scale, kk)
+        sw = sum(check_index_set(idx_np[0, h], idx_ref[h], pooled[h], where=f"cfg5 decode step {step} head {h}")
+                 for h in range(wl.Hkv))
+        sets = [idx_np[0, h] for h in range(wl.Hkv)]
+        e1 = max_abs(f64(o1[0]), ko.sparse_decode(f64(newq[0, 0]), f64(kc1[0]), f64(vc1[0]), sets, scale))
+        e2 = max_abs(f64(o2[0]), ko.sparse_decode(f64(newq[1, 0]), f64(kc2[0]), f64(vc2[0]), sets, scale))
+        print(f"  decode step {step} L={L} k={kk}: swaps {sw}, max-abs anchor {e1:.3e} reuse {e2:.3e}", flush=True)
+        assert max(e1, e2) <= TOL_OUT[BF16]
