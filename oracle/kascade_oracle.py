@@ -280,3 +280,59 @@ def kascade_layer_average(t_anchor0, t_anchor, t_reuse, n_layers=32, n_anchors=5
     (layer 0), n_anchors-1 other anchors, the rest reuse layers."""
     return (t_anchor0 + (n_anchors - 1) * t_anchor
             + (n_layers - n_anchors) * t_reuse) / n_layers
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.3, Algorithm 1: anchor-layer selection by dynamic programming
+# ----------------------------------------------------------------------------
+
+def segment_score(S, anchors):
+    """Objective the selection maximises: every layer l is served by the last anchor i <= l and
+    contributes S[i][l] (0-based layers; anchors ascending, anchors[0] == 0)."""
+    S = np.asarray(S, dtype=np.float64)
+    L = S.shape[0]
+    bounds = list(anchors) + [L]
+    return float(sum(S[i, l] for i, nxt in zip(bounds[:-1], bounds[1:]) for l in range(i, nxt)))
+
+
+def select_anchor_layers(S, n_anchors):
+    """Algorithm 1 in the paper's 1-based notation: dp[m][j] = best total similarity when the m-th
+    anchor sits at layer j (j = L+1 is the end sentinel) and the (m-1)-th anchor at some i < j serves
+    layers i..j-1.  Layer 1 is always the first anchor.  Ties keep the lowest i.
+    Returns the anchors as ascending 0-based layer numbers."""
+    S = np.asarray(S, dtype=np.float64)
+    L, M = S.shape[0], int(n_anchors)
+    if not (1 <= M <= L):
+        raise ValueError("need 1 <= n_anchors <= n_layers")
+    s1 = np.zeros((L + 2, L + 2))
+    s1[1:L + 1, 1:L + 1] = S
+    dp = np.full((M + 2, L + 2), -np.inf)
+    path = np.zeros((M + 2, L + 2), dtype=np.int64)
+    dp[1][1] = s1[1][1]
+    for m in range(2, M + 2):
+        for j in range(m, L + 2):
+            best, arg = -np.inf, 0
+            for i in range(m - 1, j):
+                val = dp[m - 1][i] + sum(s1[i][l] for l in range(i, j))
+                if val > best:
+                    best, arg = val, i
+            dp[m][j], path[m][j] = best, arg
+    anchors, j = [], L + 1
+    for m in range(M + 1, 1, -1):
+        j = int(path[m][j])
+        anchors.append(j - 1)
+    return anchors[::-1]
+
+
+def similarity_from_layers(pooled, index_sets):
+    """S[a][b] for a <= b from per-layer pooled distributions and Top-k sets of ONE query position:
+    pooled[l] is [n_seg, N] (one row per (sequence, key head)), index_sets[l] is [n_seg, k].
+    Eq. 3 per segment; Sec. 3.3 takes the minimum over the samples (here: over the segments).
+    Entries with a > b are 0 (an anchor only serves later layers)."""
+    n = len(pooled)
+    S = np.zeros((n, n))
+    for a in range(n):
+        for b in range(a, n):
+            sims = [topk_similarity(pooled[b][g], index_sets[a][g], index_sets[b][g]) for g in range(len(pooled[b]))]
+            S[a, b] = min(sims)
+    return S

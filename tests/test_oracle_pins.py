@@ -356,3 +356,50 @@ def test_table3_weighted_average_golden():
         got = ko.kascade_layer_average(float(a0), float(a), float(r_))
         # printed inputs carry +-0.005 each, weights sum to 1 -> +-0.005, plus the result's own rounding
         assert abs(got - float(avg)) <= 0.0101, (step, seqlen, pct, got, avg)
+
+
+# ------------------------------------------------------------------ Algorithm 1
+
+def brute_force_anchors(S, M):
+    L = S.shape[0]
+    best, best_val = None, -np.inf
+    for rest in itertools.combinations(range(1, L), M - 1):
+        anchors = (0,) + rest
+        val = sum(S[i, l] for i, nxt in zip(anchors, anchors[1:] + (L,)) for l in range(i, nxt))
+        if val > best_val + 1e-12:
+            best, best_val = list(anchors), val
+    return best, best_val
+
+
+@pytest.mark.parametrize("L,M,seed", [(6, 2, 0), (8, 3, 1), (9, 4, 2), (10, 5, 3), (7, 1, 4), (5, 5, 5)])
+def test_anchor_selection_matches_exhaustive_search(L, M, seed):
+    S = rng(200 + seed).random((L, L))
+    got = ko.select_anchor_layers(S, M)
+    ref, ref_val = brute_force_anchors(S, M)
+    assert got == ref
+    np.testing.assert_allclose(ko.segment_score(S, got), ref_val, atol=1e-12)
+    assert got[0] == 0 and len(got) == M and all(b > a for a, b in zip(got, got[1:]))
+
+
+def test_anchor_selection_on_block_structure():
+    # three blocks of mutually similar layers: anchors must sit on the block starts
+    L = 9
+    S = np.full((L, L), 0.2)
+    for lo, hi in ((0, 2), (2, 6), (6, 9)):
+        S[lo:hi, lo:hi] = 0.99
+    assert ko.select_anchor_layers(S, 3) == [0, 2, 6]
+    np.testing.assert_allclose(ko.segment_score(S, [0, 2, 6]), 9 * 0.99)
+
+
+def test_similarity_matrix_properties():
+    r = rng(77)
+    n_layers, n_seg, N, k = 4, 3, 60, 6
+    pooled = [ko.softmax_lastdim(2 * r.standard_normal((n_seg, N))) for _ in range(n_layers)]
+    sets = [np.stack([ko.select_topk(p[g], k) for g in range(n_seg)]) for p in pooled]
+    S = ko.similarity_from_layers(pooled, sets)
+    np.testing.assert_allclose(np.diag(S), 1.0)
+    assert (S[np.triu_indices(n_layers)] <= 1.0 + 1e-15).all() and (S >= 0).all()
+    assert (S[np.tril_indices(n_layers, -1)] == 0).all()
+    # hand check of one entry
+    g_vals = [pooled[2][g][sets[0][g]].sum() / pooled[2][g][sets[2][g]].sum() for g in range(n_seg)]
+    np.testing.assert_allclose(S[0, 2], min(g_vals))
