@@ -55,7 +55,8 @@ enum {
     KASCADE_OP_DECODE_ANCHOR = 0,
     KASCADE_OP_DECODE_REUSE = 1,
     KASCADE_OP_PREFILL_ANCHOR = 2,
-    KASCADE_OP_PREFILL_REUSE = 3
+    KASCADE_OP_PREFILL_REUSE = 3,
+    KASCADE_OP_DECODE_POOLED = 4
 };
 
 typedef struct {
@@ -136,6 +137,53 @@ int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k
                           const int64_t* idx_offsets, int64_t idx_total, const int32_t* idx_in,
                           int32_t n_anchor_heads, const int32_t* head_map, void* out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Calibration path (Sec. 3.3): which layers become anchors is decided once per model from how
+ * well one layer's Top-k set recovers a later layer's attention mass (Eq. 3).
+ *
+ * kascade_decode_pooled: passes 1-2 of the decode anchor layer only.  Writes the pooled
+ * post-softmax distribution (Eq. 1 per query head, mean over each GQA group, Sec. 3.4):
+ *   pooled_out [B,Hkv,pooled_pitch] fp32 (device), entries j < seqlens[b] written, the rest
+ *   untouched; pooled_pitch >= max_seqlen and a multiple of 4; 16-byte aligned base.
+ *   Workspace: kascade_workspace_bytes(KASCADE_OP_DECODE_POOLED, desc, max_seqlen, 0, 0).
+ */
+int kascade_decode_pooled(const kascade_desc* desc, const void* q, const void* k_cache,
+                          const int32_t* seqlens, int32_t max_seqlen, float* pooled_out,
+                          int64_t pooled_pitch, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/*
+ * Similarity of layer a's Top-k sets applied to layer b (Eq. 3), per (sequence, key head):
+ *   sim = sum_{j in idx_a[b, head_map[hk]]} pooled_b[b,hk,j] / sum_{j in idx_b[b,hk]} pooled_b[b,hk,j]
+ * over the first k_per_seq[b] entries of each set; entries that are negative or >= seqlens[b]
+ * are ignored; an empty denominator gives 1.  Sums are fp32 in a fixed order.
+ *   pooled_b [B,Hkv,pooled_pitch] fp32; idx_a [B,n_heads_a,k_max], idx_b [B,Hkv,k_max] int32;
+ *   head_map [Hkv] int32 into layer a's heads (Sec. 3.5) or NULL = identity (n_heads_a = Hkv)
+ *   sim_out  [B,Hkv] fp32 or NULL
+ *   sim_min  one fp32 or NULL: lowered to the smallest similarity of this call if that is below
+ *            its current value (Sec. 3.3 takes the minimum over the tokens of a prompt; start it
+ *            at 1).  All pointers are device memory.  At least one output is required.
+ */
+int kascade_topk_similarity(int32_t batch, int32_t n_kv_heads, const float* pooled_b,
+                            int64_t pooled_pitch, const int32_t* seqlens, const int32_t* k_per_seq,
+                            int32_t k_max, const int32_t* idx_a, int32_t n_heads_a,
+                            const int32_t* head_map, const int32_t* idx_b, float* sim_out,
+                            float* sim_min, void* hip_stream);
+
+/*
+ * Anchor-layer selection (Sec. 3.3, Algorithm 1).  HOST function, HOST pointers, no GPU work.
+ * similarity [n_layers,n_layers] row-major, entry (i,j), i <= j: similarity of layer i's Top-k
+ * set applied to layer j (entries below the diagonal are not read).  Chooses n_anchors layers,
+ * layer 0 always among them, such that every layer is served by the closest anchor at or before
+ * it and the sum of the served similarities is largest; among equal sums the earlier layer wins
+ * at each step of the recurrence.  Sums are fp64.
+ *   anchors_out [n_anchors] int32, ascending 0-based layer numbers
+ *   objective_out  the attained sum, or NULL
+ * Errors: NULL pointers, n_layers outside [1,4096], n_anchors outside [1,n_layers], NaN entries.
+ */
+int kascade_select_anchor_layers(const float* similarity, int32_t n_layers, int32_t n_anchors,
+                                 int32_t* anchors_out, double* objective_out);
 
 /*
  * Bytes of workspace the given op needs (0 is a valid answer).

@@ -19,11 +19,12 @@ LIB_PATH = os.path.join(_PKG_DIR, "libkascade.so")
 KASCADE_OK = 0
 KASCADE_F32, KASCADE_BF16 = 0, 1
 KASCADE_OUT_DENSE, KASCADE_OUT_SPARSE = 0, 1
-OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE = 0, 1, 2, 3
+OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE, OP_DECODE_POOLED = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
+    "kascade_decode_pooled", "kascade_topk_similarity", "kascade_select_anchor_layers",
     "kascade_profile_enable", "kascade_profile_calibrate", "kascade_profile_reset", "kascade_profile_kernels", "kascade_profile_read",
 ]
 
@@ -65,6 +66,13 @@ def load_library(path: Optional[str] = None):
     lib.kascade_prefill_anchor.restype = ctypes.c_int
     lib.kascade_prefill_reuse.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, i64, vp, i32, vp, vp, vp, sz, vp]
     lib.kascade_prefill_reuse.restype = ctypes.c_int
+    lib.kascade_decode_pooled.argtypes = [dp, vp, vp, vp, i32, vp, i64, vp, sz, vp]
+    lib.kascade_decode_pooled.restype = ctypes.c_int
+    lib.kascade_topk_similarity.argtypes = [i32, i32, vp, i64, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
+    lib.kascade_topk_similarity.restype = ctypes.c_int
+    lib.kascade_select_anchor_layers.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, ctypes.POINTER(i32),
+                                                 ctypes.POINTER(ctypes.c_double)]
+    lib.kascade_select_anchor_layers.restype = ctypes.c_int
     lib.kascade_workspace_bytes.argtypes = [i32, dp, i64, i64, i32]
     lib.kascade_workspace_bytes.restype = sz
     lib.kascade_status_string.argtypes = [i32]
@@ -272,3 +280,57 @@ def kascade_prefill_reuse(q, k, v, q_tile_tokens, k_per_tile, idx_offsets, idx_t
                                    int(n_anchor_heads), _ptr(head_map), _ptr(out), _ptr(workspace), nbytes, _stream())
     _check(st, "kascade_prefill_reuse")
     return out
+
+
+def kascade_decode_pooled(q, k_cache, seqlens, max_seqlen, pooled_out=None, workspace=None, softmax_scale=0.0,
+                          kv_layout="BHLD"):
+    """Returns pooled_out [B,Hkv,pitch] fp32 (pitch = max_seqlen rounded up to 4; columns past a
+    sequence's length are left as they were)."""
+    _need_gpu(q, k_cache, seqlens, pooled_out, workspace)
+    lib = load_library()
+    desc = decode_desc(q, k_cache, None, softmax_scale, kv_layout)
+    if pooled_out is None:
+        pooled_out = torch.zeros(q.shape[0], desc.n_kv_heads, (int(max_seqlen) + 3) // 4 * 4, dtype=torch.float32,
+                                 device=q.device)
+    if pooled_out.dtype != torch.float32 or not pooled_out.is_contiguous():
+        raise ValueError("pooled_out must be a contiguous fp32 [B, Hkv, pitch] tensor")
+    workspace, nbytes = _workspace(OP_DECODE_POOLED, desc, max_seqlen, 0, 0, q.device, workspace)
+    st = lib.kascade_decode_pooled(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(seqlens), int(max_seqlen),
+                                   _ptr(pooled_out), int(pooled_out.shape[2]), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_decode_pooled")
+    return pooled_out
+
+
+def kascade_topk_similarity(pooled_b, seqlens, k_per_seq, idx_a, idx_b, head_map=None, sim_out=None, sim_min=None):
+    """pooled_b [B,Hkv,pitch] fp32, idx_a [B,Ha,k_max], idx_b [B,Hkv,k_max] int32.
+    Returns (sim_out [B,Hkv] fp32, sim_min): sim_min (one fp32, device) is lowered in place when given."""
+    _need_gpu(pooled_b, seqlens, k_per_seq, idx_a, idx_b, head_map, sim_out, sim_min)
+    B, Hkv, pitch = pooled_b.shape
+    for t in (idx_a, idx_b):
+        if t.dtype != torch.int32 or not t.is_contiguous() or t.shape[2] != idx_b.shape[2]:
+            raise ValueError("index sets must be contiguous int32 [B, heads, k_max] tensors of one k_max")
+    if pooled_b.dtype != torch.float32 or not pooled_b.is_contiguous():
+        raise ValueError("pooled_b must be a contiguous fp32 [B, Hkv, pitch] tensor")
+    if sim_out is None:
+        sim_out = torch.empty(B, Hkv, dtype=torch.float32, device=pooled_b.device)
+    st = load_library().kascade_topk_similarity(int(B), int(Hkv), _ptr(pooled_b), int(pitch), _ptr(seqlens),
+                                                _ptr(k_per_seq), int(idx_b.shape[2]), _ptr(idx_a),
+                                                int(idx_a.shape[1]), _ptr(head_map), _ptr(idx_b), _ptr(sim_out),
+                                                _ptr(sim_min), _stream())
+    _check(st, "kascade_topk_similarity")
+    return sim_out, sim_min
+
+
+def kascade_select_anchor_layers(similarity, n_anchors):
+    """similarity: [L,L] array-like on the host (fp32).  Returns (anchors list, objective)."""
+    import numpy as np
+    S = np.ascontiguousarray(np.asarray(similarity, dtype=np.float32))
+    if S.ndim != 2 or S.shape[0] != S.shape[1]:
+        raise ValueError("similarity must be a square matrix")
+    n = int(n_anchors)
+    anchors = (ctypes.c_int32 * max(n, 1))()
+    obj = ctypes.c_double()
+    st = load_library().kascade_select_anchor_layers(S.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), int(S.shape[0]),
+                                                     n, anchors, ctypes.byref(obj))
+    _check(st, "kascade_select_anchor_layers")
+    return list(anchors[:n]), obj.value

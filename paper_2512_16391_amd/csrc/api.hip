@@ -144,10 +144,11 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // Events are created on demand and kept until profiling is disabled; with profiling off
 // the library creates nothing.
 enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
-                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_COUNT };
+                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
-    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel"};
+    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel",
+    "similarity"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
@@ -263,6 +264,8 @@ size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max
             return carve_decode_reuse(s, plan_gather(s, k_or_idx_total), nullptr).bytes;
         case KASCADE_OP_DECODE_ANCHOR:
             return carve_decode_anchor(s, plan_stream(s, max_seqlen), plan_gather(s, k_or_idx_total), max_seqlen, nullptr).bytes;
+        case KASCADE_OP_DECODE_POOLED:
+            return carve_decode_anchor(s, plan_stream(s, max_seqlen), plan_gather(s, 1), max_seqlen, nullptr).bytes;
         default:
             return 0;
     }
@@ -431,6 +434,97 @@ int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k
     PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
     a.idx = idx_in; a.head_map = head_map; a.n_src_heads = n_anchor_heads;
     return timed(K_PF_SPARSE, stream, [&] { return launch_prefill_attend(s, a, true, true, stream); });
+}
+
+// ---- calibration path (Sec. 3.3): pooled distributions, set similarity, anchor selection ----
+
+int kascade_decode_pooled(const kascade_desc* desc, const void* q, const void* k_cache, const int32_t* seqlens,
+                          int32_t max_seqlen, float* pooled_out, int64_t pooled_pitch, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    int st = check_desc(desc, false);
+    if (st != KASCADE_OK) return st;
+    if (!q || !k_cache || !seqlens || !pooled_out) return KASCADE_INVALID_ARG;
+    if (max_seqlen <= 0 || pooled_pitch < max_seqlen) return KASCADE_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(pooled_out) || pooled_pitch % 4) return KASCADE_MISALIGNED;
+    const Shape s = make_shape(desc);
+    const DecodePlan sp = plan_stream(s, max_seqlen);
+    const DecodeAnchorWs ws = carve_decode_anchor(s, sp, plan_gather(s, 1), max_seqlen, workspace);
+    if (!workspace || workspace_bytes < ws.bytes) return KASCADE_WORKSPACE_TOO_SMALL;
+    if (!aligned16(workspace)) return KASCADE_MISALIGNED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    DecodeRowsArgs a = {};
+    a.q = q; a.k = k_cache; a.v = nullptr; a.seqlens = seqlens;
+    a.logits = ws.logits; a.logit_pitch = ws.pitch;
+    a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = nullptr; a.hist11 = ws.hist11;
+    st = timed(K_STREAM, stream, [&] { return launch_decode_rows(s, sp, a, false, false, true, stream); });
+    if (st != KASCADE_OK) return st;
+    DecodePoolArgs pa = {};
+    pa.seqlens = seqlens; pa.k_per_seq = seqlens; pa.k_max = max_seqlen; pa.recent_window = 0;
+    pa.logits = ws.logits; pa.logit_pitch = ws.pitch; pa.part_ml = ws.st_ml; pa.pooled = pooled_out;
+    pa.pooled_pitch = pooled_pitch; pa.hist11 = ws.hist11; pa.max_seqlen = max_seqlen;
+    return timed(K_POOL, stream, [&] { return launch_decode_pool(s, sp.n_chunks, pa, stream); });
+}
+
+int kascade_topk_similarity(int32_t batch, int32_t n_kv_heads, const float* pooled_b, int64_t pooled_pitch,
+                            const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_a,
+                            int32_t n_heads_a, const int32_t* head_map, const int32_t* idx_b, float* sim_out,
+                            float* sim_min, void* hip_stream) {
+    if (batch <= 0 || n_kv_heads <= 0 || n_heads_a <= 0 || k_max <= 0 || pooled_pitch <= 0) return KASCADE_INVALID_ARG;
+    if (batch > 65535) return KASCADE_INVALID_ARG;
+    if (!pooled_b || !seqlens || !k_per_seq || !idx_a || !idx_b) return KASCADE_INVALID_ARG;
+    if (!sim_out && !sim_min) return KASCADE_INVALID_ARG;
+    if (!head_map && n_heads_a != n_kv_heads) return KASCADE_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    SimilarityArgs a = {};
+    a.B = batch; a.Hkv = n_kv_heads; a.pooled = pooled_b; a.pitch = pooled_pitch; a.seqlens = seqlens;
+    a.k_per_seq = k_per_seq; a.k_max = k_max; a.idx_a = idx_a; a.n_heads_a = n_heads_a; a.head_map = head_map;
+    a.idx_b = idx_b; a.sim_out = sim_out; a.sim_min = sim_min;
+    return timed(K_SIMILARITY, stream, [&] { return launch_similarity(a, stream); });
+}
+
+int kascade_select_anchor_layers(const float* similarity, int32_t n_layers, int32_t n_anchors, int32_t* anchors_out,
+                                 double* objective_out) {
+    if (!similarity || !anchors_out) return KASCADE_INVALID_ARG;
+    if (n_layers <= 0 || n_layers > 4096 || n_anchors <= 0 || n_anchors > n_layers) return KASCADE_INVALID_ARG;
+    const int L = n_layers, M = n_anchors;
+    for (int64_t i = 0; i < (int64_t)L * L; ++i)
+        if (!(similarity[i] == similarity[i])) return KASCADE_INVALID_ARG;   // NaN
+    // serve[i*(L+1) + j]: total similarity of the layers i..j-1 when anchor i serves them
+    std::vector<double> serve((size_t)L * (L + 1), 0.0);
+    for (int i = 0; i < L; ++i) {
+        double run = 0.0;
+        for (int j = i; j < L; ++j) {
+            run += (double)similarity[(size_t)i * L + j];
+            serve[(size_t)i * (L + 1) + j + 1] = run;
+        }
+    }
+    // best[m*(L+1) + j]: best total with m anchors placed, the next segment starting at layer j
+    // (j = L: every layer served).  The first anchor is layer 0.
+    const double kNone = -INFINITY;
+    std::vector<double> best((size_t)(M + 1) * (L + 1), kNone);
+    std::vector<int32_t> from((size_t)(M + 1) * (L + 1), -1);
+    for (int j = 1; j <= L; ++j) { best[(size_t)1 * (L + 1) + j] = serve[j]; from[(size_t)1 * (L + 1) + j] = 0; }
+    for (int m = 2; m <= M; ++m) {
+        for (int j = m; j <= L; ++j) {
+            double top = kNone; int arg = -1;
+            for (int i = m - 1; i < j; ++i) {               // i = layer of the m-th anchor
+                const double prev = best[(size_t)(m - 1) * (L + 1) + i];
+                if (prev == kNone) continue;
+                const double val = prev + serve[(size_t)i * (L + 1) + j];
+                if (val > top) { top = val; arg = i; }      // ties keep the lowest layer
+            }
+            best[(size_t)m * (L + 1) + j] = top; from[(size_t)m * (L + 1) + j] = arg;
+        }
+    }
+    int j = L;
+    for (int m = M; m >= 1; --m) {
+        const int i = from[(size_t)m * (L + 1) + j];
+        if (i < 0) return KASCADE_INVALID_ARG;
+        anchors_out[m - 1] = i;
+        j = i;
+    }
+    if (objective_out) *objective_out = best[(size_t)M * (L + 1) + L];
+    return KASCADE_OK;
 }
 
 }  // extern "C"

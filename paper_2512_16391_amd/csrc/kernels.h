@@ -94,6 +94,23 @@ struct TopkArgs {
 };
 hipError_t launch_topk_decode(const Shape& s, const TopkArgs& a, hipStream_t st);
 
+// ---- calibration: Top-k set similarity (Eq. 3) ----------------------------------------
+struct SimilarityArgs {
+    int B, Hkv;
+    const float* pooled;          // layer b: [B, Hkv, pitch]
+    int64_t pitch;
+    const int32_t* seqlens;
+    const int32_t* k_per_seq;
+    int32_t k_max;
+    const int32_t* idx_a;         // [B, n_heads_a, k_max]
+    int32_t n_heads_a;
+    const int32_t* head_map;      // [Hkv] into layer a's heads, or null
+    const int32_t* idx_b;         // [B, Hkv, k_max]
+    float* sim_out;               // [B, Hkv] or null
+    float* sim_min;               // one float, min-updated, or null
+};
+hipError_t launch_similarity(const SimilarityArgs& a, hipStream_t st);
+
 // ---- prefill -----------------------------------------------------------------------
 struct PrefillArgs {
     const void* q;                // [S, Hq, D] per q_stride

@@ -89,7 +89,8 @@ def make_decode_workload(name, config_id, n_layers, B, Hq, Hkv, d, dtype, seqlen
                          boost=3.0, q_boost=1.0, device="cpu", base_seed=BASE_SEED,
                          keep_hitters=True):
     """n_layers independent (q, K, V) triples over one batch of sequences, with
-    hitter positions drifting from layer to layer."""
+    hitter positions drifting from layer to layer.  `overlap` is one fraction or a
+    per-layer list (entry l: fraction of layer l-1's hitters that layer l keeps)."""
     device = torch.device(device)
     Lmax = int(Lmax if Lmax is not None else max(seqlens))
     G = Hq // Hkv
@@ -110,7 +111,8 @@ def make_decode_workload(name, config_id, n_layers, B, Hq, Hkv, d, dtype, seqlen
             hit_b = []
             for hk in range(Hkv):
                 u = _unit(gen, d, device)
-                pos = _next_hitters(gen, prev[b][hk], L, n_hitters, overlap, device)
+                ov = overlap[layer] if isinstance(overlap, (list, tuple)) else overlap
+                pos = _next_hitters(gen, prev[b][hk], L, n_hitters, ov, device)
                 prev[b][hk] = pos
                 kb[hk, pos] += boost * u
                 q[b, hk * G:(hk + 1) * G] += q_boost * u
@@ -271,3 +273,13 @@ def config5_prefill(device="cuda", layers=(0, 1, 2, 3), S=131072, T=32, decode_s
             q[:, hk * G:(hk + 1) * G] += us[hk]
         wl.layers.append(PrefillLayer(q.to(torch.bfloat16), k, v))
     return wl
+
+
+def layer_stack(device="cpu", n_layers=8, block_starts=(0, 3, 5), B=2, Hq=8, Hkv=2, d=64, dtype=torch.float32,
+                seqlens=(3000, 2500), k=96, n_hitters=32, within=0.95):
+    """Calibration-shaped stack (Sec. 3.3): consecutive layers inside a block keep nearly all
+    heavy-hitter positions, a new block redraws them, so the similarity matrix is block
+    structured and the best anchors are the block starts."""
+    overlap = [0.0 if l in block_starts else within for l in range(n_layers)]
+    return make_decode_workload(f"stack-{n_layers}-layers", 6, n_layers, B, Hq, Hkv, d, dtype, list(seqlens),
+                                [k] * B, n_hitters, overlap, 0, boost=12.0, q_boost=3.0, device=device)

@@ -1,0 +1,71 @@
+"""Anchor-layer selection (Sec. 3.3, Algorithm 1): the library's host routine against the oracle's
+transcription of the recurrence and against exhaustive search.  Runs without a GPU."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import kascade_oracle as ko
+from paper_2512_16391_amd import binding as kb
+
+
+def exhaustive(S, M):
+    L = S.shape[0]
+    best, best_val = None, -np.inf
+    for rest in itertools.combinations(range(1, L), M - 1):
+        anchors = (0,) + rest
+        val = sum(float(S[i, l]) for i, nxt in zip(anchors, anchors[1:] + (L,)) for l in range(i, nxt))
+        if val > best_val + 1e-9:
+            best, best_val = list(anchors), val
+    return best, best_val
+
+
+@pytest.mark.parametrize("L,M,seed", [(1, 1, 0), (6, 2, 1), (8, 3, 2), (12, 5, 3), (10, 10, 4), (9, 1, 5), (14, 4, 6)])
+def test_library_selection_matches_oracle_and_exhaustive_search(L, M, seed):
+    S = np.random.default_rng(seed).random((L, L)).astype(np.float32)
+    got, obj = kb.kascade_select_anchor_layers(S, M)
+    assert got == ko.select_anchor_layers(S.astype(np.float64), M)
+    ref, ref_val = exhaustive(S.astype(np.float64), M)
+    assert got == ref
+    np.testing.assert_allclose(obj, ref_val, rtol=0, atol=1e-9)
+    np.testing.assert_allclose(obj, ko.segment_score(S, got), rtol=0, atol=1e-9)
+
+
+def test_library_selection_model_sized():
+    # 36 layers, 5 anchors as in the paper's Qwen3-8B setting; 32 layers, 5 anchors as Llama-3.1-8B
+    for L, M, seed in ((36, 5, 11), (32, 5, 12)):
+        r = np.random.default_rng(seed)
+        # similarity decays with layer distance, plus noise: a banded structure like Fig. 3
+        i, j = np.meshgrid(np.arange(L), np.arange(L), indexing="ij")
+        S = (np.exp(-np.abs(i - j) / 6.0) * (0.9 + 0.1 * r.random((L, L)))).astype(np.float32)
+        got, obj = kb.kascade_select_anchor_layers(S, M)
+        assert got == ko.select_anchor_layers(S.astype(np.float64), M)
+        assert got[0] == 0 and all(b > a for a, b in zip(got, got[1:]))
+        np.testing.assert_allclose(obj, ko.segment_score(S, got), atol=1e-9)
+
+
+def test_library_selection_ties_keep_earliest_layer():
+    S = np.ones((7, 7), dtype=np.float32)            # every choice scores the same
+    got, obj = kb.kascade_select_anchor_layers(S, 3)
+    assert got == ko.select_anchor_layers(S.astype(np.float64), 3)
+    assert obj == 7.0
+
+
+def test_library_selection_ignores_entries_below_the_diagonal():
+    r = np.random.default_rng(3)
+    S = r.random((9, 9)).astype(np.float32)
+    T = S.copy()
+    T[np.tril_indices(9, -1)] = 1e6
+    assert kb.kascade_select_anchor_layers(S, 4) == kb.kascade_select_anchor_layers(T, 4)
+
+
+def test_library_selection_rejects_bad_arguments():
+    S = np.eye(4, dtype=np.float32)
+    for M in (0, 5, -1):
+        with pytest.raises(kb.KascadeError):
+            kb.kascade_select_anchor_layers(S, M)
+    bad = S.copy(); bad[0, 2] = np.nan
+    with pytest.raises(kb.KascadeError):
+        kb.kascade_select_anchor_layers(bad, 2)
+    with pytest.raises(ValueError):
+        kb.kascade_select_anchor_layers(np.zeros((3, 4), dtype=np.float32), 2)

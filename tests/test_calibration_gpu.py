@@ -1,0 +1,121 @@
+"""GPU parity of the calibration path (Sec. 3.3): pooled distributions, Top-k set similarity
+(Eq. 3) and the anchor layers chosen from the resulting matrix, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kascade_oracle as ko
+from paper_2512_16391_amd import binding, workloads
+from parity_utils import f64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def i32(x):
+    return torch.tensor(x, dtype=torch.int32, device=DEV)
+
+
+def oracle_layer(layer, wl):
+    """Per (sequence, key head) pooled distribution and Top-k set of one layer."""
+    pooled, sets = [], []
+    for b in range(wl.B):
+        L, k = wl.seqlens[b], wl.k_per_seq[b]
+        idx, a = ko.decode_anchor_indices(f64(layer.q[b]), f64(layer.k[b, :, :L]), ko.default_scale(wl.d), k)
+        pooled.append(a)
+        sets.append(idx)
+    return pooled, sets
+
+
+@pytest.mark.parametrize("dtype,tol", [(torch.float32, 2e-5), (torch.bfloat16, 2e-5)])
+def test_similarity_matrix_and_anchor_choice(dtype, tol):
+    print(f"case calibration stack dtype={dtype}", flush=True)
+    starts = (0, 3, 5)
+    wl = workloads.layer_stack("cpu", n_layers=8, block_starts=starts, dtype=dtype)
+    n, B, Hkv = len(wl.layers), wl.B, wl.Hkv
+    Lmax, k_max = max(wl.seqlens), max(wl.k_per_seq)
+    lens, ks = i32(wl.seqlens), i32(wl.k_per_seq)
+
+    # device: pooled distribution and fresh Top-k set of every layer
+    pooled_d, idx_d = [], []
+    for layer in wl.layers:
+        q, k, v = layer.q.to(DEV), layer.k.to(DEV), layer.v.to(DEV)
+        pooled_d.append(binding.kascade_decode_pooled(q, k, lens, Lmax))
+        idx, _ = binding.kascade_decode_anchor(q, k, v, lens, ks, Lmax, k_max)
+        idx_d.append(idx)
+    # oracle: the same, from the definition
+    ref = [oracle_layer(layer, wl) for layer in wl.layers]
+    for l in range(n):
+        for b in range(B):
+            L = wl.seqlens[b]
+            got = pooled_d[l][b, :, :L].double().cpu().numpy()
+            assert np.abs(got - ref[l][0][b]).max() <= 1e-6 + 1e-4 * ref[l][0][b].max(), (l, b)
+
+    # similarity matrix: minimum over the (sequence, key head) samples, per layer pair
+    S_dev = np.zeros((n, n), dtype=np.float32)
+    S_ref = np.zeros((n, n))
+    for a in range(n):
+        for b_ in range(a, n):
+            smin = torch.ones(1, dtype=torch.float32, device=DEV)
+            sim, _ = binding.kascade_topk_similarity(pooled_d[b_], lens, ks, idx_d[a], idx_d[b_], sim_min=smin)
+            sim = sim.cpu().numpy()
+            want = np.array([[ko.topk_similarity(ref[b_][0][s][h], ref[a][1][s][h], ref[b_][1][s][h])
+                              for h in range(Hkv)] for s in range(B)])
+            assert np.abs(sim - want).max() <= tol, (a, b_, np.abs(sim - want).max())
+            assert float(smin.item()) == float(sim.min())
+            S_dev[a, b_], S_ref[a, b_] = smin.item(), want.min()
+    np.testing.assert_allclose(np.diag(S_dev), 1.0, atol=1e-6)
+    # block structure of the recipe shows up: inside a block high, across blocks low
+    assert S_dev[0, 2] > 0.6 and S_dev[3, 4] > 0.6 and S_dev[5, 7] > 0.6
+    assert S_dev[0, 3] < 0.3 and S_dev[2, 5] < 0.3
+
+    got, obj = binding.kascade_select_anchor_layers(S_dev, len(starts))
+    want = ko.select_anchor_layers(S_ref, len(starts))
+    assert got == want == list(starts)
+    np.testing.assert_allclose(obj, ko.segment_score(S_ref, want), atol=n * tol)
+
+
+def test_similarity_with_head_map_partial_sets_and_running_minimum():
+    print("case similarity head map", flush=True)
+    rs = np.random.default_rng(5)
+    B, Hkv, Ha, pitch, k_max = 3, 4, 2, 1000, 96
+    lens, ks = [1000, 37, 512], [96, 5, 0]
+    pooled = rs.random((B, Hkv, pitch)).astype(np.float32)
+    idx_a = np.full((B, Ha, k_max), -1, dtype=np.int32)
+    idx_b = np.full((B, Hkv, k_max), -1, dtype=np.int32)
+    for b in range(B):
+        for h in range(Ha):
+            idx_a[b, h, : ks[b]] = rs.choice(lens[b], ks[b], replace=False)
+        for h in range(Hkv):
+            idx_b[b, h, : ks[b]] = rs.choice(lens[b], ks[b], replace=False)
+    idx_a[0, 1, 3] = -1          # ignored entries: negative and beyond the sequence
+    idx_a[0, 0, 7] = 5000
+    head_map = [1, 0, 0, 1]
+    smin = torch.full((1,), 0.25, dtype=torch.float32, device=DEV)
+    sim, _ = binding.kascade_topk_similarity(torch.from_numpy(pooled).to(DEV), i32(lens), i32(ks),
+                                             torch.from_numpy(idx_a).to(DEV), torch.from_numpy(idx_b).to(DEV),
+                                             head_map=i32(head_map), sim_min=smin)
+    sim = sim.cpu().numpy()
+    for b in range(B):
+        for h in range(Hkv):
+            ia = [j for j in idx_a[b, head_map[h], : ks[b]] if 0 <= j < lens[b]]
+            ib = idx_b[b, h, : ks[b]]
+            want = 1.0 if ks[b] == 0 else ko.topk_similarity(pooled[b, h].astype(np.float64), np.array(ia, dtype=np.int64), ib)
+            assert abs(sim[b, h] - want) <= 1e-5 * max(1.0, want), (b, h, sim[b, h], want)
+    assert smin.item() == min(0.25, float(sim.min()))
+
+
+def test_calibration_entries_reject_bad_arguments():
+    q = torch.zeros(1, 8, 64, device=DEV)
+    k = torch.zeros(1, 2, 128, 64, device=DEV)
+    lens = i32([128])
+    with pytest.raises(binding.KascadeError):       # pitch shorter than the sequence bound
+        binding.kascade_decode_pooled(q, k, lens, 128, pooled_out=torch.zeros(1, 2, 64, device=DEV))
+    with pytest.raises(binding.KascadeError):       # workspace too small
+        binding.kascade_decode_pooled(q, k, lens, 128, workspace=torch.zeros(256, dtype=torch.uint8, device=DEV))
+    pooled = torch.zeros(1, 2, 128, device=DEV)
+    idx = torch.zeros(1, 2, 8, dtype=torch.int32, device=DEV)
+    idx3 = torch.zeros(1, 3, 8, dtype=torch.int32, device=DEV)
+    with pytest.raises(binding.KascadeError):       # head counts differ and no head map
+        binding.kascade_topk_similarity(pooled, lens, i32([8]), idx3, idx)
