@@ -336,3 +336,37 @@ def similarity_from_layers(pooled, index_sets):
             sims = [topk_similarity(pooled[b][g], index_sets[a][g], index_sets[b][g]) for g in range(len(pooled[b]))]
             S[a, b] = min(sims)
     return S
+
+
+def weight_similarity(S, w):
+    """Sec. 3.3, layer importance: entry (i, j) is scaled by the weight of the SERVED layer j."""
+    return np.asarray(S, dtype=np.float64) * np.asarray(w, dtype=np.float64)[None, :]
+
+
+def layer_importance(x, y):
+    """Sec. 3.3: 1 - cosine similarity between the input x and the output y of a layer's
+    attention block, one value per row (token)."""
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    cos = (x * y).sum(-1) / (np.sqrt((x * x).sum(-1)) * np.sqrt((y * y).sum(-1)))
+    return 1.0 - cos
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.5: head map from head-level similarity
+# ----------------------------------------------------------------------------
+
+def head_similarity(pooled_b, sets_a, sets_b):
+    """Eq. 3 at head level for ONE sample: pooled_b [H, N] of the reuse layer, sets_a [Ha, k] of
+    the anchor layer, sets_b [H, k] of the reuse layer.  Entry (h, h') = similarity of anchor head
+    h' used for reuse head h."""
+    H, Ha = len(pooled_b), len(sets_a)
+    return np.array([[topk_similarity(pooled_b[h], sets_a[g], sets_b[h]) for g in range(Ha)] for h in range(H)])
+
+
+def head_map_from_similarity(sims):
+    """sims [n_samples, H, Ha].  Each reuse head takes the anchor head with the largest mean
+    similarity over the samples (many-to-one allowed); ties go to the lower anchor head.
+    Reading: the paper aggregates over its development set without naming the statistic."""
+    mean = np.asarray(sims, dtype=np.float64).mean(axis=0)
+    return np.argmax(mean, axis=1).astype(np.int64), mean

@@ -403,3 +403,55 @@ def test_similarity_matrix_properties():
     # hand check of one entry
     g_vals = [pooled[2][g][sets[0][g]].sum() / pooled[2][g][sets[2][g]].sum() for g in range(n_seg)]
     np.testing.assert_allclose(S[0, 2], min(g_vals))
+
+
+def test_layer_weighting_scales_the_served_layer():
+    S = np.arange(16, dtype=np.float64).reshape(4, 4)
+    w = np.array([1.0, 0.5, 0.25, 2.0])
+    W = ko.weight_similarity(S, w)
+    for i in range(4):
+        for j in range(4):
+            assert W[i, j] == S[i, j] * w[j]
+    # weights that vanish on the late layers pull the anchors towards the early ones
+    L = 8
+    base = np.full((L, L), 0.5) + 0.5 * np.eye(L)
+    early = np.array([1, 1, 1, 1, 1e-3, 1e-3, 1e-3, 1e-3])
+    assert ko.select_anchor_layers(ko.weight_similarity(base, early), 4) == [0, 1, 2, 3]
+    assert ko.select_anchor_layers(ko.weight_similarity(base, early[::-1].copy()), 5) == [0, 4, 5, 6, 7]
+
+
+def test_layer_importance_closed_forms():
+    x = np.array([[1.0, 0.0], [1.0, 0.0], [1.0, 1.0], [2.0, 0.0]])
+    y = np.array([[3.0, 0.0], [0.0, 5.0], [1.0, 0.0], [-1.0, 0.0]])
+    np.testing.assert_allclose(ko.layer_importance(x, y), [0.0, 1.0, 1.0 - 1.0 / np.sqrt(2.0), 2.0], atol=1e-15)
+
+
+def test_head_map_recovers_planted_permutation_and_beats_every_other_map():
+    r = rng(91)
+    H, N, k, n_samples = 4, 200, 10, 3
+    perm = [2, 0, 3, 1]                       # reuse head h behaves like anchor head perm[h]
+    sims = []
+    for _ in range(n_samples):
+        pooled_a = ko.softmax_lastdim(3 * r.standard_normal((H, N)))
+        pooled_b = np.stack([ko.softmax_lastdim(np.log(pooled_a[perm[h]]) + 0.1 * r.standard_normal(N)) for h in range(H)])
+        sets_a = np.stack([ko.select_topk(p, k) for p in pooled_a])
+        sets_b = np.stack([ko.select_topk(p, k) for p in pooled_b])
+        sims.append(ko.head_similarity(pooled_b, sets_a, sets_b))
+    hm, mean = ko.head_map_from_similarity(np.stack(sims))
+    assert hm.tolist() == perm
+    # exhaustive: no assignment of anchor heads to reuse heads has a larger total mean similarity
+    best = max(itertools.product(range(H), repeat=H), key=lambda m: sum(mean[h, m[h]] for h in range(H)))
+    assert list(best) == hm.tolist()
+    # entry check by hand
+    h, g = 1, 3
+    want = pooled_b[h][sets_a[g]].sum() / pooled_b[h][sets_b[h]].sum()
+    np.testing.assert_allclose(sims[-1][h, g], want)
+
+
+def test_head_map_many_to_one_and_ties():
+    sims = np.zeros((2, 3, 2))
+    sims[:, 0] = [0.9, 0.1]
+    sims[:, 1] = [0.8, 0.2]
+    sims[:, 2] = [0.5, 0.5]                   # tie -> lower anchor head
+    hm, _ = ko.head_map_from_similarity(sims)
+    assert hm.tolist() == [0, 0, 0]
