@@ -178,12 +178,49 @@ int kascade_topk_similarity(int32_t batch, int32_t n_kv_heads, const float* pool
  * layer 0 always among them, such that every layer is served by the closest anchor at or before
  * it and the sum of the served similarities is largest; among equal sums the earlier layer wins
  * at each step of the recurrence.  Sums are fp64.
+ *   layer_weights [n_layers] or NULL: importance of each layer; entry (i,j) is multiplied by
+ *                 layer_weights[j], the weight of the served layer (Sec. 3.3)
  *   anchors_out [n_anchors] int32, ascending 0-based layer numbers
  *   objective_out  the attained sum, or NULL
  * Errors: NULL pointers, n_layers outside [1,4096], n_anchors outside [1,n_layers], NaN entries.
  */
-int kascade_select_anchor_layers(const float* similarity, int32_t n_layers, int32_t n_anchors,
-                                 int32_t* anchors_out, double* objective_out);
+int kascade_select_anchor_layers(const float* similarity, const float* layer_weights,
+                                 int32_t n_layers, int32_t n_anchors, int32_t* anchors_out,
+                                 double* objective_out);
+
+/*
+ * Head-level similarity (Sec. 3.5, Eq. 3 per pair of heads): for every sequence b, every key
+ * head hk of the reuse layer and every key head ha of the anchor layer,
+ *   sim_out[b,hk,ha] = sum_{j in idx_a[b,ha]} pooled_b[b,hk,j] / sum_{j in idx_b[b,hk]} pooled_b[b,hk,j]
+ * with the same conventions as kascade_topk_similarity.  sim_out [B,Hkv,n_heads_a] fp32 (device).
+ */
+int kascade_head_similarity(int32_t batch, int32_t n_kv_heads, const float* pooled_b,
+                            int64_t pooled_pitch, const int32_t* seqlens, const int32_t* k_per_seq,
+                            int32_t k_max, const int32_t* idx_a, int32_t n_heads_a,
+                            const int32_t* idx_b, float* sim_out, void* hip_stream);
+
+/*
+ * Head map of a reuse layer (Sec. 3.5): each of its key heads takes the anchor-layer head with
+ * the largest mean similarity over the samples; several heads may take the same one; equal means
+ * go to the lower anchor head.  (The paper aggregates over its development set without naming the
+ * statistic; the mean is this library's reading.)
+ *   sim [n_samples,Hkv,n_heads_a] fp32 (device), e.g. kascade_head_similarity outputs stacked
+ *   mean_out [Hkv,n_heads_a] fp32 (device) or NULL;  head_map_out [Hkv] int32 (device), the
+ *   array the reuse entry points take as `head_map`.
+ */
+int kascade_head_map(int32_t n_samples, int32_t n_kv_heads, int32_t n_heads_a, const float* sim,
+                     float* mean_out, int32_t* head_map_out, void* hip_stream);
+
+/*
+ * Layer importance (Sec. 3.3): w_out[r] = 1 - cosine similarity of row r of x (input of a
+ * layer's attention block) and row r of y (its output); fp32 accumulation.  Averaging the rows
+ * of a layer gives the weight passed to kascade_select_anchor_layers.
+ *   x, y [n_rows,n_cols] of `dtype` (KASCADE_F32 / KASCADE_BF16), row strides in elements;
+ *   w_out [n_rows] fp32.  All device memory.  A zero row gives NaN.
+ */
+int kascade_layer_importance(const void* x, const void* y, int64_t n_rows, int32_t n_cols,
+                             int32_t dtype, int64_t x_row_stride, int64_t y_row_stride,
+                             float* w_out, void* hip_stream);
 
 /*
  * Bytes of workspace the given op needs (0 is a valid answer).

@@ -25,6 +25,7 @@ EXPORTS = [
     "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
     "kascade_decode_pooled", "kascade_topk_similarity", "kascade_select_anchor_layers",
+    "kascade_head_similarity", "kascade_head_map", "kascade_layer_importance",
     "kascade_profile_enable", "kascade_profile_calibrate", "kascade_profile_reset", "kascade_profile_kernels", "kascade_profile_read",
 ]
 
@@ -70,8 +71,15 @@ def load_library(path: Optional[str] = None):
     lib.kascade_decode_pooled.restype = ctypes.c_int
     lib.kascade_topk_similarity.argtypes = [i32, i32, vp, i64, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp]
     lib.kascade_topk_similarity.restype = ctypes.c_int
-    lib.kascade_select_anchor_layers.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, ctypes.POINTER(i32),
+    fpp = ctypes.POINTER(ctypes.c_float)
+    lib.kascade_select_anchor_layers.argtypes = [fpp, fpp, i32, i32, ctypes.POINTER(i32),
                                                  ctypes.POINTER(ctypes.c_double)]
+    lib.kascade_head_similarity.argtypes = [i32, i32, vp, i64, vp, vp, i32, vp, i32, vp, vp, vp]
+    lib.kascade_head_similarity.restype = ctypes.c_int
+    lib.kascade_head_map.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+    lib.kascade_head_map.restype = ctypes.c_int
+    lib.kascade_layer_importance.argtypes = [vp, vp, i64, i32, i32, i64, i64, vp, vp]
+    lib.kascade_layer_importance.restype = ctypes.c_int
     lib.kascade_select_anchor_layers.restype = ctypes.c_int
     lib.kascade_workspace_bytes.argtypes = [i32, dp, i64, i64, i32]
     lib.kascade_workspace_bytes.restype = sz
@@ -321,8 +329,9 @@ def kascade_topk_similarity(pooled_b, seqlens, k_per_seq, idx_a, idx_b, head_map
     return sim_out, sim_min
 
 
-def kascade_select_anchor_layers(similarity, n_anchors):
-    """similarity: [L,L] array-like on the host (fp32).  Returns (anchors list, objective)."""
+def kascade_select_anchor_layers(similarity, n_anchors, layer_weights=None):
+    """similarity: [L,L] array-like on the host (fp32); layer_weights [L] or None.
+    Returns (anchors list, objective)."""
     import numpy as np
     S = np.ascontiguousarray(np.asarray(similarity, dtype=np.float32))
     if S.ndim != 2 or S.shape[0] != S.shape[1]:
@@ -330,7 +339,57 @@ def kascade_select_anchor_layers(similarity, n_anchors):
     n = int(n_anchors)
     anchors = (ctypes.c_int32 * max(n, 1))()
     obj = ctypes.c_double()
-    st = load_library().kascade_select_anchor_layers(S.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), int(S.shape[0]),
-                                                     n, anchors, ctypes.byref(obj))
+    fpp = ctypes.POINTER(ctypes.c_float)
+    w = None
+    if layer_weights is not None:
+        w = np.ascontiguousarray(np.asarray(layer_weights, dtype=np.float32))
+        if w.shape != (S.shape[0],):
+            raise ValueError("layer_weights must have one entry per layer")
+    st = load_library().kascade_select_anchor_layers(S.ctypes.data_as(fpp), w.ctypes.data_as(fpp) if w is not None else None,
+                                                     int(S.shape[0]), n, anchors, ctypes.byref(obj))
     _check(st, "kascade_select_anchor_layers")
     return list(anchors[:n]), obj.value
+
+
+def kascade_head_similarity(pooled_b, seqlens, k_per_seq, idx_a, idx_b, sim_out=None):
+    """Returns sim_out [B,Hkv,Ha] fp32: every anchor-layer head's set applied to every head of layer b."""
+    _need_gpu(pooled_b, seqlens, k_per_seq, idx_a, idx_b, sim_out)
+    B, Hkv, pitch = pooled_b.shape
+    for t in (idx_a, idx_b):
+        if t.dtype != torch.int32 or not t.is_contiguous() or t.shape[2] != idx_b.shape[2]:
+            raise ValueError("index sets must be contiguous int32 [B, heads, k_max] tensors of one k_max")
+    if pooled_b.dtype != torch.float32 or not pooled_b.is_contiguous():
+        raise ValueError("pooled_b must be a contiguous fp32 [B, Hkv, pitch] tensor")
+    Ha = idx_a.shape[1]
+    if sim_out is None:
+        sim_out = torch.empty(B, Hkv, Ha, dtype=torch.float32, device=pooled_b.device)
+    st = load_library().kascade_head_similarity(int(B), int(Hkv), _ptr(pooled_b), int(pitch), _ptr(seqlens),
+                                                _ptr(k_per_seq), int(idx_b.shape[2]), _ptr(idx_a), int(Ha),
+                                                _ptr(idx_b), _ptr(sim_out), _stream())
+    _check(st, "kascade_head_similarity")
+    return sim_out
+
+
+def kascade_head_map(sim):
+    """sim [n_samples,Hkv,Ha] fp32 (device).  Returns (head_map [Hkv] int32, mean [Hkv,Ha] fp32)."""
+    _need_gpu(sim)
+    if sim.dtype != torch.float32 or not sim.is_contiguous() or sim.dim() != 3:
+        raise ValueError("sim must be a contiguous fp32 [n_samples, Hkv, Ha] tensor")
+    n, Hkv, Ha = sim.shape
+    mean = torch.empty(Hkv, Ha, dtype=torch.float32, device=sim.device)
+    head_map = torch.empty(Hkv, dtype=torch.int32, device=sim.device)
+    _check(load_library().kascade_head_map(int(n), int(Hkv), int(Ha), _ptr(sim), _ptr(mean), _ptr(head_map), _stream()),
+           "kascade_head_map")
+    return head_map, mean
+
+
+def kascade_layer_importance(x, y):
+    """x, y [n_rows,n_cols] (fp32 or bf16, device, unit column stride).  Returns w [n_rows] fp32."""
+    _need_gpu(x, y)
+    if x.shape != y.shape or x.dim() != 2 or x.dtype != y.dtype or x.stride(1) != 1 or y.stride(1) != 1:
+        raise ValueError("x and y must be 2-D tensors of one shape and dtype with contiguous rows")
+    w = torch.empty(x.shape[0], dtype=torch.float32, device=x.device)
+    st = load_library().kascade_layer_importance(_ptr(x), _ptr(y), int(x.shape[0]), int(x.shape[1]), _dtype_code(x),
+                                                 int(x.stride(0)), int(y.stride(0)), _ptr(w), _stream())
+    _check(st, "kascade_layer_importance")
+    return w

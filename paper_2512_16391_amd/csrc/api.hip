@@ -144,11 +144,11 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // Events are created on demand and kept until profiling is disabled; with profiling off
 // the library creates nothing.
 enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
-                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_COUNT };
+                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
     "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel",
-    "similarity"};
+    "similarity", "head_map", "layer_importance"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
@@ -482,19 +482,56 @@ int kascade_topk_similarity(int32_t batch, int32_t n_kv_heads, const float* pool
     return timed(K_SIMILARITY, stream, [&] { return launch_similarity(a, stream); });
 }
 
-int kascade_select_anchor_layers(const float* similarity, int32_t n_layers, int32_t n_anchors, int32_t* anchors_out,
-                                 double* objective_out) {
+int kascade_head_similarity(int32_t batch, int32_t n_kv_heads, const float* pooled_b, int64_t pooled_pitch,
+                            const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_a,
+                            int32_t n_heads_a, const int32_t* idx_b, float* sim_out, void* hip_stream) {
+    if (batch <= 0 || n_kv_heads <= 0 || n_heads_a <= 0 || k_max <= 0 || pooled_pitch <= 0) return KASCADE_INVALID_ARG;
+    if (batch > 65535 || n_heads_a > 65535) return KASCADE_INVALID_ARG;
+    if (!pooled_b || !seqlens || !k_per_seq || !idx_a || !idx_b || !sim_out) return KASCADE_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    SimilarityArgs a = {};
+    a.B = batch; a.Hkv = n_kv_heads; a.pooled = pooled_b; a.pitch = pooled_pitch; a.seqlens = seqlens;
+    a.k_per_seq = k_per_seq; a.k_max = k_max; a.idx_a = idx_a; a.n_heads_a = n_heads_a; a.head_map = nullptr;
+    a.idx_b = idx_b; a.sim_out = sim_out; a.sim_min = nullptr; a.all_pairs = 1;
+    return timed(K_SIMILARITY, stream, [&] { return launch_similarity(a, stream); });
+}
+
+int kascade_head_map(int32_t n_samples, int32_t n_kv_heads, int32_t n_heads_a, const float* sim, float* mean_out,
+                     int32_t* head_map_out, void* hip_stream) {
+    if (n_samples <= 0 || n_kv_heads <= 0 || n_heads_a <= 0 || !sim || !head_map_out) return KASCADE_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return timed(K_HEAD_MAP, stream, [&] {
+        return launch_head_map(n_samples, n_kv_heads, n_heads_a, sim, mean_out, head_map_out, stream);
+    });
+}
+
+int kascade_layer_importance(const void* x, const void* y, int64_t n_rows, int32_t n_cols, int32_t dtype,
+                             int64_t x_row_stride, int64_t y_row_stride, float* w_out, void* hip_stream) {
+    if (!x || !y || !w_out || n_rows <= 0 || n_cols <= 0) return KASCADE_INVALID_ARG;
+    if (n_rows > (int64_t)0x7fffffff * 4) return KASCADE_INVALID_ARG;
+    if (x_row_stride < n_cols || y_row_stride < n_cols) return KASCADE_INVALID_ARG;
+    if (dtype != KASCADE_F32 && dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return timed(K_IMPORTANCE, stream, [&] {
+        return launch_importance(dtype, x, y, n_rows, n_cols, x_row_stride, y_row_stride, w_out, stream);
+    });
+}
+
+int kascade_select_anchor_layers(const float* similarity, const float* layer_weights, int32_t n_layers,
+                                 int32_t n_anchors, int32_t* anchors_out, double* objective_out) {
     if (!similarity || !anchors_out) return KASCADE_INVALID_ARG;
     if (n_layers <= 0 || n_layers > 4096 || n_anchors <= 0 || n_anchors > n_layers) return KASCADE_INVALID_ARG;
     const int L = n_layers, M = n_anchors;
     for (int64_t i = 0; i < (int64_t)L * L; ++i)
         if (!(similarity[i] == similarity[i])) return KASCADE_INVALID_ARG;   // NaN
+    for (int i = 0; layer_weights && i < L; ++i)
+        if (!(layer_weights[i] == layer_weights[i])) return KASCADE_INVALID_ARG;
     // serve[i*(L+1) + j]: total similarity of the layers i..j-1 when anchor i serves them
     std::vector<double> serve((size_t)L * (L + 1), 0.0);
     for (int i = 0; i < L; ++i) {
         double run = 0.0;
         for (int j = i; j < L; ++j) {
-            run += (double)similarity[(size_t)i * L + j];
+            run += (double)similarity[(size_t)i * L + j] * (layer_weights ? (double)layer_weights[j] : 1.0);
             serve[(size_t)i * (L + 1) + j + 1] = run;
         }
     }

@@ -1,4 +1,5 @@
-// Calibration-time kernel: similarity of two layers' Top-k sets (Eq. 3).
+// Calibration-time kernels: similarity of two layers' Top-k sets (Eq. 3), head map from the
+// head-level similarity (Sec. 3.5), layer importance (Sec. 3.3).
 //
 // For one (sequence, key head) segment the similarity of layer a's set applied to layer b is
 // the pooled attention mass of layer b that a's set recovers, over the mass b's own set
@@ -26,11 +27,12 @@ __device__ __forceinline__ float block_sum(float x, float* sm) {
 }
 
 __global__ __launch_bounds__(kSimBlock) void similarity_kernel(SimilarityArgs a) {
+    // all_pairs: blockIdx.z walks layer a's heads and the output is [B, Hkv, n_heads_a]
     const int hk = blockIdx.x, b = blockIdx.y;
     const int L = a.seqlens[b];
     int k = a.k_per_seq[b];
     k = k < 0 ? 0 : (k > a.k_max ? a.k_max : k);
-    const int src = a.head_map ? a.head_map[hk] : hk;
+    const int src = a.all_pairs ? (int)blockIdx.z : (a.head_map ? a.head_map[hk] : hk);
     const float* row = a.pooled + ((int64_t)b * a.Hkv + hk) * a.pitch;
     const int32_t* ia = a.idx_a + ((int64_t)b * a.n_heads_a + src) * a.k_max;
     const int32_t* ib = a.idx_b + ((int64_t)b * a.Hkv + hk) * a.k_max;
@@ -45,16 +47,73 @@ __global__ __launch_bounds__(kSimBlock) void similarity_kernel(SimilarityArgs a)
     den = block_sum(den, sm);
     if (threadIdx.x == 0) {
         const float sim = den > 0.f ? num / den : 1.f;
-        if (a.sim_out) a.sim_out[b * a.Hkv + hk] = sim;
+        if (a.sim_out) a.sim_out[a.all_pairs ? (b * a.Hkv + hk) * a.n_heads_a + src : b * a.Hkv + hk] = sim;
         // similarities are non-negative, so their bit patterns order like the values
         if (a.sim_min) atomicMin(reinterpret_cast<unsigned int*>(a.sim_min), __float_as_uint(fmaxf(sim, 0.f)));
     }
 }
 
+// One wave per head of the reuse layer: mean over the samples of sim[b, hk, ha] for every anchor
+// head ha (each lane sums a strided share in order, then a fixed butterfly), then the arg-max;
+// equal means keep the lower anchor head.
+__global__ __launch_bounds__(kWave) void head_map_kernel(int B, int Hkv, int Ha, const float* sim, float* mean_out,
+                                                         int32_t* head_map_out) {
+    const int hk = blockIdx.x, lane = threadIdx.x;
+    float best = -INFINITY;
+    int arg = 0;
+    for (int ha = 0; ha < Ha; ++ha) {
+        float t = 0.f;
+        for (int b = lane; b < B; b += kWave) t += sim[((int64_t)b * Hkv + hk) * Ha + ha];
+        t = wave_sum(t) / (float)B;
+        if (mean_out && lane == 0) mean_out[hk * Ha + ha] = t;
+        if (t > best) { best = t; arg = ha; }
+    }
+    if (lane == 0) head_map_out[hk] = arg;
+}
+
+__device__ __forceinline__ float widen1(float v) { return v; }
+__device__ __forceinline__ float widen1(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+// One wave per row: 1 - <x, y> / (|x| |y|), fp32 accumulation.
+template <typename T>
+__global__ __launch_bounds__(kSimBlock) void importance_kernel(const T* x, const T* y, int64_t n_rows, int n_cols,
+                                                               int64_t x_stride, int64_t y_stride, float* w_out) {
+    const int64_t row = (int64_t)blockIdx.x * (kSimBlock / kWave) + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int lane = threadIdx.x & 63;
+    const T* xr = x + row * x_stride;
+    const T* yr = y + row * y_stride;
+    float xy = 0.f, xx = 0.f, yy = 0.f;
+    for (int c = lane; c < n_cols; c += kWave) {
+        const float a = widen1(xr[c]), b = widen1(yr[c]);
+        xy = fmaf(a, b, xy); xx = fmaf(a, a, xx); yy = fmaf(b, b, yy);
+    }
+    xy = wave_sum(xy); xx = wave_sum(xx); yy = wave_sum(yy);
+    if (lane == 0) w_out[row] = 1.f - xy / (sqrtf(xx) * sqrtf(yy));
+}
+
 }  // namespace
 
 hipError_t launch_similarity(const SimilarityArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(similarity_kernel, dim3(a.Hkv, a.B), dim3(kSimBlock), 0, st, a);
+    hipLaunchKernelGGL(similarity_kernel, dim3(a.Hkv, a.B, a.all_pairs ? a.n_heads_a : 1), dim3(kSimBlock), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_head_map(int B, int Hkv, int Ha, const float* sim, float* mean_out, int32_t* head_map_out,
+                           hipStream_t st) {
+    hipLaunchKernelGGL(head_map_kernel, dim3(Hkv), dim3(kWave), 0, st, B, Hkv, Ha, sim, mean_out, head_map_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_importance(int dtype, const void* x, const void* y, int64_t n_rows, int n_cols, int64_t x_stride,
+                             int64_t y_stride, float* w_out, hipStream_t st) {
+    const dim3 grid((unsigned)((n_rows + kSimBlock / kWave - 1) / (kSimBlock / kWave))), block(kSimBlock);
+    if (dtype == 0)
+        hipLaunchKernelGGL(importance_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)y, n_rows, n_cols,
+                           x_stride, y_stride, w_out);
+    else
+        hipLaunchKernelGGL(importance_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)y, n_rows,
+                           n_cols, x_stride, y_stride, w_out);
     return hipGetLastError();
 }
 

@@ -106,10 +106,15 @@ struct SimilarityArgs {
     int32_t n_heads_a;
     const int32_t* head_map;      // [Hkv] into layer a's heads, or null
     const int32_t* idx_b;         // [B, Hkv, k_max]
-    float* sim_out;               // [B, Hkv] or null
+    float* sim_out;               // [B, Hkv] or null; all_pairs: [B, Hkv, n_heads_a]
     float* sim_min;               // one float, min-updated, or null
+    int all_pairs;                // 1: every head of layer a against every head of layer b (head_map unused)
 };
 hipError_t launch_similarity(const SimilarityArgs& a, hipStream_t st);
+hipError_t launch_head_map(int B, int Hkv, int Ha, const float* sim, float* mean_out, int32_t* head_map_out,
+                           hipStream_t st);
+hipError_t launch_importance(int dtype, const void* x, const void* y, int64_t n_rows, int n_cols, int64_t x_stride,
+                             int64_t y_stride, float* w_out, hipStream_t st);
 
 // ---- prefill -----------------------------------------------------------------------
 struct PrefillArgs {

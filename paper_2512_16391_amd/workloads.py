@@ -283,3 +283,19 @@ def layer_stack(device="cpu", n_layers=8, block_starts=(0, 3, 5), B=2, Hq=8, Hkv
     overlap = [0.0 if l in block_starts else within for l in range(n_layers)]
     return make_decode_workload(f"stack-{n_layers}-layers", 6, n_layers, B, Hq, Hkv, d, dtype, list(seqlens),
                                 [k] * B, n_hitters, overlap, 0, boost=12.0, q_boost=3.0, device=device)
+
+
+def permuted_head_layer(layer, perm, Hq, noise=0.05, seed=BASE_SEED + 6500):
+    """A second layer whose key head h (with its query group) is a noisy copy of key head
+    perm[h] of `layer`: the planted head correspondence of Sec. 3.5."""
+    g = torch.Generator().manual_seed(seed)
+    Hkv = layer.k.shape[1]
+    G = Hq // Hkv
+    dtype = layer.q.dtype
+    qh = [h2 * G + i for h2 in perm for i in range(G)]
+    q = layer.q.float().cpu()[:, qh]
+    k = layer.k.float().cpu()[:, list(perm)]
+    v = layer.v.float().cpu()[:, list(perm)]
+    q = q + noise * torch.randn(q.shape, generator=g)
+    k = k + noise * torch.randn(k.shape, generator=g)
+    return DecodeLayer(q.to(dtype), k.to(dtype), v.to(dtype), None)

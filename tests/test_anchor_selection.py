@@ -69,3 +69,20 @@ def test_library_selection_rejects_bad_arguments():
         kb.kascade_select_anchor_layers(bad, 2)
     with pytest.raises(ValueError):
         kb.kascade_select_anchor_layers(np.zeros((3, 4), dtype=np.float32), 2)
+
+
+def test_library_selection_with_layer_weights():
+    r = np.random.default_rng(21)
+    L, M = 11, 4
+    S = r.random((L, L)).astype(np.float32)
+    w = (1.0 / (1.0 + np.arange(L))).astype(np.float32)       # importance falling with depth
+    got, obj = kb.kascade_select_anchor_layers(S, M, layer_weights=w)
+    SW = ko.weight_similarity(S.astype(np.float64), w.astype(np.float64))
+    assert got == ko.select_anchor_layers(SW, M)
+    ref, ref_val = exhaustive(SW, M)
+    assert got == ref
+    np.testing.assert_allclose(obj, ref_val, atol=1e-9)
+    # unit weights change nothing
+    assert kb.kascade_select_anchor_layers(S, M, layer_weights=np.ones(L))[0] == kb.kascade_select_anchor_layers(S, M)[0]
+    with pytest.raises(ValueError):
+        kb.kascade_select_anchor_layers(S, M, layer_weights=np.ones(L + 1))

@@ -119,3 +119,61 @@ def test_calibration_entries_reject_bad_arguments():
     idx3 = torch.zeros(1, 3, 8, dtype=torch.int32, device=DEV)
     with pytest.raises(binding.KascadeError):       # head counts differ and no head map
         binding.kascade_topk_similarity(pooled, lens, i32([8]), idx3, idx)
+
+
+def test_head_map_from_planted_head_permutation_and_reuse_with_it():
+    print("case head map calibration", flush=True)
+    wl = workloads.layer_stack("cpu", n_layers=1, block_starts=(0,), B=4, Hq=16, Hkv=4, d=64,
+                               seqlens=(2000, 1500, 1800, 777), k=64, n_hitters=24)
+    perm = [2, 0, 3, 1]
+    anchor = wl.layers[0]
+    reuse = workloads.permuted_head_layer(anchor, perm, wl.Hq)
+    lens, ks = i32(wl.seqlens), i32(wl.k_per_seq)
+    Lmax, k_max = max(wl.seqlens), max(wl.k_per_seq)
+    dev = lambda t: t.to(DEV)
+    idx_a, _ = binding.kascade_decode_anchor(dev(anchor.q), dev(anchor.k), dev(anchor.v), lens, ks, Lmax, k_max)
+    idx_b, _ = binding.kascade_decode_anchor(dev(reuse.q), dev(reuse.k), dev(reuse.v), lens, ks, Lmax, k_max)
+    pooled_b = binding.kascade_decode_pooled(dev(reuse.q), dev(reuse.k), lens, Lmax)
+    sim = binding.kascade_head_similarity(pooled_b, lens, ks, idx_a, idx_b)
+    head_map, mean = binding.kascade_head_map(sim)
+
+    # oracle: same quantities from the definitions
+    ref_a = oracle_layer(anchor, wl)
+    ref_b = oracle_layer(reuse, wl)
+    sims = np.stack([ko.head_similarity(ref_b[0][s], ref_a[1][s], ref_b[1][s]) for s in range(wl.B)])
+    hm_ref, mean_ref = ko.head_map_from_similarity(sims)
+    assert np.abs(sim.cpu().numpy() - sims).max() <= 2e-5
+    assert np.abs(mean.cpu().numpy() - mean_ref).max() <= 2e-5
+    assert head_map.cpu().tolist() == hm_ref.tolist() == perm
+
+    # the calibrated map drives a reuse layer: parity with the oracle under the same map
+    out = binding.kascade_decode_reuse(dev(reuse.q), dev(reuse.k), dev(reuse.v), lens, ks, k_max, idx_a,
+                                       head_map=head_map)
+    idx_host = idx_a.cpu().numpy()
+    for s in range(wl.B):
+        L = wl.seqlens[s]
+        sets = [idx_host[s, h, : wl.k_per_seq[s]] for h in range(wl.Hkv)]
+        want = ko.sparse_decode(f64(reuse.q[s]), f64(reuse.k[s, :, :L]), f64(reuse.v[s, :, :L]), sets,
+                                ko.default_scale(wl.d), perm)
+        assert np.abs(out[s].double().cpu().numpy() - want).max() <= 1e-4
+
+
+@pytest.mark.parametrize("dtype,tol", [(torch.float32, 1e-5), (torch.bfloat16, 1e-5)])
+def test_layer_importance_matches_oracle(dtype, tol):
+    print(f"case layer importance {dtype}", flush=True)
+    g = torch.Generator().manual_seed(9)
+    n_rows, n_cols = 1029, 4096
+    x = torch.randn(n_rows, n_cols, generator=g)
+    y = (x * torch.linspace(0, 1, n_rows)[:, None] + torch.randn(n_rows, n_cols, generator=g) * 0.5)
+    x, y = x.to(dtype), y.to(dtype)
+    y[3] = x[3] * 2          # parallel rows: importance 0
+    y[4] = -x[4]             # opposite rows: importance 2
+    w = binding.kascade_layer_importance(x.to(DEV), y.to(DEV)).double().cpu().numpy()
+    want = ko.layer_importance(f64(x), f64(y))
+    assert np.abs(w - want).max() <= tol, np.abs(w - want).max()
+    assert abs(w[3]) <= tol and abs(w[4] - 2.0) <= tol
+    # strided rows (a column slice of a wider tensor)
+    wide = torch.randn(64, 512, generator=g).to(dtype).to(DEV)
+    w2 = binding.kascade_layer_importance(wide[:, :200], wide[:, 256:456]).double().cpu().numpy()
+    want2 = ko.layer_importance(f64(wide[:, :200].cpu()), f64(wide[:, 256:456].cpu()))
+    assert np.abs(w2 - want2).max() <= tol
