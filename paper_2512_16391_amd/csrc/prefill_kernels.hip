@@ -17,6 +17,7 @@
 //      (post-softmax pooling, Sec. 3.4).  Here a lane owns one key column, so the row sum is
 //      again in-lane.
 #include <limits.h>
+#include <stdlib.h>
 
 #include "device_utils.h"
 #include "kernels.h"
@@ -238,7 +239,9 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         }
     }
 
-    float m_run = -INFINITY, l_run = 0.f;
+    // (m_run, l_run): reference exponent and the sum of 2^(s c - m_run) over the keys seen so far;
+    // neg_ref = -m_run once a finite reference exists, +inf before (forces the exact path)
+    float m_run = -INFINITY, l_run = 0.f, neg_ref = INFINITY;
     f32x16_t acc_o[WITH_V ? DBLK : 1];
 #pragma unroll
     for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
@@ -298,35 +301,54 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
                 if (smPos[32 + slot] > q_token) s1[r] = -INFINITY;
             }
         }
-        // online softmax, base 2; this lane owns query row q (other half-wave holds the other keys)
-        float mx = s0[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
-        mx *= c;
-        mx = half_swap_max(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        // Online softmax, base 2; this lane owns query row q (the other half-wave holds the other
+        // keys of the same row).  The exponentials are taken against a reference that may lag the
+        // true running maximum: any reference gives the same quotient acc / l as long as nothing
+        // overflows, so the block maximum is only looked at when a term exceeds 2^kLag (or is not
+        // finite, which is how the first block gets its reference).  That rare path is wave-uniform.
+        constexpr float kLag = 1073741824.f;   // 2^30
+        f32x16_t e0, e1;
         float rs = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            s0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));
-            s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));
-            rs += s0[r] + s1[r];
+            e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, neg_ref));
+            e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg_ref));
+            rs += e0[r] + e1[r];
+        }
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kLag)) != 0) {
+            float mx = s0[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
+            mx *= c;
+            mx = half_swap_max(mx);
+            const float m_new = fmaxf(m_run, mx);
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
+            rs = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));
+                e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));
+                rs += e0[r] + e1[r];
+            }
+            l_run *= alpha;
+            if constexpr (WITH_V) {
+#pragma unroll
+                for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+            }
+            m_run = m_new;
+            neg_ref = -m_safe;
         }
         rs = half_swap_sum(rs);
-        l_run = fmaf(l_run, alpha, rs);
-        m_run = m_new;
+        l_run += rs;
 
         if constexpr (WITH_V) {
-#pragma unroll
-            for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
             bf16x8_t pf[4];
-            pf[0] = pack_p(s0, 0); pf[1] = pack_p(s0, 8); pf[2] = pack_p(s1, 0); pf[3] = pack_p(s1, 8);
+            pf[0] = pack_p(e0, 0); pf[1] = pack_p(e0, 8); pf[2] = pack_p(e1, 0); pf[3] = pack_p(e1, 8);
 #pragma unroll
             for (int i = 0; i < DBLK; ++i) {
 #pragma unroll
@@ -464,6 +486,152 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
     }
 }
 
+// ---- direct global -> LDS staging ---------------------------------------------------------
+// global_load_lds_dwordx4 writes lane i's 16 bytes to (wave-uniform LDS base) + 16 i, so the LDS
+// side is linear in the thread index and the XOR swizzle is applied on the source side: the
+// thread that fills chunk position pp of a row fetches logical chunk pp ^ f(row).  The resulting
+// LDS image is the one k_off<D> addresses.  No staging registers, no LDS write instructions.
+typedef __attribute__((address_space(1))) const void* gmem_ptr_t;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+template <int D> struct Dma {
+    static constexpr int PPR = D / 8, RPP = kPB / PPR, PASSES = BK / RPP;
+    // byte offset inside a row of the chunk this thread fetches (same for all its passes)
+    static __device__ __forceinline__ uint32_t chunk_off() {
+        const int r0 = threadIdx.x / PPR, pp = threadIdx.x % PPR;
+        const int f = (D == 128) ? (r0 & 15) : ((r0 >> 1) & 7);
+        return (uint32_t)((pp ^ f) << 4);
+    }
+};
+
+// stage key rows row_first + slot (slot = 0..63), rows clamped to row_last, into `tile`
+template <int D>
+__device__ __forceinline__ void dma_rows_seq(unsigned char* tile, const unsigned char* base, uint32_t row_bytes,
+                                             int row_first, int row_last, uint32_t coff) {
+    const int r0 = threadIdx.x / Dma<D>::PPR, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < Dma<D>::PASSES; ++i) {
+        int row = row_first + i * Dma<D>::RPP + r0;
+        row = row < row_last ? row : row_last;
+        const unsigned char* src = base + (size_t)((uint32_t)row * row_bytes + coff);
+        __builtin_amdgcn_global_load_lds((gmem_ptr_t)src, (lds_ptr_t)(tile + (i * kPB + w * kWave) * 16), 16, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only
+
+// One 64-key block of anchor pass 2 for this wave: S = Q K^T from the staged tile, pooled
+// weights 2^(s c - e_r), column sums over the wave's 32 rows into part[w][key].
+template <int D>
+__device__ __forceinline__ void pool_block(const unsigned char* tile, float (*part)[BK], const bf16x8_t (&qf)[D / 16],
+                                           const float (&e_r)[16], float c, int key0, int key1, int h, int w) {
+    constexpr int KSTEPS = D / 16;
+    f32x16_t s0, s1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        const bf16x8_t b0 = lds_frag(tile + k_off<D>(key0, kk * 2 + h));
+        const bf16x8_t b1 = lds_frag(tile + k_off<D>(key1, kk * 2 + h));
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b0, s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b1, s1, 0, 0, 0);
+    }
+    float c0 = 0.f, c1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        c0 += __builtin_amdgcn_exp2f(fmaf(s0[r], c, -e_r[r]));
+        c1 += __builtin_amdgcn_exp2f(fmaf(s1[r], c, -e_r[r]));
+    }
+    c0 = half_swap_sum(c0);
+    c1 = half_swap_sum(c1);
+    if (h == 0) { part[w][key0] = c0; part[w][key1] = c1; }
+}
+
+// Anchor pass 2 with two K tiles in LDS filled by direct loads: block kb+1 streams in while block
+// kb is multiplied; one barrier per block.  The cross-wave sum of block kb's column partials is
+// taken after the next barrier (two partial buffers), so it needs no barrier of its own.
+template <int D>
+__global__ __launch_bounds__(kPB, 4) void prefill_pool_dma_kernel(Shape s, PrefillArgs a) {
+    constexpr int KSTEPS = D / 16;
+    __shared__ __align__(16) unsigned char smK0[BK * D * 2];
+    __shared__ __align__(16) unsigned char smK1[BK * D * 2];
+    __shared__ float smPart0[kPW][BK];
+    __shared__ float smPart1[kPW][BK];
+
+    const int hk = blockIdx.x % s.Hkv;
+    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
+    const int T = a.tile_tokens, S = a.seqlen;
+    const int prefix = t * T;
+    if (prefix == 0) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int q = lane & 31, h = lane >> 5;
+    const float c = s.scale_log2;
+    const int diag_end = (prefix + T < S) ? prefix + T : S;
+    const float inv_rows = 1.f / (float)((diag_end - prefix) * s.G);
+    const int n_blocks = (prefix + BK - 1) / BK;
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
+    const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
+    const uint32_t coff = Dma<D>::chunk_off();
+    dma_rows_seq<D>(smK0, Kb, row_bytes, 0, prefix - 1, coff);
+
+    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
+    bf16x8_t qf[KSTEPS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    // e_r = m + log2(l * rows) of the query rows whose scores land in this lane's registers;
+    // rows beyond the sequence get weight 0
+    float e_r[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const RowMap rr = map_row(w * 32 + (r >> 2) * 8 + h * 4 + (r & 3), t, T, hk, s.G, S);
+        e_r[r] = INFINITY;
+        if (rr.ok) {
+            const float* st = a.stats + ((int64_t)rr.head * S + rr.token) * 2;
+            e_r[r] = st[0] + __builtin_amdgcn_logf(st[1] / inv_rows);
+        }
+    }
+    const int key0 = perm_key(q), key1 = 32 + key0;
+    float* dst = a.pooled + hk * a.pooled_pitch + (int64_t)T * t * (t - 1) / 2;
+
+#define KASCADE_POOL_STEP(kb_, cur_, nxt_, part_cur_, part_prev_)                                              \
+    {                                                                                                          \
+        wait_vmem();                                                                                           \
+        __syncthreads();                                                                                       \
+        if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(nxt_, Kb, row_bytes, ((kb_) + 1) * BK, prefix - 1, coff);    \
+        if ((kb_) > 0 && threadIdx.x < BK) {                                                                   \
+            const int j_ = ((kb_) - 1) * BK + threadIdx.x;                                                     \
+            if (j_ < prefix)                                                                                   \
+                dst[j_] = (part_prev_[0][threadIdx.x] + part_prev_[1][threadIdx.x]) +                          \
+                          (part_prev_[2][threadIdx.x] + part_prev_[3][threadIdx.x]);                           \
+        }                                                                                                      \
+        pool_block<D>(cur_, part_cur_, qf, e_r, c, key0, key1, h, w);                                          \
+    }
+    int kb = 0;
+    for (; kb + 1 < n_blocks; kb += 2) {
+        KASCADE_POOL_STEP(kb, smK0, smK1, smPart0, smPart1)
+        KASCADE_POOL_STEP(kb + 1, smK1, smK0, smPart1, smPart0)
+    }
+    if (kb < n_blocks) {
+        KASCADE_POOL_STEP(kb, smK0, smK1, smPart0, smPart1)
+        ++kb;
+    }
+#undef KASCADE_POOL_STEP
+    __syncthreads();
+    if (threadIdx.x < BK) {
+        float (*last)[BK] = (kb & 1) ? smPart0 : smPart1;
+        const int j = (kb - 1) * BK + threadIdx.x;
+        if (j < prefix) dst[j] = (last[0][threadIdx.x] + last[1][threadIdx.x]) + (last[2][threadIdx.x] + last[3][threadIdx.x]);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
@@ -481,6 +649,12 @@ hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool spar
 
 hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t st) {
     dim3 grid(a.n_tiles * s.Hkv), block(kPB);
+    if (getenv("KASCADE_POOL_OLD") == nullptr) {
+        if (s.D == 128) hipLaunchKernelGGL((prefill_pool_dma_kernel<128>), grid, block, 0, st, s, a);
+        else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_dma_kernel<64>), grid, block, 0, st, s, a);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     if (s.D == 128) hipLaunchKernelGGL((prefill_pool_kernel<128>), grid, block, 0, st, s, a);
     else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_kernel<64>), grid, block, 0, st, s, a);
     else return hipErrorInvalidValue;
