@@ -298,3 +298,21 @@ def test_config5_shape_prefill_131072_then_decode():
         e2 = max_abs(f64(o2[0]), ko.sparse_decode(f64(newq[1, 0]), f64(kc2[0]), f64(vc2[0]), sets, scale))
         print(f"  decode step {step} L={L} k={kk}: swaps {sw}, max-abs anchor {e1:.3e} reuse {e2:.3e}", flush=True)
         assert max(e1, e2) <= TOL_OUT[BF16]
+
+
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_prefill_anchor_logits_rising_and_falling_along_the_keys(out_mode):
+    """Keys whose logits climb by hundreds of nats along the sequence (and drop again): the running
+    softmax must move its reference exponent many times and still match the oracle."""
+    print(f"case prefill rising logits out_mode={out_mode}", flush=True)
+    S, Hq, Hkv, d, T = 640, 8, 2, 128, 32
+    g = torch.Generator().manual_seed(31)
+    u = torch.randn(d, generator=g)
+    u = u / u.norm()
+    q = (0.3 * torch.randn(S, Hq, d, generator=g) + 4.0 * u).to(BF16)
+    ramp = torch.cat([torch.linspace(0.0, 240.0, 400), torch.linspace(240.0, -40.0, S - 400)])
+    k = (0.3 * torch.randn(Hkv, S, d, generator=g) + ramp[None, :, None] * u).to(BF16)
+    v = torch.randn(Hkv, S, d, generator=g).to(BF16)
+    # logit of key j ~ 4 * ramp[j] / sqrt(d): up to 85 nats (122 in base 2), i.e. several reference updates
+    kpt = workloads.prefill_budgets(S, T, 100, 24)
+    run_anchor(q, k, v, T, kpt, out_mode, where="ramp")
