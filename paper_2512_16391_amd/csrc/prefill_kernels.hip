@@ -173,7 +173,7 @@ __device__ __forceinline__ RowMap map_row(int rho, int t, int T, int hk, int G, 
 }
 
 template <int D, bool SPARSE, bool WITH_V>
-__global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(Shape s, PrefillArgs a) {
+__global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_old_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     __shared__ __align__(16) unsigned char smK[BK * D * 2];
     __shared__ __align__(16) unsigned char smVt[WITH_V ? BK * D * 2 : 16];   // V tile, row-major
@@ -520,6 +520,263 @@ __device__ __forceinline__ void dma_rows_seq(unsigned char* tile, const unsigned
 
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only
 
+// Flash-style attention over a key list with both tiles (K, and V when an output is wanted) double
+// buffered in LDS and filled by direct loads: block kb+1 streams in while block kb is multiplied,
+// one barrier per block.  BUF is the LDS buffer of this block; it is a template constant so that all
+// LDS addresses of a block differ from the other buffer's only by an immediate offset.
+template <int D, bool SPARSE, bool WITH_V>
+__global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(Shape s, PrefillArgs a) {
+    constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = BK * D * 2;
+    constexpr int PASSES = Dma<D>::PASSES, RPP = Dma<D>::RPP, PPR = Dma<D>::PPR;
+    __shared__ __align__(16) unsigned char smK[2 * TILE];
+    __shared__ __align__(16) unsigned char smV[WITH_V ? 2 * TILE : 16];
+    __shared__ int smPos[2][BK];
+    __shared__ int smFlag[3];   // "block holds a slot without a key", rotating over three blocks
+
+    const int hk = blockIdx.x % s.Hkv;
+    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;   // long tiles first
+    const int T = a.tile_tokens, S = a.seqlen;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int q = lane & 31, h = lane >> 5;
+    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
+    const int q_token = rm.ok ? rm.token : INT_MAX - 1;
+    const float c = s.scale_log2;
+
+    const int prefix = t * T;
+    const int diag_end = (prefix + T < S) ? prefix + T : S;
+    int n_sparse = 0, nb_gather = 0, n_blocks;
+    const int32_t* idx = nullptr;
+    if constexpr (SPARSE) {
+        int kt = a.k_per_tile[t];
+        n_sparse = kt < 0 ? 0 : (kt > prefix ? prefix : kt);
+        nb_gather = (n_sparse + BK - 1) / BK;
+        n_blocks = nb_gather + (diag_end - prefix + BK - 1) / BK;
+        int src = a.head_map ? a.head_map[hk] : hk;
+        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+        idx = a.idx + (int64_t)src * a.idx_total + a.idx_offsets[t];
+    } else {
+        n_blocks = (diag_end + BK - 1) / BK;
+    }
+    const int n_seq = SPARSE ? 0 : prefix / BK;   // dense: blocks entirely before the tile, every slot a key
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
+    const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + hk * s.kv_stride[1]);
+    const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
+    const int r0 = threadIdx.x / PPR, pp = threadIdx.x % PPR;
+    const uint32_t koff = Dma<D>::chunk_off();
+    const uint32_t voff = (uint32_t)((pp ^ ((D == 128) ? ((r0 & 3) << 2) : (((r0 >> 1) & 1) << 2))) << 4);
+
+    // Key position of this thread's staging slots in block kb (-1 = no key).  Gathered blocks take
+    // two steps so that nothing waits on the index load when it is issued: KASCADE_BLOCK_RAW fetches
+    // the list entries a block early (clamped subscript, value untouched), KASCADE_BLOCK_POS turns
+    // them into positions when the block is staged.
+#define KASCADE_BLOCK_RAW(kb_, pos_)                                                        \
+    if (SPARSE && (kb_) < nb_gather) {                                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                              \
+            const int j_ = (kb_) * BK + i_ * RPP + r0;                                       \
+            pos_[i_] = idx[j_ < n_sparse ? j_ : n_sparse - 1];                               \
+        }                                                                                    \
+    }
+#define KASCADE_BLOCK_POS(kb_, pos_)                                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                                  \
+        const int slot_ = i_ * RPP + r0;                                                     \
+        int p_;                                                                              \
+        if (SPARSE && (kb_) < nb_gather) {                                                   \
+            p_ = ((kb_) * BK + slot_ < n_sparse && pos_[i_] < prefix) ? pos_[i_] : -1;       \
+        } else {                                                                             \
+            p_ = (SPARSE ? prefix + ((kb_) - nb_gather) * BK : (kb_) * BK) + slot_;          \
+            if (p_ >= diag_end) p_ = -1;                                                     \
+        }                                                                                    \
+        pos_[i_] = p_;                                                                       \
+    }
+    // direct loads of the rows pos_[] into buffer buf_; records the positions for the masks
+#define KASCADE_STAGE(buf_, pos_, flag_)                                                                     \
+    {                                                                                                        \
+        bool bad_ = false;                                                                                   \
+        _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                                               \
+            const uint32_t off_ = (uint32_t)(pos_[i_] < 0 ? 0 : pos_[i_]) * row_bytes;                       \
+            unsigned char* dk_ = smK + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + (size_t)(off_ + koff)), (lds_ptr_t)dk_, 16, 0, 0); \
+            if constexpr (WITH_V) {                                                                          \
+                unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                       \
+                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + (size_t)(off_ + voff)), (lds_ptr_t)dv_, 16, 0, 0); \
+            }                                                                                                \
+            if (pp == 0) smPos[buf_][i_ * RPP + r0] = pos_[i_] < 0 ? INT_MAX : pos_[i_];                     \
+            bad_ |= pos_[i_] < 0;                                                                            \
+        }                                                                                                    \
+        if (bad_) smFlag[flag_] = 1;                                                                         \
+    }
+    // the same for a block of consecutive keys that all exist (no masks, no bookkeeping)
+#define KASCADE_STAGE_SEQ(buf_, kb_)                                                                         \
+    {                                                                                                        \
+        const uint32_t base_ = (uint32_t)((kb_) * BK + r0) * row_bytes;                                      \
+        _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                                               \
+            const uint32_t off_ = base_ + (uint32_t)(i_ * RPP) * row_bytes;                                  \
+            unsigned char* dk_ = smK + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + (size_t)(off_ + koff)), (lds_ptr_t)dk_, 16, 0, 0); \
+            if constexpr (WITH_V) {                                                                          \
+                unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                       \
+                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + (size_t)(off_ + voff)), (lds_ptr_t)dv_, 16, 0, 0); \
+            }                                                                                                \
+        }                                                                                                    \
+    }
+
+    // query fragments (B operand of S^T = K Q^T): row q of this wave, 8 elements per k-step
+    bf16x8_t qf[KSTEPS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+
+    // (m_run, l_run): reference exponent and the sum of 2^(s c - m_run) over the keys seen so far;
+    // neg_ref = -m_run once a finite reference exists, +inf before (forces the exact path)
+    float m_run = -INFINITY, l_run = 0.f, neg_ref = INFINITY;
+    f32x16_t acc_o[WITH_V ? DBLK : 1];
+#pragma unroll
+    for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+
+    if (threadIdx.x < 3) smFlag[threadIdx.x] = 0;
+    __syncthreads();
+    int pos[PASSES];
+    if (0 < n_seq) {
+        KASCADE_STAGE_SEQ(0, 0)
+    } else {
+        KASCADE_BLOCK_RAW(0, pos)
+        KASCADE_BLOCK_POS(0, pos)
+        KASCADE_STAGE(0, pos, 0)
+    }
+    KASCADE_BLOCK_RAW(1, pos)
+
+    const int key0 = perm_key(q), key1 = 32 + key0;
+    int f_cur = 0, f_next = 1, f_free = 2;   // smFlag slots of block kb, kb+1 and the one to clear for kb+2
+
+    // one block; buf_ is a literal
+#define KASCADE_ATTEND_BLOCK(kb_, buf_)                                                                       \
+    {                                                                                                        \
+        wait_vmem();                                                                                         \
+        __syncthreads();   /* tile kb_ has landed; nobody reads the other buffer any more */                 \
+        if (threadIdx.x == 0) smFlag[f_free] = 0;                                                            \
+        if ((kb_) + 1 < n_seq) {                                                                             \
+            KASCADE_STAGE_SEQ(1 - (buf_), (kb_) + 1)                                                         \
+        } else if ((kb_) + 1 < n_blocks) {                                                                   \
+            KASCADE_BLOCK_POS((kb_) + 1, pos)                                                                \
+            KASCADE_STAGE(1 - (buf_), pos, f_next)                                                           \
+            KASCADE_BLOCK_RAW((kb_) + 2, pos)                                                                \
+        }                                                                                                    \
+        const unsigned char* tK_ = smK + (buf_) * TILE;                                                      \
+        /* S^T block: rows = 64 keys (two MFMA tiles), cols = this wave's 32 queries */                      \
+        f32x16_t s0, s1;                                                                                     \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }                          \
+        _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                                               \
+            const bf16x8_t a0 = lds_frag(tK_ + k_off<D>(key0, kk * 2 + h));                                  \
+            const bf16x8_t a1 = lds_frag(tK_ + k_off<D>(key1, kk * 2 + h));                                  \
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[kk], s0, 0, 0, 0);                           \
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[kk], s1, 0, 0, 0);                           \
+        }                                                                                                    \
+        /* mask: causal inside / beyond the diagonal, and slots without a key */                             \
+        bool need_mask = smFlag[f_cur] != 0;                                                                 \
+        if constexpr (SPARSE) need_mask |= (kb_) >= nb_gather;                                               \
+        else need_mask |= ((kb_) + 1) * BK > prefix;                                                         \
+        if (need_mask) {                                                                                     \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
+                const int slot = (r >> 3) * 16 + h * 8 + (r & 7);                                            \
+                if (smPos[buf_][slot] > q_token) s0[r] = -INFINITY;                                          \
+                if (smPos[buf_][32 + slot] > q_token) s1[r] = -INFINITY;                                     \
+            }                                                                                                \
+        }                                                                                                    \
+        /* Online softmax, base 2; this lane owns query row q (the other half-wave holds the other keys   */ \
+        /* of the same row).  The exponentials are taken against a reference that may lag the true running */ \
+        /* maximum: any reference gives the same quotient acc / l as long as nothing overflows, so the     */ \
+        /* block maximum is only looked at when a term exceeds 2^30 (or is not finite, which is how the    */ \
+        /* first block gets its reference).  That rare path is wave-uniform.                               */ \
+        f32x16_t e0, e1;                                                                                     \
+        float rs = 0.f;                                                                                      \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                      \
+            e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, neg_ref));                                         \
+            e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg_ref));                                         \
+            rs += e0[r] + e1[r];                                                                             \
+        }                                                                                                    \
+        if (__builtin_amdgcn_ballot_w64(!(rs <= 1073741824.f)) != 0) {                                       \
+            float mx = s0[0];                                                                                \
+            _Pragma("unroll") for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);                             \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);                             \
+            mx *= c;                                                                                         \
+            mx = half_swap_max(mx);                                                                          \
+            const float m_new = fmaxf(m_run, mx);                                                            \
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;                                         \
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   /* 0 while m_run is -inf */        \
+            rs = 0.f;                                                                                        \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
+                e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));                                     \
+                e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));                                     \
+                rs += e0[r] + e1[r];                                                                         \
+            }                                                                                                \
+            l_run *= alpha;                                                                                  \
+            if constexpr (WITH_V) {                                                                          \
+                _Pragma("unroll") for (int i = 0; i < DBLK; ++i)                                              \
+                    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;                      \
+            }                                                                                                \
+            m_run = m_new;                                                                                   \
+            neg_ref = -m_safe;                                                                               \
+        }                                                                                                    \
+        rs = half_swap_sum(rs);                                                                              \
+        l_run += rs;                                                                                         \
+        if constexpr (WITH_V) {                                                                              \
+            const unsigned char* tV_ = smV + (buf_) * TILE;                                                  \
+            bf16x8_t pf[4];                                                                                  \
+            pf[0] = pack_p(e0, 0); pf[1] = pack_p(e0, 8); pf[2] = pack_p(e1, 0); pf[3] = pack_p(e1, 8);      \
+            _Pragma("unroll") for (int i = 0; i < DBLK; ++i) {                                                \
+                _Pragma("unroll") for (int st = 0; st < 4; ++st) {                                            \
+                    const bf16x8_t va = vt_frag<D>(tV_, i, st * 16);                                         \
+                    acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[st], acc_o[i], 0, 0, 0);       \
+                }                                                                                            \
+            }                                                                                                \
+        }                                                                                                    \
+        { const int f_ = f_cur; f_cur = f_next; f_next = f_free; f_free = f_; }                              \
+    }
+
+    int kb = 0;
+    for (; kb + 1 < n_blocks; kb += 2) {
+        KASCADE_ATTEND_BLOCK(kb, 0)
+        KASCADE_ATTEND_BLOCK(kb + 1, 1)
+    }
+    if (kb < n_blocks) { KASCADE_ATTEND_BLOCK(kb, 0) }
+#undef KASCADE_ATTEND_BLOCK
+#undef KASCADE_STAGE_SEQ
+#undef KASCADE_STAGE
+#undef KASCADE_BLOCK_POS
+#undef KASCADE_BLOCK_RAW
+
+    if (!rm.ok) return;
+    if (a.stats && h == 0) {
+        float* st = a.stats + ((int64_t)rm.head * S + rm.token) * 2;
+        st[0] = m_run;
+        st[1] = l_run;
+    }
+    if constexpr (WITH_V) {
+        const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+        bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + (int64_t)rm.token * s.o_stride[1] + (int64_t)rm.head * s.o_stride[2];
+#pragma unroll
+        for (int i = 0; i < DBLK; ++i) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int d0 = i * 32 + r4 * 8 + h * 4;
+                uint2 pk;
+                pk.x = pack_bf16(acc_o[i][r4 * 4 + 0] * inv, acc_o[i][r4 * 4 + 1] * inv);
+                pk.y = pack_bf16(acc_o[i][r4 * 4 + 2] * inv, acc_o[i][r4 * 4 + 3] * inv);
+                *reinterpret_cast<uint2*>(op + d0) = pk;
+            }
+        }
+    }
+}
+
 // One 64-key block of anchor pass 2 for this wave: S = Q K^T from the staged tile, pooled
 // weights 2^(s c - e_r), column sums over the wave's 32 rows into part[w][key].
 template <int D>
@@ -637,6 +894,11 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_dma_kernel(Shape s, Prefi
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
     dim3 grid(a.n_tiles * s.Hkv), block(kPB);
 #define KASCADE_LAUNCH_ATTEND(DD)                                                                                      \
+    if (getenv("KASCADE_ATTEND_OLD")) {                                                                                \
+    if (sparse) hipLaunchKernelGGL((prefill_attend_old_kernel<DD, true, true>), grid, block, 0, st, s, a);             \
+    else if (with_v) hipLaunchKernelGGL((prefill_attend_old_kernel<DD, false, true>), grid, block, 0, st, s, a);       \
+    else hipLaunchKernelGGL((prefill_attend_old_kernel<DD, false, false>), grid, block, 0, st, s, a);                  \
+    } else                                                                                                             \
     if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true>), grid, block, 0, st, s, a);                 \
     else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true>), grid, block, 0, st, s, a);           \
     else hipLaunchKernelGGL((prefill_attend_kernel<DD, false, false>), grid, block, 0, st, s, a);
