@@ -2,9 +2,12 @@
 //
 // A query tile is T consecutive tokens times the G query heads of one key head = 128 rows
 // (paper Sec. 3.4).  One workgroup of four waves owns one (tile, key head); wave w owns rows
-// 32w..32w+31, row rho = g*T + token_in_tile.  Keys are processed in blocks of 64 staged
-// through LDS, K and V row-major and XOR-swizzled against bank conflicts; V^T operand fragments come
-// from the transposing LDS read (ds_read_b64_tr_b16).
+// 32w..32w+31, row rho = g*T + token_in_tile.  Keys are processed in blocks of 64 held in LDS,
+// K and V row-major and XOR-swizzled against bank conflicts; V^T operand fragments come from the
+// transposing LDS read (ds_read_b64_tr_b16).  Tiles are double buffered and filled by direct
+// global-to-LDS loads, so block kb+1 streams in while block kb is multiplied and a block costs one
+// barrier.  The running softmax keeps a reference exponent that may lag the true maximum and looks
+// at a block's maximum only when a term would exceed 2^30.
 //
 //  prefill_attend_kernel  flash-style attention over a key list:
 //      dense  - all keys up to the diagonal, causal (anchor pass 1, Sec. 3.6): emits the row
@@ -17,7 +20,6 @@
 //      (post-softmax pooling, Sec. 3.4).  Here a lane owns one key column, so the row sum is
 //      again in-lane.
 #include <limits.h>
-#include <stdlib.h>
 
 #include "device_utils.h"
 #include "kernels.h"
@@ -101,65 +103,6 @@ __device__ __forceinline__ bf16x8_t pack_p(const f32x16_t& s, int base) {
     return r;
 }
 
-// Global -> register -> LDS staging of one block of 64 key slots.  A row of D bf16 is D/8
-// 16-byte pieces; thread tid owns piece tid % PPR of rows tid / PPR + i * RPP.
-template <int D> struct Stage {
-    static constexpr int PPR = D / 8;          // 16-byte pieces per row
-    static constexpr int RPP = kPB / PPR;      // rows per pass
-    static constexpr int PASSES = BK / RPP;
-};
-
-// Kb / Vb: base of this key head (uniform); offsets are 32-bit byte offsets (a head's rows span < 4 GiB)
-template <int D, bool WITH_V>
-__device__ __forceinline__ void stage_issue(u32x4_t (&kr)[Stage<D>::PASSES], u32x4_t (&vr)[Stage<D>::PASSES],
-                                            const int (&pos)[Stage<D>::PASSES], const bf16_t* Kb, const bf16_t* Vb,
-                                            uint32_t row_bytes) {
-    const uint32_t piece_off = (threadIdx.x % Stage<D>::PPR) * 16;
-#pragma unroll
-    for (int i = 0; i < Stage<D>::PASSES; ++i) {
-        const uint32_t off = (uint32_t)(pos[i] < 0 ? 0 : pos[i]) * row_bytes + piece_off;
-        kr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Kb) + off);
-        if constexpr (WITH_V) vr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Vb) + off);
-    }
-}
-
-// Blocks that lie entirely before the tile (dense sweeps): every slot holds key kb*BK + slot, so
-// the byte offsets just advance by one block and no validity bookkeeping is needed.
-template <int D, bool WITH_V>
-__device__ __forceinline__ void stage_issue_seq(u32x4_t (&kr)[Stage<D>::PASSES], u32x4_t (&vr)[Stage<D>::PASSES],
-                                                uint32_t kb, const bf16_t* Kb, const bf16_t* Vb, uint32_t row_bytes) {
-    const uint32_t base = (kb * BK + threadIdx.x / Stage<D>::PPR) * row_bytes + (threadIdx.x % Stage<D>::PPR) * 16;
-#pragma unroll
-    for (int i = 0; i < Stage<D>::PASSES; ++i) {
-        const uint32_t off = base + (uint32_t)(i * Stage<D>::RPP) * row_bytes;
-        kr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Kb) + off);
-        if constexpr (WITH_V) vr[i] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const unsigned char*>(Vb) + off);
-    }
-}
-
-// returns true if this thread staged an invalid slot
-template <int D, bool WITH_V, bool SEQ = false>
-__device__ __forceinline__ bool stage_commit(const u32x4_t (&kr)[Stage<D>::PASSES], const u32x4_t (&vr)[Stage<D>::PASSES],
-                                             const int (&pos)[Stage<D>::PASSES], unsigned char* smK,
-                                             unsigned char* smVt, int* smPos) {
-    const int piece = threadIdx.x % Stage<D>::PPR, r0 = threadIdx.x / Stage<D>::PPR;
-    bool bad = false;
-#pragma unroll
-    for (int i = 0; i < Stage<D>::PASSES; ++i) {
-        const int slot = i * Stage<D>::RPP + r0;
-        *reinterpret_cast<u32x4_t*>(smK + k_off<D>(slot, piece)) = kr[i];
-        if constexpr (WITH_V) {
-            const int f = (D == 128) ? ((slot & 3) << 2) : (((slot >> 1) & 1) << 2);
-            *reinterpret_cast<u32x4_t*>(smVt + slot * (D * 2) + ((piece ^ f) << 4)) = vr[i];
-        }
-        if constexpr (!SEQ) {
-            if (piece == 0) smPos[slot] = pos[i] < 0 ? INT_MAX : pos[i];
-            bad |= pos[i] < 0;
-        }
-    }
-    return bad;
-}
-
 struct RowMap {   // which (token, head) a tile row is
     int token, head;
     bool ok;
@@ -170,320 +113,6 @@ __device__ __forceinline__ RowMap map_row(int rho, int t, int T, int hk, int G, 
     m.head = hk * G + rho / T;
     m.ok = m.token < S;
     return m;
-}
-
-template <int D, bool SPARSE, bool WITH_V>
-__global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_old_kernel(Shape s, PrefillArgs a) {
-    constexpr int KSTEPS = D / 16, DBLK = D / 32;
-    __shared__ __align__(16) unsigned char smK[BK * D * 2];
-    __shared__ __align__(16) unsigned char smVt[WITH_V ? BK * D * 2 : 16];   // V tile, row-major
-    __shared__ int smPos[BK];
-    __shared__ int smFlag[2];
-
-    const int hk = blockIdx.x % s.Hkv;
-    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;   // long tiles first
-    const int T = a.tile_tokens, S = a.seqlen;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int q = lane & 31, h = lane >> 5;
-    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
-    const int q_token = rm.ok ? rm.token : INT_MAX - 1;
-    const float c = s.scale_log2;
-
-    const int prefix = t * T;
-    const int diag_end = (prefix + T < S) ? prefix + T : S;
-    int n_sparse = 0, nb_gather = 0, n_blocks;
-    const int32_t* idx = nullptr;
-    if constexpr (SPARSE) {
-        int kt = a.k_per_tile[t];
-        n_sparse = kt < 0 ? 0 : (kt > prefix ? prefix : kt);
-        nb_gather = (n_sparse + BK - 1) / BK;
-        n_blocks = nb_gather + (diag_end - prefix + BK - 1) / BK;
-        int src = a.head_map ? a.head_map[hk] : hk;
-        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
-        idx = a.idx + (int64_t)src * a.idx_total + a.idx_offsets[t];
-    } else {
-        n_blocks = (diag_end + BK - 1) / BK;
-    }
-
-    const bf16_t* Kb = reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1];
-    const bf16_t* Vb = reinterpret_cast<const bf16_t*>(a.v) + hk * s.kv_stride[1];
-    const uint32_t row_stride = (uint32_t)s.kv_stride[2] * 2u;   // bytes
-
-    constexpr int PASSES = Stage<D>::PASSES;
-    const int slot0 = threadIdx.x / Stage<D>::PPR;
-    // key position of this thread's staging slots in block kb (-1 = no key)
-#define KASCADE_BLOCK_POS(kb_, pos_)                                                        \
-    _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                                  \
-        const int slot_ = i_ * Stage<D>::RPP + slot0;                                        \
-        int p_;                                                                              \
-        if (SPARSE && (kb_) < nb_gather) {                                                   \
-            const int j_ = (kb_) * BK + slot_;                                               \
-            p_ = j_ < n_sparse ? idx[j_] : -1;                                               \
-            if (p_ >= prefix) p_ = -1;                                                       \
-        } else {                                                                             \
-            p_ = (SPARSE ? prefix + ((kb_) - nb_gather) * BK : (kb_) * BK) + slot_;          \
-            if (p_ >= diag_end) p_ = -1;                                                     \
-        }                                                                                    \
-        pos_[i_] = p_;                                                                       \
-    }
-
-    // query fragments (B operand of S^T = K Q^T): row q of this wave, 8 elements per k-step
-    bf16x8_t qf[KSTEPS];
-    {
-        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
-            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
-        }
-    }
-
-    // (m_run, l_run): reference exponent and the sum of 2^(s c - m_run) over the keys seen so far;
-    // neg_ref = -m_run once a finite reference exists, +inf before (forces the exact path)
-    float m_run = -INFINITY, l_run = 0.f, neg_ref = INFINITY;
-    f32x16_t acc_o[WITH_V ? DBLK : 1];
-#pragma unroll
-    for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
-
-    if (threadIdx.x < 2) smFlag[threadIdx.x] = 0;
-
-    u32x4_t kr[PASSES], vr[PASSES];
-    int pos[PASSES];
-    const int n_seq = SPARSE ? 0 : prefix / BK;   // dense: blocks entirely before the tile, all slots valid
-    if (0 < n_seq) {
-        stage_issue_seq<D, WITH_V>(kr, vr, 0, Kb, Vb, row_stride);
-    } else {
-        KASCADE_BLOCK_POS(0, pos)
-        stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
-    }
-
-    const int key0 = perm_key(q), key1 = 32 + key0;
-
-    for (int kb = 0; kb < n_blocks; ++kb) {
-        __syncthreads();   // previous block fully consumed
-        if (kb < n_seq) {
-            stage_commit<D, WITH_V, true>(kr, vr, pos, smK, smVt, smPos);
-        } else {
-            if (stage_commit<D, WITH_V>(kr, vr, pos, smK, smVt, smPos)) smFlag[kb & 1] = 1;
-        }
-        __syncthreads();
-        if (kb + 1 < n_seq) {
-            stage_issue_seq<D, WITH_V>(kr, vr, kb + 1, Kb, Vb, row_stride);
-        } else if (kb + 1 < n_blocks) {
-            KASCADE_BLOCK_POS(kb + 1, pos)
-            stage_issue<D, WITH_V>(kr, vr, pos, Kb, Vb, row_stride);
-        }
-        if (threadIdx.x == 0) smFlag[(kb + 1) & 1] = 0;
-
-        // S^T block: rows = 64 keys (two MFMA tiles), cols = this wave's 32 queries
-        f32x16_t s0, s1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            const bf16x8_t a0 = lds_frag(smK + k_off<D>(key0, kk * 2 + h));
-            const bf16x8_t a1 = lds_frag(smK + k_off<D>(key1, kk * 2 + h));
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[kk], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[kk], s1, 0, 0, 0);
-        }
-        // mask: causal inside / beyond the diagonal, and invalid slots
-        bool need_mask = smFlag[kb & 1] != 0;
-        if constexpr (SPARSE) need_mask |= kb >= nb_gather;
-        else need_mask |= (kb + 1) * BK > prefix;
-        if (need_mask) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int slot = (r >> 3) * 16 + h * 8 + (r & 7);
-                if (smPos[slot] > q_token) s0[r] = -INFINITY;
-                if (smPos[32 + slot] > q_token) s1[r] = -INFINITY;
-            }
-        }
-        // Online softmax, base 2; this lane owns query row q (the other half-wave holds the other
-        // keys of the same row).  The exponentials are taken against a reference that may lag the
-        // true running maximum: any reference gives the same quotient acc / l as long as nothing
-        // overflows, so the block maximum is only looked at when a term exceeds 2^kLag (or is not
-        // finite, which is how the first block gets its reference).  That rare path is wave-uniform.
-        constexpr float kLag = 1073741824.f;   // 2^30
-        f32x16_t e0, e1;
-        float rs = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, neg_ref));
-            e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg_ref));
-            rs += e0[r] + e1[r];
-        }
-        if (__builtin_amdgcn_ballot_w64(!(rs <= kLag)) != 0) {
-            float mx = s0[0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
-            mx *= c;
-            mx = half_swap_max(mx);
-            const float m_new = fmaxf(m_run, mx);
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
-            rs = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));
-                e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));
-                rs += e0[r] + e1[r];
-            }
-            l_run *= alpha;
-            if constexpr (WITH_V) {
-#pragma unroll
-                for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
-            }
-            m_run = m_new;
-            neg_ref = -m_safe;
-        }
-        rs = half_swap_sum(rs);
-        l_run += rs;
-
-        if constexpr (WITH_V) {
-            bf16x8_t pf[4];
-            pf[0] = pack_p(e0, 0); pf[1] = pack_p(e0, 8); pf[2] = pack_p(e1, 0); pf[3] = pack_p(e1, 8);
-#pragma unroll
-            for (int i = 0; i < DBLK; ++i) {
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    const bf16x8_t va = vt_frag<D>(smVt, i, st * 16);
-                    acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[st], acc_o[i], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-#undef KASCADE_BLOCK_POS
-    if (!rm.ok) return;
-    if (a.stats && h == 0) {
-        float* st = a.stats + ((int64_t)rm.head * S + rm.token) * 2;
-        st[0] = m_run;
-        st[1] = l_run;
-    }
-    if constexpr (WITH_V) {
-        const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-        bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + (int64_t)rm.token * s.o_stride[1] + (int64_t)rm.head * s.o_stride[2];
-#pragma unroll
-        for (int i = 0; i < DBLK; ++i) {
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const int d0 = i * 32 + r4 * 8 + h * 4;
-                uint2 pk;
-                pk.x = pack_bf16(acc_o[i][r4 * 4 + 0] * inv, acc_o[i][r4 * 4 + 1] * inv);
-                pk.y = pack_bf16(acc_o[i][r4 * 4 + 2] * inv, acc_o[i][r4 * 4 + 3] * inv);
-                *reinterpret_cast<uint2*>(op + d0) = pk;
-            }
-        }
-    }
-}
-
-template <int D>
-__global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillArgs a) {
-    constexpr int KSTEPS = D / 16;
-    __shared__ __align__(16) unsigned char smK[BK * D * 2];
-    __shared__ int smPos[BK];
-    __shared__ float smPart[kPW][BK];
-
-    const int hk = blockIdx.x % s.Hkv;
-    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
-    const int T = a.tile_tokens, S = a.seqlen;
-    const int prefix = t * T;
-    if (prefix == 0) return;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int q = lane & 31, h = lane >> 5;
-    const float c = s.scale_log2;
-    const int diag_end = (prefix + T < S) ? prefix + T : S;
-    const float inv_rows = 1.f / (float)((diag_end - prefix) * s.G);
-    const int n_blocks = (prefix + BK - 1) / BK;
-
-    const bf16_t* Kb = reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1];
-    const uint32_t row_stride = (uint32_t)s.kv_stride[2] * 2u;   // bytes
-
-    // A operand: query row q of this wave
-    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
-    bf16x8_t qf[KSTEPS];
-    {
-        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
-            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
-        }
-    }
-    // per query row whose scores land in this lane's registers: e_r = m + log2(l * rows), so that the
-    // pooled weight of a score is 2^(s c - e_r); rows beyond the sequence get weight 0
-    float e_r[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const RowMap rr = map_row(w * 32 + (r >> 2) * 8 + h * 4 + (r & 3), t, T, hk, s.G, S);
-        e_r[r] = INFINITY;
-        if (rr.ok) {
-            const float* st = a.stats + ((int64_t)rr.head * S + rr.token) * 2;
-            e_r[r] = st[0] + __builtin_amdgcn_logf(st[1] / inv_rows);
-        }
-    }
-
-    constexpr int PASSES = Stage<D>::PASSES;
-    const int slot0 = threadIdx.x / Stage<D>::PPR;
-    u32x4_t kr[PASSES], vr[PASSES];
-    int pos[PASSES];
-    const int n_seq = prefix / BK;   // blocks without a ragged end
-    if (0 < n_seq) {
-        stage_issue_seq<D, false>(kr, vr, 0, Kb, nullptr, row_stride);
-    } else {
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) { const int p = i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
-        stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
-    }
-    const int key0 = perm_key(q), key1 = 32 + key0;
-    float* dst = a.pooled + hk * a.pooled_pitch + (int64_t)T * t * (t - 1) / 2;
-
-    for (int kb = 0; kb < n_blocks; ++kb) {
-        __syncthreads();
-        if (kb < n_seq) stage_commit<D, false, true>(kr, vr, pos, smK, nullptr, smPos);
-        else stage_commit<D, false>(kr, vr, pos, smK, nullptr, smPos);
-        __syncthreads();
-        if (kb + 1 < n_seq) {
-            stage_issue_seq<D, false>(kr, vr, kb + 1, Kb, nullptr, row_stride);
-        } else if (kb + 1 < n_blocks) {
-#pragma unroll
-            for (int i = 0; i < PASSES; ++i) { const int p = (kb + 1) * BK + i * Stage<D>::RPP + slot0; pos[i] = p < prefix ? p : -1; }
-            stage_issue<D, false>(kr, vr, pos, Kb, nullptr, row_stride);
-        }
-
-        f32x16_t s0, s1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            const bf16x8_t b0 = lds_frag(smK + k_off<D>(key0, kk * 2 + h));
-            const bf16x8_t b1 = lds_frag(smK + k_off<D>(key1, kk * 2 + h));
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b0, s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b1, s1, 0, 0, 0);
-        }
-        float c0 = 0.f, c1 = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            c0 += __builtin_amdgcn_exp2f(fmaf(s0[r], c, -e_r[r]));
-            c1 += __builtin_amdgcn_exp2f(fmaf(s1[r], c, -e_r[r]));
-        }
-        c0 = half_swap_sum(c0);
-        c1 = half_swap_sum(c1);
-        if (h == 0) { smPart[w][key0] = c0; smPart[w][key1] = c1; }
-        __syncthreads();
-        if (threadIdx.x < BK) {
-            const int j = kb * BK + threadIdx.x;
-            if (j < prefix) dst[j] = (smPart[0][threadIdx.x] + smPart[1][threadIdx.x]) + (smPart[2][threadIdx.x] + smPart[3][threadIdx.x]);
-        }
-    }
 }
 
 // ---- direct global -> LDS staging ---------------------------------------------------------
@@ -657,6 +286,41 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     const int key0 = perm_key(q), key1 = 32 + key0;
     int f_cur = 0, f_next = 1, f_free = 2;   // smFlag slots of block kb, kb+1 and the one to clear for kb+2
 
+    // S^T block: rows = 64 keys (two MFMA tiles), cols = this wave's 32 queries; then the masks:
+    // causal inside / beyond the diagonal, and slots without a key.  Fragment reads run four k-steps
+    // ahead of the products that use them.
+#define KASCADE_SCORES(tK_, buf_, kb_)                                                                       \
+    {                                                                                                        \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }                          \
+        bf16x8_t fa_[KSTEPS], fb_[KSTEPS];                                                                   \
+        _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                                               \
+            fa_[kk] = lds_frag(tK_ + k_off<D>(key0, kk * 2 + h));                                            \
+            fb_[kk] = lds_frag(tK_ + k_off<D>(key1, kk * 2 + h));                                            \
+        }                                                                                                    \
+        _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                                               \
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[kk], qf[kk], s0, 0, 0, 0);                      \
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[kk], qf[kk], s1, 0, 0, 0);                      \
+        }                                                                                                    \
+        if constexpr (WITH_V) {   /* these variants have registers to spare */                               \
+            __builtin_amdgcn_sched_group_barrier(0x100, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                    \
+            _Pragma("unroll") for (int kk = 0; kk + 4 < KSTEPS; ++kk) {                                       \
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                           \
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                           \
+            }                                                                                                \
+            __builtin_amdgcn_sched_group_barrier(0x008, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                    \
+        }                                                                                                    \
+        bool need_mask = smFlag[f_cur] != 0;                                                                 \
+        if constexpr (SPARSE) need_mask |= (kb_) >= nb_gather;                                               \
+        else need_mask |= ((kb_) + 1) * BK > prefix;                                                         \
+        if (need_mask) {                                                                                     \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
+                const int slot = (r >> 3) * 16 + h * 8 + (r & 7);                                            \
+                if (smPos[buf_][slot] > q_token) s0[r] = -INFINITY;                                          \
+                if (smPos[buf_][32 + slot] > q_token) s1[r] = -INFINITY;                                     \
+            }                                                                                                \
+        }                                                                                                    \
+    }
+
     // one block; buf_ is a literal
 #define KASCADE_ATTEND_BLOCK(kb_, buf_)                                                                       \
     {                                                                                                        \
@@ -671,39 +335,21 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             KASCADE_BLOCK_RAW((kb_) + 2, pos)                                                                \
         }                                                                                                    \
         const unsigned char* tK_ = smK + (buf_) * TILE;                                                      \
-        /* S^T block: rows = 64 keys (two MFMA tiles), cols = this wave's 32 queries */                      \
         f32x16_t s0, s1;                                                                                     \
-        _Pragma("unroll") for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }                          \
-        _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                                               \
-            const bf16x8_t a0 = lds_frag(tK_ + k_off<D>(key0, kk * 2 + h));                                  \
-            const bf16x8_t a1 = lds_frag(tK_ + k_off<D>(key1, kk * 2 + h));                                  \
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[kk], s0, 0, 0, 0);                           \
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[kk], s1, 0, 0, 0);                           \
-        }                                                                                                    \
-        /* mask: causal inside / beyond the diagonal, and slots without a key */                             \
-        bool need_mask = smFlag[f_cur] != 0;                                                                 \
-        if constexpr (SPARSE) need_mask |= (kb_) >= nb_gather;                                               \
-        else need_mask |= ((kb_) + 1) * BK > prefix;                                                         \
-        if (need_mask) {                                                                                     \
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
-                const int slot = (r >> 3) * 16 + h * 8 + (r & 7);                                            \
-                if (smPos[buf_][slot] > q_token) s0[r] = -INFINITY;                                          \
-                if (smPos[buf_][32 + slot] > q_token) s1[r] = -INFINITY;                                     \
-            }                                                                                                \
-        }                                                                                                    \
+        KASCADE_SCORES(tK_, buf_, kb_)                                                                       \
         /* Online softmax, base 2; this lane owns query row q (the other half-wave holds the other keys   */ \
         /* of the same row).  The exponentials are taken against a reference that may lag the true running */ \
         /* maximum: any reference gives the same quotient acc / l as long as nothing overflows, so the     */ \
         /* block maximum is only looked at when a term exceeds 2^30 (or is not finite, which is how the    */ \
-        /* first block gets its reference).  That rare path is wave-uniform.                               */ \
-        f32x16_t e0, e1;                                                                                     \
+        /* first block gets its reference).  That rare path is wave-uniform and recomputes the scores.     */ \
         float rs = 0.f;                                                                                      \
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                      \
-            e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, neg_ref));                                         \
-            e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg_ref));                                         \
-            rs += e0[r] + e1[r];                                                                             \
+            s0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, neg_ref));                                         \
+            s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg_ref));                                         \
+            rs += s0[r] + s1[r];                                                                             \
         }                                                                                                    \
         if (__builtin_amdgcn_ballot_w64(!(rs <= 1073741824.f)) != 0) {                                       \
+            KASCADE_SCORES(tK_, buf_, kb_)                                                                   \
             float mx = s0[0];                                                                                \
             _Pragma("unroll") for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);                             \
             _Pragma("unroll") for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);                             \
@@ -714,9 +360,9 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   /* 0 while m_run is -inf */        \
             rs = 0.f;                                                                                        \
             _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
-                e0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));                                     \
-                e1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));                                     \
-                rs += e0[r] + e1[r];                                                                         \
+                s0[r] = __builtin_amdgcn_exp2f(fmaf(s0[r], c, -m_safe));                                     \
+                s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, -m_safe));                                     \
+                rs += s0[r] + s1[r];                                                                         \
             }                                                                                                \
             l_run *= alpha;                                                                                  \
             if constexpr (WITH_V) {                                                                          \
@@ -731,7 +377,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         if constexpr (WITH_V) {                                                                              \
             const unsigned char* tV_ = smV + (buf_) * TILE;                                                  \
             bf16x8_t pf[4];                                                                                  \
-            pf[0] = pack_p(e0, 0); pf[1] = pack_p(e0, 8); pf[2] = pack_p(e1, 0); pf[3] = pack_p(e1, 8);      \
+            pf[0] = pack_p(s0, 0); pf[1] = pack_p(s0, 8); pf[2] = pack_p(s1, 0); pf[3] = pack_p(s1, 8);      \
             _Pragma("unroll") for (int i = 0; i < DBLK; ++i) {                                                \
                 _Pragma("unroll") for (int st = 0; st < 4; ++st) {                                            \
                     const bf16x8_t va = vt_frag<D>(tV_, i, st * 16);                                         \
@@ -749,6 +395,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     }
     if (kb < n_blocks) { KASCADE_ATTEND_BLOCK(kb, 0) }
 #undef KASCADE_ATTEND_BLOCK
+#undef KASCADE_SCORES
 #undef KASCADE_STAGE_SEQ
 #undef KASCADE_STAGE
 #undef KASCADE_BLOCK_POS
@@ -808,7 +455,7 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
 // kb is multiplied; one barrier per block.  The cross-wave sum of block kb's column partials is
 // taken after the next barrier (two partial buffers), so it needs no barrier of its own.
 template <int D>
-__global__ __launch_bounds__(kPB, 4) void prefill_pool_dma_kernel(Shape s, PrefillArgs a) {
+__global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16;
     __shared__ __align__(16) unsigned char smK0[BK * D * 2];
     __shared__ __align__(16) unsigned char smK1[BK * D * 2];
@@ -894,11 +541,6 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_dma_kernel(Shape s, Prefi
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
     dim3 grid(a.n_tiles * s.Hkv), block(kPB);
 #define KASCADE_LAUNCH_ATTEND(DD)                                                                                      \
-    if (getenv("KASCADE_ATTEND_OLD")) {                                                                                \
-    if (sparse) hipLaunchKernelGGL((prefill_attend_old_kernel<DD, true, true>), grid, block, 0, st, s, a);             \
-    else if (with_v) hipLaunchKernelGGL((prefill_attend_old_kernel<DD, false, true>), grid, block, 0, st, s, a);       \
-    else hipLaunchKernelGGL((prefill_attend_old_kernel<DD, false, false>), grid, block, 0, st, s, a);                  \
-    } else                                                                                                             \
     if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true>), grid, block, 0, st, s, a);                 \
     else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true>), grid, block, 0, st, s, a);           \
     else hipLaunchKernelGGL((prefill_attend_kernel<DD, false, false>), grid, block, 0, st, s, a);
@@ -911,12 +553,6 @@ hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool spar
 
 hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t st) {
     dim3 grid(a.n_tiles * s.Hkv), block(kPB);
-    if (getenv("KASCADE_POOL_OLD") == nullptr) {
-        if (s.D == 128) hipLaunchKernelGGL((prefill_pool_dma_kernel<128>), grid, block, 0, st, s, a);
-        else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_dma_kernel<64>), grid, block, 0, st, s, a);
-        else return hipErrorInvalidValue;
-        return hipGetLastError();
-    }
     if (s.D == 128) hipLaunchKernelGGL((prefill_pool_kernel<128>), grid, block, 0, st, s, a);
     else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_kernel<64>), grid, block, 0, st, s, a);
     else return hipErrorInvalidValue;
