@@ -136,8 +136,17 @@ template <int D> struct Dma {
 // stage key rows row_first + slot (slot = 0..63), rows clamped to row_last, into `tile`
 template <int D>
 __device__ __forceinline__ void dma_rows_seq(unsigned char* tile, const unsigned char* base, uint32_t row_bytes,
-                                             int row_first, int row_last, uint32_t coff) {
-    const int r0 = threadIdx.x / Dma<D>::PPR, w = threadIdx.x >> 6;
+                                             int row_first, int row_last, uint32_t coff, int w) {
+    const int r0 = threadIdx.x / Dma<D>::PPR;
+    if (row_first + BK - 1 <= row_last) {   // every row exists: uniform block/pass offset + a constant per-thread part
+        const uint32_t tofs = (uint32_t)r0 * row_bytes + coff;
+#pragma unroll
+        for (int i = 0; i < Dma<D>::PASSES; ++i) {
+            const unsigned char* src = base + (size_t)(row_first + i * Dma<D>::RPP) * row_bytes + (size_t)tofs;
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)src, (lds_ptr_t)(tile + (i * kPB + w * kWave) * 16), 16, 0, 0);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < Dma<D>::PASSES; ++i) {
         int row = row_first + i * Dma<D>::RPP + r0;
@@ -165,7 +174,8 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     const int hk = blockIdx.x % s.Hkv;
     const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;   // long tiles first
     const int T = a.tile_tokens, S = a.seqlen;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, held in a scalar register
     const int q = lane & 31, h = lane >> 5;
     const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
     const int q_token = rm.ok ? rm.token : INT_MAX - 1;
@@ -194,6 +204,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     const int r0 = threadIdx.x / PPR, pp = threadIdx.x % PPR;
     const uint32_t koff = Dma<D>::chunk_off();
     const uint32_t voff = (uint32_t)((pp ^ ((D == 128) ? ((r0 & 3) << 2) : (((r0 >> 1) & 1) << 2))) << 4);
+    const uint32_t seq_k = (uint32_t)r0 * row_bytes + koff, seq_v = (uint32_t)r0 * row_bytes + voff;
 
     // Key position of this thread's staging slots in block kb (-1 = no key).  Gathered blocks take
     // two steps so that nothing waits on the index load when it is issued: KASCADE_BLOCK_RAW fetches
@@ -235,17 +246,17 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         }                                                                                                    \
         if (bad_) smFlag[flag_] = 1;                                                                         \
     }
-    // the same for a block of consecutive keys that all exist (no masks, no bookkeeping)
+    // the same for a block of consecutive keys that all exist (no masks, no bookkeeping): the block
+    // and pass offsets are uniform (scalar base), the per-thread part never changes
 #define KASCADE_STAGE_SEQ(buf_, kb_)                                                                         \
     {                                                                                                        \
-        const uint32_t base_ = (uint32_t)((kb_) * BK + r0) * row_bytes;                                      \
         _Pragma("unroll") for (int i_ = 0; i_ < PASSES; ++i_) {                                               \
-            const uint32_t off_ = base_ + (uint32_t)(i_ * RPP) * row_bytes;                                  \
+            const size_t blk_ = (size_t)((kb_) * BK + i_ * RPP) * row_bytes;                                  \
             unsigned char* dk_ = smK + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
-            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + (size_t)(off_ + koff)), (lds_ptr_t)dk_, 16, 0, 0); \
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + blk_ + (size_t)seq_k), (lds_ptr_t)dk_, 16, 0, 0); \
             if constexpr (WITH_V) {                                                                          \
                 unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                       \
-                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + (size_t)(off_ + voff)), (lds_ptr_t)dv_, 16, 0, 0); \
+                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + blk_ + (size_t)seq_v), (lds_ptr_t)dv_, 16, 0, 0); \
             }                                                                                                \
         }                                                                                                    \
     }
@@ -467,7 +478,8 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
     const int T = a.tile_tokens, S = a.seqlen;
     const int prefix = t * T;
     if (prefix == 0) return;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, held in a scalar register
     const int q = lane & 31, h = lane >> 5;
     const float c = s.scale_log2;
     const int diag_end = (prefix + T < S) ? prefix + T : S;
@@ -477,7 +489,7 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
     const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
     const uint32_t coff = Dma<D>::chunk_off();
-    dma_rows_seq<D>(smK0, Kb, row_bytes, 0, prefix - 1, coff);
+    dma_rows_seq<D>(smK0, Kb, row_bytes, 0, prefix - 1, coff, w);
 
     const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
     bf16x8_t qf[KSTEPS];
@@ -509,7 +521,7 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
     {                                                                                                          \
         wait_vmem();                                                                                           \
         __syncthreads();                                                                                       \
-        if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(nxt_, Kb, row_bytes, ((kb_) + 1) * BK, prefix - 1, coff);    \
+        if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(nxt_, Kb, row_bytes, ((kb_) + 1) * BK, prefix - 1, coff, w);    \
         if ((kb_) > 0 && threadIdx.x < BK) {                                                                   \
             const int j_ = ((kb_) - 1) * BK + threadIdx.x;                                                     \
             if (j_ < prefix)                                                                                   \
