@@ -369,6 +369,8 @@ int check_prefill(const kascade_desc* desc, const void* q, const void* k, const 
     if (desc->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
     // a query tile is 128 (token, head) rows: T tokens times the G heads of a key head
     if ((int64_t)T * (desc->n_q_heads / desc->n_kv_heads) != 128) return KASCADE_UNSUPPORTED;
+    // the kernels address the rows of one key head with 32-bit byte offsets
+    if ((int64_t)seqlen * desc->kv_stride[2] * 2 >= ((int64_t)1 << 32)) return KASCADE_UNSUPPORTED;
     if ((desc->o_stride[1] * 2) % 8 || (desc->o_stride[2] * 2) % 8) return KASCADE_MISALIGNED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || (reinterpret_cast<uintptr_t>(out) & 7u)) return KASCADE_MISALIGNED;
     return KASCADE_OK;

@@ -97,3 +97,25 @@ def test_binding_refuses_cpu_tensors(lib):
     idx = torch.zeros(1, 2, 4, dtype=torch.int32)
     with pytest.raises(RuntimeError, match="GPU"):
         binding.kascade_decode_reuse(q, k, k, sl, sl, 4, idx)
+
+
+def call_prefill_reuse(lib, d, S, T, q=0x1000, k=0x2000, v=0x3000, kpt=0x4000, off=0x5000, total=10, idx=0x6000,
+                       out=0x7000):
+    vp = ctypes.c_void_p
+    return lib.kascade_prefill_reuse(ctypes.byref(d), vp(q), vp(k), vp(v), S, T, vp(kpt), vp(off), total, vp(idx),
+                                     d.n_kv_heads, vp(0), vp(out), vp(0), 0, vp(0))
+
+
+def test_prefill_argument_checks(lib):
+    # fake pointers again: all of these return from validation
+    bf = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=binding.KASCADE_BF16,
+              q_stride=(0, 32 * 128, 128), kv_stride=(0, 4096 * 128, 128), o_stride=(0, 32 * 128, 128))
+    assert call_prefill_reuse(lib, make_desc(**bf), 4096, 64) == -2                       # T * G = 256
+    assert call_prefill_reuse(lib, make_desc(**{**bf, "dtype": binding.KASCADE_F32}), 4096, 32) == -2
+    assert call_prefill_reuse(lib, make_desc(**{**bf, "batch": 2}), 4096, 32) == -1
+    assert call_prefill_reuse(lib, make_desc(**bf), 0, 32) == -1
+    assert call_prefill_reuse(lib, make_desc(**bf), 4096, 32, idx=0) == -1
+    assert call_prefill_reuse(lib, make_desc(**bf), 4096, 32, k=0x2008) == -3
+    # one key head's rows must stay below 4 GiB: 2^24 tokens of 256 bytes are exactly 4 GiB
+    huge = {**bf, "kv_stride": (0, (1 << 24) * 128, 128)}
+    assert call_prefill_reuse(lib, make_desc(**huge), 1 << 24, 32) == -2
