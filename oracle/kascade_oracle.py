@@ -370,3 +370,23 @@ def head_map_from_similarity(sims):
     Reading: the paper aggregates over its development set without naming the statistic."""
     mean = np.asarray(sims, dtype=np.float64).mean(axis=0)
     return np.argmax(mean, axis=1).astype(np.int64), mean
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.5, first strategy: one Top-k set shared by all heads of a layer
+# ----------------------------------------------------------------------------
+
+def decode_shared_indices(q, K, scale, k, recent_window=0):
+    """Post-softmax distributions of ALL query heads averaged into one layer distribution
+    (the variant the paper reports as "all heads pooled"), then Top-k.
+    Returns (idx [k] ascending, pooled a [L])."""
+    a = decode_probabilities(q, K, scale).mean(axis=0)
+    return select_topk(a, k, recent_window), a
+
+
+def prefill_shared_indices_tile(Q, Kp, t, T, scale, k_t):
+    """The same for a prefill tile: mean over the tile's tokens and all query heads of the causal
+    post-softmax weight of each prefix key, then Top-k_t.  Returns (idx [k_t], pooled a [t*T])."""
+    P = prefill_tile_probabilities(Q, Kp, t, T, scale)
+    a = P[:, :, : t * T].mean(axis=(0, 1))
+    return select_topk(a, k_t, 0), a

@@ -455,3 +455,35 @@ def test_head_map_many_to_one_and_ties():
     sims[:, 2] = [0.5, 0.5]                   # tie -> lower anchor head
     hm, _ = ko.head_map_from_similarity(sims)
     assert hm.tolist() == [0, 0, 0]
+
+
+# ------------------------------------------------------------------ shared (all heads pooled) sets
+
+def test_shared_indices_are_the_mean_of_the_per_head_pooled_scores():
+    r = rng(61)
+    Hq, Hkv, d, L, k = 8, 2, 16, 90, 9
+    q, K = r.standard_normal((Hq, d)), r.standard_normal((Hkv, L, d))
+    idx, a = ko.decode_shared_indices(q, K, 0.3, k)
+    _, per_head = ko.decode_anchor_indices(q, K, 0.3, k)
+    np.testing.assert_allclose(a, per_head.mean(axis=0), atol=1e-15)      # equal group sizes: mean of means
+    np.testing.assert_allclose(a.sum(), 1.0, atol=1e-12)
+    lib = torch.topk(torch.from_numpy(a), k).indices.sort().values.numpy()
+    np.testing.assert_array_equal(idx, lib)
+    # one key head: the shared set is that head's set
+    idx1, _ = ko.decode_shared_indices(q[:4], K[:1], 0.3, k)
+    per1, _ = ko.decode_anchor_indices(q[:4], K[:1], 0.3, k)
+    np.testing.assert_array_equal(idx1, per1[0])
+
+
+def test_shared_prefill_indices_match_decode_for_single_token_tiles():
+    r = rng(62)
+    S, Hq, Hkv, d = 12, 4, 2, 8
+    Q, Kp = r.standard_normal((S, Hq, d)), r.standard_normal((Hkv, S, d))
+    t, k_t = 9, 4
+    idx, a = ko.prefill_shared_indices_tile(Q, Kp, t, 1, 0.5, k_t)
+    # T = 1: the tile is token t; its prefix scores are the decode probabilities over keys 0..t
+    p = ko.decode_probabilities(Q[t], Kp[:, : t + 1], 0.5).mean(axis=0)
+    np.testing.assert_allclose(a, p[:t], atol=1e-15)
+    np.testing.assert_array_equal(idx, ko.select_topk(p[:t], k_t))
+    per_head = ko.prefill_pooled_tile(Q, Kp, t, 1, 0.5)
+    np.testing.assert_allclose(a, per_head.mean(axis=0), atol=1e-15)
