@@ -140,6 +140,26 @@ int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Shared index sets (Sec. 3.5, the "all heads pooled" variant): the anchor calls above with the pooled
+ * distributions of all key heads averaged into one per sequence (decode) or per tile (prefill), so one
+ * Top-k set serves every head of the layer.  Same arguments, checks and workspace sizes as
+ * kascade_decode_anchor / kascade_prefill_anchor, except
+ *   idx_out  decode: [B,1,k_max];  prefill: [1,idx_total]
+ * Reuse layers consume such a set through kascade_decode_reuse / kascade_prefill_reuse with
+ * n_anchor_heads = 1 and a head_map of Hkv zeros.
+ */
+int kascade_decode_anchor_shared(const kascade_desc* desc, const void* q, const void* k_cache,
+                                 const void* v_cache, const int32_t* seqlens, const int32_t* k_per_seq,
+                                 int32_t max_seqlen, int32_t k_max, int32_t recent_window,
+                                 int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+int kascade_prefill_anchor_shared(const kascade_desc* desc, const void* q, const void* k, const void* v,
+                                  int32_t seqlen, int32_t q_tile_tokens, const int32_t* k_per_tile,
+                                  const int64_t* idx_offsets, int64_t idx_total, int32_t out_mode,
+                                  int32_t* idx_out, void* out, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream);
+
+/*
  * Calibration path (Sec. 3.3): which layers become anchors is decided once per model from how
  * well one layer's Top-k set recovers a later layer's attention mass (Eq. 3).
  *

@@ -106,7 +106,7 @@ DecodeReuseWs carve_decode_reuse(const Shape& s, const DecodePlan& plan, void* w
 }
 
 struct DecodeAnchorWs {
-    float* logits; float* pooled; float* st_ml; float* st_acc; uint32_t* hist11; int64_t pitch;
+    float* logits; float* pooled; float* st_ml; float* st_acc; uint32_t* hist11; int32_t* zero_map; int64_t pitch;
     DecodeReuseWs gather; size_t bytes;
 };
 DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, const DecodePlan& gather,
@@ -120,12 +120,13 @@ DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, con
     r.st_ml = c.take<float>(rows * 2);
     r.st_acc = c.take<float>(rows * s.D);
     r.hist11 = c.take<uint32_t>((size_t)s.B * s.Hkv * 2048);
+    r.zero_map = c.take<int32_t>((size_t)s.Hkv);
     r.gather = carve_decode_reuse(s, gather, ws, c.used);
     r.bytes = r.gather.bytes;
     return r;
 }
 
-struct PrefillWs { float* stats; float* pooled; int64_t pooled_pitch; size_t bytes; };
+struct PrefillWs { float* stats; float* pooled; int32_t* zero_map; int64_t pooled_pitch; size_t bytes; };
 PrefillWs carve_prefill_anchor(const Shape& s, int64_t S, int T, void* ws) {
     Carver c(ws);
     PrefillWs r;
@@ -133,6 +134,7 @@ PrefillWs carve_prefill_anchor(const Shape& s, int64_t S, int T, void* ws) {
     r.pooled_pitch = round_up_i((int64_t)T * n_tiles * (n_tiles - 1) / 2 + 4, 4);
     r.stats = c.take<float>((size_t)s.Hq * S * 2);
     r.pooled = c.take<float>((size_t)s.Hkv * r.pooled_pitch);
+    r.zero_map = c.take<int32_t>((size_t)s.Hkv);
     r.bytes = c.used;
     return r;
 }
@@ -144,11 +146,11 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // Events are created on demand and kept until profiling is disabled; with profiling off
 // the library creates nothing.
 enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
-                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_COUNT };
+                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_POOL_HEADS, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
     "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel",
-    "similarity", "head_map", "layer_importance"};
+    "similarity", "head_map", "layer_importance", "pool_heads"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
@@ -298,10 +300,10 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
     return st;
 }
 
-int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
-                          const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
-                          int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+static int decode_anchor_impl(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
+                              int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream, bool shared) {
     int st = check_desc(desc, false);
     if (st != KASCADE_OK) return st;
     if (!q || !k_cache || !v_cache || !seqlens || !k_per_seq || !idx_out || !out) return KASCADE_INVALID_ARG;
@@ -336,22 +338,48 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
     pa.pooled_pitch = ws.pitch; pa.hist11 = ws.hist11; pa.max_seqlen = max_seqlen;
     st = timed(K_POOL, stream, [&] { return launch_decode_pool(s, sp.n_chunks, pa, stream); });
     if (st != KASCADE_OK) return st;
-    // pass 3: Top-k per (sequence, key head)
+    // shared variant: one distribution per sequence = mean over the key heads (written over head 0's row)
+    if (shared) {
+        st = timed(K_POOL_HEADS, stream, [&] {
+            return launch_pool_heads(ws.pooled, (int64_t)s.Hkv * ws.pitch, ws.pitch, s.Hkv, s.B, max_seqlen, seqlens,
+                                     ws.zero_map, stream);
+        });
+        if (st != KASCADE_OK) return st;
+    }
+    // pass 3: Top-k per (sequence, key head); shared: per sequence, without the per-head histograms
+    Shape ts = s;
     TopkArgs t = {};
     t.scores = ws.pooled; t.hist11 = ws.hist11; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
     t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window;
-    st = timed(K_TOPK, stream, [&] { return launch_topk_decode(s, t, stream); });
+    if (shared) { ts.Hkv = 1; t.hist11 = nullptr; t.pitch = (int64_t)s.Hkv * ws.pitch; }
+    st = timed(K_TOPK, stream, [&] { return launch_topk_decode(ts, t, stream); });
     if (st != KASCADE_OK || dense) return st;
     // pass 4: attention over the fresh index set
     DecodeRowsArgs g = {};
     g.q = q; g.k = k_cache; g.v = v_cache; g.seqlens = seqlens; g.k_per_seq = k_per_seq;
-    g.idx = idx_out; g.head_map = nullptr; g.k_max = k_max; g.n_src_heads = s.Hkv;
+    g.idx = idx_out; g.head_map = shared ? ws.zero_map : nullptr; g.k_max = k_max; g.n_src_heads = shared ? 1 : s.Hkv;
     g.part_ml = ws.gather.part_ml; g.part_acc = ws.gather.part_acc; g.out = out;
     st = timed(K_GATHER, stream, [&] { return launch_decode_rows(s, gp, g, true, true, false, stream); });
     if (st != KASCADE_OK) return st;
     if (gp.n_chunks > 1)
         st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, gp.n_chunks, ws.gather.part_ml, ws.gather.part_acc, out, stream); });
     return st;
+}
+
+int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
+                          int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    return decode_anchor_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window, out_mode,
+                              idx_out, out, workspace, workspace_bytes, hip_stream, false);
+}
+
+int kascade_decode_anchor_shared(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                 const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
+                                 int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return decode_anchor_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window, out_mode,
+                              idx_out, out, workspace, workspace_bytes, hip_stream, true);
 }
 
 }  // extern "C"
@@ -389,10 +417,10 @@ PrefillArgs prefill_args(const void* q, const void* k, const void* v, void* out,
 
 extern "C" {
 
-int kascade_prefill_anchor(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
-                           int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
-                           int64_t idx_total, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+static int prefill_anchor_impl(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
+                               int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
+                               int64_t idx_total, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                               size_t workspace_bytes, void* hip_stream, bool shared) {
     int st = check_prefill(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, idx_out, out);
     if (st != KASCADE_OK) return st;
     if (out_mode != KASCADE_OUT_DENSE && out_mode != KASCADE_OUT_SPARSE) return KASCADE_INVALID_ARG;
@@ -411,15 +439,40 @@ int kascade_prefill_anchor(const kascade_desc* desc, const void* q, const void* 
     // pass 2: recompute scores over the prefix, normalise, pool the tile's rows
     st = timed(K_PF_SWEEP2, stream, [&] { return launch_prefill_pool(s, a, stream); });
     if (st != KASCADE_OK) return st;
-    // pass 3: Top-k per (tile, key head)
+    // shared variant: one distribution per tile = mean over the key heads (written over head 0's row)
+    if (shared) {
+        st = timed(K_POOL_HEADS, stream, [&] {
+            return launch_pool_heads(ws.pooled, 0, ws.pooled_pitch, s.Hkv, 1, ws.pooled_pitch, nullptr, ws.zero_map, stream);
+        });
+        if (st != KASCADE_OK) return st;
+    }
+    // pass 3: Top-k per (tile, key head); shared: per tile
+    Shape ts = s;
+    if (shared) ts.Hkv = 1;
     TopkArgs t = {};
     t.scores = ws.pooled; t.idx_out = idx_out; t.k_per_tile = k_per_tile; t.idx_offsets = idx_offsets;
     t.idx_total = idx_total; t.pooled_pitch = ws.pooled_pitch; t.tile_tokens = q_tile_tokens; t.n_tiles = a.n_tiles;
-    st = timed(K_PF_TOPK, stream, [&] { return launch_topk_prefill(s, t, stream); });
+    st = timed(K_PF_TOPK, stream, [&] { return launch_topk_prefill(ts, t, stream); });
     if (st != KASCADE_OK || dense) return st;
     // pass 4: sparse attention over the fresh sets
-    a.stats = nullptr; a.idx = idx_out; a.head_map = nullptr; a.n_src_heads = s.Hkv;
+    a.stats = nullptr; a.idx = idx_out; a.head_map = shared ? ws.zero_map : nullptr; a.n_src_heads = shared ? 1 : s.Hkv;
     return timed(K_PF_SPARSE, stream, [&] { return launch_prefill_attend(s, a, true, true, stream); });
+}
+
+int kascade_prefill_anchor(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
+                           int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
+                           int64_t idx_total, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    return prefill_anchor_impl(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, out_mode, idx_out,
+                               out, workspace, workspace_bytes, hip_stream, false);
+}
+
+int kascade_prefill_anchor_shared(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,
+                                  int32_t q_tile_tokens, const int32_t* k_per_tile, const int64_t* idx_offsets,
+                                  int64_t idx_total, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+    return prefill_anchor_impl(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, out_mode, idx_out,
+                               out, workspace, workspace_bytes, hip_stream, true);
 }
 
 int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,

@@ -1,5 +1,6 @@
 // Calibration-time kernels: similarity of two layers' Top-k sets (Eq. 3), head map from the
-// head-level similarity (Sec. 3.5), layer importance (Sec. 3.3).
+// head-level similarity (Sec. 3.5), layer importance (Sec. 3.3); and the mean over heads behind the
+// shared (all heads pooled) index sets of Sec. 3.5.
 //
 // For one (sequence, key head) segment the similarity of layer a's set applied to layer b is
 // the pooled attention mass of layer b that a's set recovers, over the mass b's own set
@@ -92,7 +93,43 @@ __global__ __launch_bounds__(kSimBlock) void importance_kernel(const T* x, const
     if (lane == 0) w_out[row] = 1.f - xy / (sqrtf(xx) * sqrtf(yy));
 }
 
+// grid (ceil(n / 1024), n_batches), 256 threads, four consecutive values per thread; heads are added
+// in ascending order (bit-stable) and the mean overwrites head 0's row
+__global__ __launch_bounds__(kSimBlock) void pool_heads_kernel(float* rows, int64_t batch_pitch, int64_t head_pitch,
+                                                               int n_heads, int64_t n, const int32_t* lens,
+                                                               int32_t* zero_map) {
+    const int b = blockIdx.y;
+    if (blockIdx.x == 0 && b == 0 && threadIdx.x < n_heads) zero_map[threadIdx.x] = 0;
+    const int64_t len = lens ? (int64_t)lens[b] : n;
+    const int64_t j = ((int64_t)blockIdx.x * kSimBlock + threadIdx.x) * 4;
+    if (j >= len) return;
+    float* base = rows + b * batch_pitch + j;
+    const float inv = 1.f / (float)n_heads;
+    if (j + 3 < len) {
+        float4 acc = *reinterpret_cast<const float4*>(base);
+        for (int h = 1; h < n_heads; ++h) {
+            const float4 v = *reinterpret_cast<const float4*>(base + h * head_pitch);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(base) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    } else {
+        for (int e = 0; j + e < len; ++e) {
+            float acc = base[e];
+            for (int h = 1; h < n_heads; ++h) acc += base[h * head_pitch + e];
+            base[e] = acc * inv;
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_pool_heads(float* rows, int64_t batch_pitch, int64_t head_pitch, int n_heads, int n_batches, int64_t n,
+                             const int32_t* lens, int32_t* zero_map, hipStream_t st) {
+    const dim3 grid((unsigned)((n + kSimBlock * 4 - 1) / (kSimBlock * 4)), n_batches);
+    hipLaunchKernelGGL(pool_heads_kernel, grid, dim3(kSimBlock), 0, st, rows, batch_pitch, head_pitch, n_heads, n, lens,
+                       zero_map);
+    return hipGetLastError();
+}
 
 hipError_t launch_similarity(const SimilarityArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(similarity_kernel, dim3(a.Hkv, a.B, a.all_pairs ? a.n_heads_a : 1), dim3(kSimBlock), 0, st, a);

@@ -116,6 +116,13 @@ hipError_t launch_head_map(int B, int Hkv, int Ha, const float* sim, float* mean
 hipError_t launch_importance(int dtype, const void* x, const void* y, int64_t n_rows, int n_cols, int64_t x_stride,
                              int64_t y_stride, float* w_out, hipStream_t st);
 
+// ---- shared index sets (Sec. 3.5, all heads pooled) --------------------------------------
+// rows[batch][head][j] (head_pitch apart, batch_pitch between batches): row 0 of every batch becomes
+// the mean over the n_heads rows, for j < (lens ? lens[batch] : n).  Also writes n_heads zeros to
+// zero_map: the head map that sends every head of a layer to index set 0.
+hipError_t launch_pool_heads(float* rows, int64_t batch_pitch, int64_t head_pitch, int n_heads, int n_batches,
+                             int64_t n, const int32_t* lens, int32_t* zero_map, hipStream_t st);
+
 // ---- prefill -----------------------------------------------------------------------
 struct PrefillArgs {
     const void* q;                // [S, Hq, D] per q_stride
