@@ -246,7 +246,10 @@ __global__ __launch_bounds__(kTopkBlock) void topk_decode_kernel(Shape s, TopkAr
 }
 
 __global__ __launch_bounds__(kTopkBlock) void topk_prefill_kernel(Shape s, TopkArgs a) {
-    const int t = blockIdx.x, hk = blockIdx.y;
+    // long segments first (the last workgroups to start are then the shortest), key head = block mod
+    // Hkv as in the attention kernels, so a head's pooled scores are swept by the XCD that wrote them
+    const int hk = blockIdx.x % s.Hkv;
+    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
     const int64_t prefix = (int64_t)t * a.tile_tokens;
     int k = a.k_per_tile[t];
     k = k < 0 ? 0 : (k > prefix ? (int)prefix : k);
@@ -271,7 +274,7 @@ hipError_t launch_topk_decode(const Shape& s, const TopkArgs& a, hipStream_t st)
 }
 
 hipError_t launch_topk_prefill(const Shape& s, const TopkArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(topk_prefill_kernel, dim3(a.n_tiles, s.Hkv), dim3(kTopkBlock), 0, st, s, a);
+    hipLaunchKernelGGL(topk_prefill_kernel, dim3(a.n_tiles * s.Hkv), dim3(kTopkBlock), 0, st, s, a);
     return hipGetLastError();
 }
 
