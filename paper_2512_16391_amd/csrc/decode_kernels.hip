@@ -387,13 +387,10 @@ __global__ __launch_bounds__(kBlock, (PIPE ? 2 : 4)) void decode_rows_bf16_kerne
             else { row_ = (rows_) + r * LPR + (u0_) + u; valid_ = row_ < end; }                        \
             okv |= (valid_ ? 1u : 0u) << u;                                                            \
             const uint64_t off_ = (uint64_t)(valid_ ? row_ : 0) * row_bytes + lane_off;                \
-            if constexpr (GATHER) {                                                                    \
-                kbuf[u] = *reinterpret_cast<const u32x4_t*>(Kb + off_);                                \
-                if constexpr (WITH_V) vbuf[u] = *reinterpret_cast<const u32x4_t*>(Vb + off_);          \
-            } else {   /* the stream touches every row once: keep it out of the caches' way */          \
-                kbuf[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Kb + off_));     \
-                if constexpr (WITH_V) vbuf[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Vb + off_)); \
-            }                                                                                          \
+            /* every row is touched once per call: non-temporal loads do not allocate cache lines, so  */ \
+            /* they neither evict the logits / partials nor wait for dirty lines to be written back    */ \
+            kbuf[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Kb + off_));         \
+            if constexpr (WITH_V) vbuf[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Vb + off_)); \
         }                                                                                              \
     }
 #define KASCADE_COMPUTE(kbuf, vbuf, okv, u0_)                                                          \
