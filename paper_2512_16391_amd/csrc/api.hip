@@ -81,7 +81,16 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
 }
 // gather: about four workgroups per compute unit.  stream: many more, smaller workgroups - with
 // ragged sequence lengths whole chunks fall away and few large workgroups leave a long tail.
-DecodePlan plan_gather(const Shape& s, int64_t k_max) { return plan_rows(k_max, s.B * s.Hkv, kTargetBlocks, 256, 64, "KASCADE_GATHER_CHUNK"); }
+DecodePlan plan_gather(const Shape& s, int64_t k_max) {
+    DecodePlan p = plan_rows(k_max, s.B * s.Hkv, kTargetBlocks, 256, 64, "KASCADE_GATHER_CHUNK");
+    // 256 rows are a single pass of a workgroup; if that still leaves three or more workgroups per compute
+    // unit, two passes per workgroup amortise its start-up and merge better (measured, cold caches)
+    if (p.chunk == 256 && !getenv("KASCADE_GATHER_CHUNK") && (int64_t)p.n_chunks * s.B * s.Hkv >= 3 * 256) {
+        p.chunk = 512;
+        p.n_chunks = (int)((k_max + 511) / 512);
+    }
+    return p;
+}
 DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 16 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
 
 struct Carver {
