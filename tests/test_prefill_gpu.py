@@ -316,3 +316,63 @@ def test_prefill_anchor_logits_rising_and_falling_along_the_keys(out_mode):
     # logit of key j ~ 4 * ramp[j] / sqrt(d): up to 85 nats (122 in base 2), i.e. several reference updates
     kpt = workloads.prefill_budgets(S, T, 100, 24)
     run_anchor(q, k, v, T, kpt, out_mode, where="ramp")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_prefill_reuse_random_shapes(seed):
+    """Seeded random shapes: both head dimensions, every group size, lengths that end inside a tile and
+    inside a 64-key block, budgets around the block size, unordered lists with entries to ignore."""
+    rs = np.random.default_rng(1000 + seed)
+    d = [64, 128][seed % 2]
+    G = [1, 2, 4, 8][(seed // 2) % 4]
+    T = 128 // G
+    Hkv = int(rs.integers(1, 4))
+    Hq = Hkv * G
+    S = int(rs.integers(T + 1, 6 * T + 40))
+    n_tiles = (S + T - 1) // T
+    n_anchor = int(rs.integers(1, Hkv + 1))
+    hm = rs.integers(0, n_anchor, size=Hkv).tolist()
+    kpt = [int(min(t * T, rs.choice([0, 1, 63, 64, 65, 100, 129]))) for t in range(n_tiles)]
+    off = offsets(kpt)
+    print(f"case prefill reuse random seed={seed}: S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} anchors={n_anchor} k_t={kpt}", flush=True)
+    q, k, v = random_prefill(2000 + seed, S, Hq, Hkv, d)
+    idx = np.full((n_anchor, max(off[-1], 1)), -1, dtype=np.int32)
+    sets = {}
+    for t in range(n_tiles):
+        sets[t] = []
+        for h in range(n_anchor):
+            kt = kpt[t]
+            n_bad = int(min(kt, rs.integers(0, 3)))
+            good = rs.permutation(rs.choice(t * T, kt - n_bad, replace=False)) if kt - n_bad > 0 else np.zeros(0, np.int64)
+            bad = rs.choice([-1, -7, t * T, t * T + 3, S + 5], size=n_bad)
+            row = rs.permutation(np.concatenate([good, bad]).astype(np.int64))
+            idx[h, off[t]:off[t] + kt] = row
+            sets[t].append(np.asarray(good, dtype=np.int64))
+    out = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                        torch.from_numpy(idx).to(DEV), head_map=dev_i32(hm), n_anchor_heads=n_anchor)
+    torch.cuda.synchronize()
+    Q, Kp, Vp = f64(q), f64(k), f64(v)
+    o = f64(out)
+    worst = 0.0
+    for t in range(n_tiles):
+        lo, hi = ko.tile_bounds(t, T, S)
+        ref = ko.prefill_sparse_tile(Q, Kp, Vp, t, T, sets[t], ko.default_scale(d), head_map=hm)
+        worst = max(worst, max_abs(o[lo:hi], ref))
+    print(f"  max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[BF16]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_prefill_anchor_random_shapes(seed):
+    rs = np.random.default_rng(3000 + seed)
+    d = [128, 64][seed % 2]
+    G = [4, 1, 8, 2][(seed // 2) % 4]
+    T = 128 // G
+    Hkv = int(rs.integers(1, 3))
+    Hq = Hkv * G
+    S = int(rs.integers(2 * T + 1, 5 * T + 30))
+    n_tiles = (S + T - 1) // T
+    kpt = [int(min(t * T, rs.choice([1, 17, 64, 90]))) for t in range(n_tiles)]
+    print(f"case prefill anchor random seed={seed}: S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} k_t={kpt}", flush=True)
+    q, k, v = random_prefill(4000 + seed, S, Hq, Hkv, d)
+    run_anchor(q, k, v, T, kpt, seed % 2, where=f"random {seed}")
