@@ -313,3 +313,22 @@ def test_decode_config3_full_size_sampled():
         worst = max(worst, max_abs(f64(out_r[b]), ko.sparse_decode(f64(r.q[b]), f64(r.k[b, :, :L]), f64(r.v[b, :, :L]), sets, scale)))
         print(f"  cfg3 b{b} L={L} k={kb}: swaps {swaps}, worst max-abs {worst:.3e}", flush=True)
     assert worst <= TOL_OUT[wl.dtype]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_decode_anchor_random_shapes(seed):
+    """Seeded random shapes: both dtypes and head dimensions, every group size, ragged lengths down to a
+    single token, budgets from 1 to the whole sequence, with and without a recent window."""
+    rs = np.random.default_rng(5000 + seed)
+    dtype = [torch.bfloat16, torch.float32][seed % 2]
+    d = [128, 64][(seed // 2) % 2]
+    G = [4, 1, 8, 2, 4][seed % 5]
+    Hkv = int(rs.integers(1, 4))
+    Hq = Hkv * G
+    B = int(rs.integers(1, 5))
+    lens = [int(rs.choice([1, 2, 63, 64, 65, 257, 1000, 3000, 4097])) for _ in range(B)]
+    W = int(rs.choice([0, 0, 1, 16]))
+    ks = [int(min(L, max(W, rs.choice([1, 2, 31, 64, 100, 1500, L])))) for L in lens]
+    print(f"case decode anchor random seed={seed}: {dtype} d={d} Hq={Hq} Hkv={Hkv} lens={lens} ks={ks} W={W}", flush=True)
+    q, k, v = random_case(6000 + seed, B, Hq, Hkv, d, dtype, lens, Lmax=max(lens) + int(rs.integers(0, 70)))
+    run_anchor_case(q, k, v, lens, ks, min(W, min(ks)), seed % 2, dtype, where=f"random {seed}")
