@@ -93,6 +93,22 @@ DecodePlan plan_gather(const Shape& s, int64_t k_max) {
 }
 DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 16 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
 
+// Workgroups per segment of the decode selection.  One is the single-workgroup kernel; more pay two extra
+// launches, so the split is used only when segments are few (the chip would idle) and long.
+int plan_topk_parts(const Shape& s, int64_t max_seqlen) {
+    if (const char* e = getenv("KASCADE_TOPK_PARTS")) {
+        const int v = atoi(e);
+        return v < 1 ? 1 : (v > kTopkMaxParts ? kTopkMaxParts : v);
+    }
+    const int64_t segments = (int64_t)s.B * s.Hkv;
+    if (segments > 128 || max_seqlen < 65536) return 1;          // measured: no gain below 64k scores per segment
+    int64_t parts = 256 / segments;                               // about one workgroup per compute unit in total
+    const int64_t by_len = max_seqlen / 4096;                     // at least 4096 scores per part
+    if (parts > by_len) parts = by_len;
+    if (parts > kTopkMaxParts) parts = kTopkMaxParts;
+    return parts < 2 ? 1 : (int)parts;
+}
+
 struct Carver {
     char* base; size_t used;
     explicit Carver(void* p) : base(static_cast<char*>(p)), used(0) {}
@@ -116,6 +132,7 @@ DecodeReuseWs carve_decode_reuse(const Shape& s, const DecodePlan& plan, void* w
 
 struct DecodeAnchorWs {
     float* logits; float* pooled; float* st_ml; float* st_acc; uint32_t* hist11; int32_t* zero_map; int64_t pitch;
+    uint32_t* topk_cand; uint32_t* topk_seg; uint32_t* topk_part; int topk_parts;
     DecodeReuseWs gather; size_t bytes;
 };
 DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, const DecodePlan& gather,
@@ -130,6 +147,14 @@ DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, con
     r.st_acc = c.take<float>(rows * s.D);
     r.hist11 = c.take<uint32_t>((size_t)s.B * s.Hkv * 2048);
     r.zero_map = c.take<int32_t>((size_t)s.Hkv);
+    r.topk_parts = plan_topk_parts(s, max_seqlen);
+    r.topk_cand = r.topk_seg = r.topk_part = nullptr;
+    if (r.topk_parts > 1) {
+        const size_t segs = (size_t)s.B * s.Hkv;
+        r.topk_cand = c.take<uint32_t>(segs * kTopkCandCap);
+        r.topk_seg = c.take<uint32_t>(segs * 8);
+        r.topk_part = c.take<uint32_t>(segs * kTopkMaxParts * 2);
+    }
     r.gather = carve_decode_reuse(s, gather, ws, c.used);
     r.bytes = r.gather.bytes;
     return r;
@@ -345,6 +370,8 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     pa.seqlens = seqlens; pa.k_per_seq = k_per_seq; pa.k_max = k_max; pa.recent_window = recent_window;
     pa.logits = ws.logits; pa.logit_pitch = ws.pitch; pa.part_ml = ws.st_ml; pa.pooled = ws.pooled;
     pa.pooled_pitch = ws.pitch; pa.hist11 = ws.hist11; pa.max_seqlen = max_seqlen;
+    const bool split = ws.topk_parts > 1 && !shared;
+    pa.seg_info = split ? ws.topk_seg : nullptr;
     st = timed(K_POOL, stream, [&] { return launch_decode_pool(s, sp.n_chunks, pa, stream); });
     if (st != KASCADE_OK) return st;
     // shared variant: one distribution per sequence = mean over the key heads (written over head 0's row)
@@ -361,7 +388,13 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     t.scores = ws.pooled; t.hist11 = ws.hist11; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
     t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window;
     if (shared) { ts.Hkv = 1; t.hist11 = nullptr; t.pitch = (int64_t)s.Hkv * ws.pitch; }
-    st = timed(K_TOPK, stream, [&] { return launch_topk_decode(ts, t, stream); });
+    if (split) {
+        t.cand = ws.topk_cand; t.seg_info = ws.topk_seg; t.part_info = ws.topk_part; t.n_parts = ws.topk_parts;
+        t.max_seqlen = max_seqlen;
+        st = timed(K_TOPK, stream, [&] { return launch_topk_decode_split(ts, t, stream); });
+    } else {
+        st = timed(K_TOPK, stream, [&] { return launch_topk_decode(ts, t, stream); });
+    }
     if (st != KASCADE_OK || dense) return st;
     // pass 4: attention over the fresh index set
     DecodeRowsArgs g = {};

@@ -569,6 +569,7 @@ template <int G>
 __global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, DecodePoolArgs a) {
     const int b = blockIdx.z, hk = blockIdx.y;
     const int L = a.seqlens[b];
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.seg_info) a.seg_info[((int64_t)b * s.Hkv + hk) * 8] = 0u;
     if (blockIdx.x * kBlock * 4 >= L) return;   // uniform per workgroup
     int k = a.k_per_seq[b];
     k = k < 0 ? 0 : (k > L ? L : k);

@@ -65,6 +65,7 @@ struct DecodePoolArgs {
     int64_t pooled_pitch;
     uint32_t* hist11;
     int max_seqlen;
+    uint32_t* seg_info;           // split selection: [B, Hkv, 8] words, word 0 (candidate counter) cleared here; or null
 };
 hipError_t launch_decode_pool(const Shape& s, int n_chunks, const DecodePoolArgs& a, hipStream_t st);
 
@@ -84,6 +85,12 @@ struct TopkArgs {
     int64_t pitch;
     int32_t k_max;
     int32_t recent_window;
+    // decode, split selection (several workgroups per segment): null / 0 when unused
+    uint32_t* cand;               // [B, Hkv, kTopkCandCap] threshold-bucket candidates: low 20 score bits | part << 20
+    uint32_t* seg_info;           // [B, Hkv, 8]: candidate count, round-1 digit / rest / bucket size, THR, need_eq, fallback flag
+    uint32_t* part_info;          // [B, Hkv, kTopkMaxParts, 2]: scores above the bucket per part, then output offsets
+    int32_t n_parts;
+    int32_t max_seqlen;
     // prefill
     const int32_t* k_per_tile;
     const int64_t* idx_offsets;
@@ -92,7 +99,11 @@ struct TopkArgs {
     int32_t tile_tokens;
     int32_t n_tiles;
 };
+constexpr int kTopkCandCap = 8192;   // scores of the threshold bucket the selection keeps on chip
+constexpr int kTopkMaxParts = 64;
 hipError_t launch_topk_decode(const Shape& s, const TopkArgs& a, hipStream_t st);
+// the same selection with n_parts workgroups per segment (three launches); needs the first-round histogram
+hipError_t launch_topk_decode_split(const Shape& s, const TopkArgs& a, hipStream_t st);
 
 // ---- calibration: Top-k set similarity (Eq. 3) ----------------------------------------
 struct SimilarityArgs {

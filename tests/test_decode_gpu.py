@@ -332,3 +332,64 @@ def test_decode_anchor_random_shapes(seed):
     print(f"case decode anchor random seed={seed}: {dtype} d={d} Hq={Hq} Hkv={Hkv} lens={lens} ks={ks} W={W}", flush=True)
     q, k, v = random_case(6000 + seed, B, Hq, Hkv, d, dtype, lens, Lmax=max(lens) + int(rs.integers(0, 70)))
     run_anchor_case(q, k, v, lens, ks, min(W, min(ks)), seed % 2, dtype, where=f"random {seed}")
+
+
+# --------------------------------------------------------------------------- split selection
+# Few long segments: the Top-k of a segment is computed by several workgroups (three launches).
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,W", [(torch.bfloat16, 128, 8, 2, 0), (torch.float32, 64, 4, 1, 64),
+                                              (torch.bfloat16, 64, 8, 1, 5)])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_decode_anchor_split_selection_long_sequences(dtype, d, Hq, Hkv, W, out_mode):
+    print(f"case split selection {dtype} d={d} Hq={Hq} Hkv={Hkv} W={W} out_mode={out_mode}", flush=True)
+    lens, ks = [70001, 33000], [7000, max(W, 1)]      # max length >= 65536: several workgroups per segment
+    wl = workloads.make_decode_workload("split", 11, 1, 2, Hq, Hkv, d, dtype, lens, ks, 512, 0.8, recent_window=W)
+    a = wl.layers[0]
+    run_anchor_case(a.q, a.k, a.v, lens, ks, W, out_mode, dtype, where="split")
+
+
+def test_decode_anchor_split_selection_ties_across_parts():
+    """Every key row appears 40 times, spread over the whole sequence: exact ties cross the part
+    boundaries and the cut falls inside a tie group; the lowest positions must win."""
+    dtype, d, Hq, Hkv = torch.float32, 64, 4, 1
+    L, period = 70000, 1000
+    q, k, v = random_case(23, 1, Hq, Hkv, d, dtype, [L])
+    k[0, 0] = k[0, 0, :period].repeat(L // period, 1)
+    for kk in (1, 69, 70, 71, 4017, 69999):
+        idx, _ = binding.kascade_decode_anchor(q.to(DEV), k.to(DEV), v.to(DEV), i32([L]), i32([kk]), L, kk)
+        torch.cuda.synchronize()
+        ref, _ = ko.decode_anchor_indices(f64(q[0]), f64(k[0]), ko.default_scale(d), kk)
+        np.testing.assert_array_equal(idx[0, 0].cpu().numpy(), ref[0])
+
+
+def test_decode_anchor_split_selection_falls_back_when_all_scores_are_equal():
+    """Identical keys: every pooled score is 1/L, far more than the selection keeps on chip."""
+    dtype, d, Hq, Hkv = torch.bfloat16, 128, 4, 2
+    L, kk, W = 66000, 777, 10
+    q, k, v = random_case(29, 1, Hq, Hkv, d, dtype, [L])
+    k[0, :, :] = k[0, :, :1]
+    idx, out = binding.kascade_decode_anchor(q.to(DEV), k.to(DEV), v.to(DEV), i32([L]), i32([kk]), L, kk,
+                                             recent_window=W)
+    torch.cuda.synchronize()
+    want = np.concatenate([np.arange(kk - W), np.arange(L - W, L)])
+    for h in range(Hkv):
+        np.testing.assert_array_equal(idx[0, h].cpu().numpy(), want)
+    ref = ko.sparse_decode(f64(q[0]), f64(k[0]), f64(v[0]), [want] * Hkv, ko.default_scale(d))
+    assert max_abs(f64(out)[0], ref) <= TOL_OUT[dtype]
+
+
+def test_decode_anchor_split_and_single_selection_agree(monkeypatch):
+    dtype, d, Hq, Hkv = torch.bfloat16, 128, 8, 2
+    lens, ks = [45000, 36000, 66000], [4500, 3600, 1]
+    wl = workloads.make_decode_workload("split-ab", 12, 1, 3, Hq, Hkv, d, dtype, lens, ks, 700, 0.8)
+    a = wl.layers[0]
+    args = (a.q.to(DEV), a.k.to(DEV), a.v.to(DEV), i32(lens), i32(ks), max(lens), max(ks))
+    res = {}
+    for parts in ("1", "7", "64"):
+        monkeypatch.setenv("KASCADE_TOPK_PARTS", parts)
+        idx, out = binding.kascade_decode_anchor(*args)
+        torch.cuda.synchronize()
+        res[parts] = (idx.clone(), out.clone())
+    for parts in ("7", "64"):
+        assert torch.equal(res[parts][0], res["1"][0])
+        assert torch.equal(res[parts][1], res["1"][1])
