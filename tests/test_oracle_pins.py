@@ -371,7 +371,9 @@ def brute_force_anchors(S, M):
     return best, best_val
 
 
-@pytest.mark.parametrize("L,M,seed", [(6, 2, 0), (8, 3, 1), (9, 4, 2), (10, 5, 3), (7, 1, 4), (5, 5, 5)])
+@pytest.mark.parametrize("L,M,seed", [(6, 2, 0), (8, 3, 1), (9, 4, 2), (10, 5, 3), (7, 1, 4), (5, 5, 5),
+                                      # matrices on which splitting greedily is not optimal
+                                      (11, 4, 6), (7, 3, 8), (8, 3, 8), (9, 4, 10), (8, 3, 11)])
 def test_anchor_selection_matches_exhaustive_search(L, M, seed):
     S = rng(200 + seed).random((L, L))
     got = ko.select_anchor_layers(S, M)
