@@ -323,13 +323,19 @@ class PrefillBench:
 
 def load_traffic():
     """HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same
-    command (scaled by the 1 GiB copy above); the summary lives in profiles/hbm_traffic.json."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    command (scaled by the 1 GiB copy above): the table in profiles/bench_cfg2_cfg4_hbm_traffic.txt
+    (columns: kernel, read MB, write MB, total MB)."""
+    path = os.path.join(ROOT, "profiles", "bench_cfg2_cfg4_hbm_traffic.txt")
+    out = {}
     try:
         with open(path) as f:
-            return {k: v.get("bytes_per_launch") for k, v in json.load(f).get("kernels", {}).items()}
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and not line.startswith("#") and parts[0] != "kernel":
+                    out[parts[0]] = float(parts[3]) * 1e6
     except (OSError, ValueError):
         return {}
+    return out
 
 
 def _blas_threads():
