@@ -338,6 +338,12 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         wait_vmem();                                                                                         \
         __syncthreads();   /* tile kb_ has landed; nobody reads the other buffer any more */                 \
         if (threadIdx.x == 0) smFlag[f_free] = 0;                                                            \
+        const unsigned char* tK_ = smK + (buf_) * TILE;                                                      \
+        f32x16_t s0, s1;                                                                                     \
+        KASCADE_SCORES(tK_, buf_, kb_)                                                                       \
+        /* The loads of the next block are issued here, behind this block's score products, not right   */ \
+        /* after the barrier: there every wave of the compute unit would issue its loads at once and     */ \
+        /* queue behind the others while its matrix work waits.                                          */ \
         if ((kb_) + 1 < n_seq) {                                                                             \
             KASCADE_STAGE_SEQ(1 - (buf_), (kb_) + 1)                                                         \
         } else if ((kb_) + 1 < n_blocks) {                                                                   \
@@ -345,9 +351,6 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             KASCADE_STAGE(1 - (buf_), pos, f_next)                                                           \
             KASCADE_BLOCK_RAW((kb_) + 2, pos)                                                                \
         }                                                                                                    \
-        const unsigned char* tK_ = smK + (buf_) * TILE;                                                      \
-        f32x16_t s0, s1;                                                                                     \
-        KASCADE_SCORES(tK_, buf_, kb_)                                                                       \
         /* Online softmax, base 2; this lane owns query row q (the other half-wave holds the other keys   */ \
         /* of the same row).  The exponentials are taken against a reference that may lag the true running */ \
         /* maximum: any reference gives the same quotient acc / l as long as nothing overflows, so the     */ \
