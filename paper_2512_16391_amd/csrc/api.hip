@@ -478,8 +478,11 @@ static int prefill_anchor_impl(const kascade_desc* desc, const void* q, const vo
     // pass 1: causal scores -> row statistics (layer 0: plus the dense output)
     st = timed(dense ? K_PF_SWEEP1_V : K_PF_SWEEP1, stream, [&] { return launch_prefill_attend(s, a, false, dense, stream); });
     if (st != KASCADE_OK) return st;
-    // pass 2: recompute scores over the prefix, normalise, pool the tile's rows
+    // pass 2: recompute scores over the prefix, normalise, pool the tile's rows; per-head sets are
+    // selected by the same workgroups (pass 3), shared sets need the mean over the heads first
+    a.topk_out = shared ? nullptr : idx_out;
     st = timed(K_PF_SWEEP2, stream, [&] { return launch_prefill_pool(s, a, stream); });
+    a.topk_out = nullptr;
     if (st != KASCADE_OK) return st;
     // shared variant: one distribution per tile = mean over the key heads (written over head 0's row)
     if (shared) {
@@ -494,7 +497,7 @@ static int prefill_anchor_impl(const kascade_desc* desc, const void* q, const vo
     TopkArgs t = {};
     t.scores = ws.pooled; t.idx_out = idx_out; t.k_per_tile = k_per_tile; t.idx_offsets = idx_offsets;
     t.idx_total = idx_total; t.pooled_pitch = ws.pooled_pitch; t.tile_tokens = q_tile_tokens; t.n_tiles = a.n_tiles;
-    st = timed(K_PF_TOPK, stream, [&] { return launch_topk_prefill(ts, t, stream); });
+    if (shared) st = timed(K_PF_TOPK, stream, [&] { return launch_topk_prefill(ts, t, stream); });
     if (st != KASCADE_OK || dense) return st;
     // pass 4: sparse attention over the fresh sets
     a.stats = nullptr; a.idx = idx_out; a.head_map = shared ? ws.zero_map : nullptr; a.n_src_heads = shared ? 1 : s.Hkv;

@@ -150,6 +150,7 @@ struct PrefillArgs {
     int64_t idx_total;
     int32_t n_src_heads;
     int32_t seqlen, tile_tokens, n_tiles;
+    int32_t* topk_out;            // pool kernel: [Hkv, idx_total] receives the per-(tile, head) Top-k sets; null = pooled scores only
 };
 // sparse = false: all keys up to the diagonal (causal); with_v = false computes statistics only
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st);

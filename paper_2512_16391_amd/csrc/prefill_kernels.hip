@@ -23,6 +23,7 @@
 
 #include "device_utils.h"
 #include "kernels.h"
+#include "topk_select.h"
 
 namespace kascade {
 
@@ -470,11 +471,16 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
 // taken after the next barrier (two partial buffers), so it needs no barrier of its own.
 template <int D>
 __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillArgs a) {
-    constexpr int KSTEPS = D / 16;
-    __shared__ __align__(16) unsigned char smK0[BK * D * 2];
-    __shared__ __align__(16) unsigned char smK1[BK * D * 2];
-    __shared__ float smPart0[kPW][BK];
-    __shared__ float smPart1[kPW][BK];
+    constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
+    constexpr int PART = kPW * BK * (int)sizeof(float);
+    // two K tiles and two buffers of column partials during the sweep; afterwards the same memory
+    // holds the selection's histogram and candidate list
+    constexpr int kSmem = (2 * TILE + 2 * PART) > (int)sizeof(SelectShared<kPB>) ? (2 * TILE + 2 * PART) : (int)sizeof(SelectShared<kPB>);
+    __shared__ __align__(16) unsigned char smem[kSmem];
+    unsigned char* const smK0 = smem;
+    unsigned char* const smK1 = smem + TILE;
+    float (*const smPart0)[BK] = reinterpret_cast<float (*)[BK]>(smem + 2 * TILE);
+    float (*const smPart1)[BK] = reinterpret_cast<float (*)[BK]>(smem + 2 * TILE + PART);
 
     const int hk = blockIdx.x % s.Hkv;
     const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
@@ -548,6 +554,21 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
         float (*last)[BK] = (kb & 1) ? smPart0 : smPart1;
         const int j = (kb - 1) * BK + threadIdx.x;
         if (j < prefix) dst[j] = (last[0][threadIdx.x] + last[1][threadIdx.x]) + (last[2][threadIdx.x] + last[3][threadIdx.x]);
+    }
+    // anchor pass 3 for this (tile, key head): the pooled scores of the tile were all written by this
+    // workgroup, so it selects right away - while it does, the other workgroups of the compute unit keep
+    // the matrix pipes busy, and no separate selection launch (one workgroup per compute unit, latency
+    // bound) is needed
+    if (a.topk_out) {
+        __syncthreads();   // the pooled scores are visible to the whole workgroup; LDS is free
+        int k = a.k_per_tile[t];
+        k = k < 0 ? 0 : (k > prefix ? prefix : k);
+        Segment sg;
+        sg.scores = dst;
+        sg.out = a.topk_out + hk * a.idx_total + a.idx_offsets[t];
+        sg.hist11 = nullptr;
+        sg.n = prefix; sg.k_sel = k; sg.forced = 0; sg.pad_to = k;
+        select_segment<kPB>(sg, *reinterpret_cast<SelectShared<kPB>*>(smem));
     }
 }
 
