@@ -66,6 +66,7 @@ Shape make_shape(const kascade_desc* d) {
 // rows per workgroup for `n_rows` rows in each of `pairs` (sequence, key head) problems
 DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk, int max_chunks, const char* env_name) {
     DecodePlan p;
+    if (max_chunks > kMaxChunks) max_chunks = kMaxChunks;
     int64_t want = (target_blocks + pairs - 1) / pairs;
     if (want < 1) want = 1;
     int64_t chunk = round_up_i((n_rows + want - 1) / want, 256);

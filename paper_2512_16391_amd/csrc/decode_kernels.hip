@@ -514,28 +514,57 @@ __global__ __launch_bounds__(kBlock, (PIPE ? 2 : 4)) void decode_rows_bf16_kerne
 
 // grid (Hq, B), one wave per (sequence, query head):
 //   out[b,h,:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c,   M = max_c m_c.
-// Lanes first share the chunk statistics (one chunk per lane, all loads in flight at once),
-// then each lane owns D/64 output columns and walks the chunks with independent loads.
+// The wave is latency-bound, so everything is requested in one round: the statistics (chunk c in
+// lane c mod 64, at most kMaxChunks/64 per lane) together with the accumulators of the first
+// kMergeAhead chunks (each lane owns D/64 output columns).  Chunks are added in ascending order.
+constexpr int kMergeAhead = 16;
 template <typename T, int D>
 __global__ __launch_bounds__(kWave) void decode_merge_kernel(Shape s, int n_chunks, const float* __restrict__ part_ml,
                                                              const float* __restrict__ part_acc, void* out) {
-    constexpr int CPL = D / kWave;   // columns per lane (1 or 2)
+    constexpr int CPL = D / kWave;                 // columns per lane (1 or 2)
+    constexpr int SPL = kMaxChunks / kWave;        // statistics per lane
     const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
     const int64_t base = ((int64_t)(b * s.Hq + h)) * n_chunks;
-    float M = -INFINITY;
-    for (int c = lane; c < n_chunks; c += kWave) M = fmaxf(M, part_ml[(base + c) * 2]);
+    float x0[kMergeAhead][CPL];
+#pragma unroll
+    for (int u = 0; u < kMergeAhead; ++u) {
+        const int c = u < n_chunks ? u : n_chunks - 1;
+#pragma unroll
+        for (int e = 0; e < CPL; ++e) x0[u][e] = part_acc[(base + c) * D + e * kWave + lane];
+    }
+    float mloc[SPL], lloc[SPL];
+#pragma unroll
+    for (int i = 0; i < SPL; ++i) {
+        const int c = lane + i * kWave;
+        mloc[i] = -INFINITY; lloc[i] = 0.f;
+        if (c < n_chunks) {
+            mloc[i] = part_ml[(base + c) * 2];
+            lloc[i] = part_ml[(base + c) * 2 + 1];
+        }
+    }
+    float M = mloc[0];
+#pragma unroll
+    for (int i = 1; i < SPL; ++i) M = fmaxf(M, mloc[i]);
     M = wave_max(M);
     float lsum = 0.f;
     float val[CPL];
 #pragma unroll
     for (int e = 0; e < CPL; ++e) val[e] = 0.f;
     if (M != -INFINITY) {
-        for (int c = lane; c < n_chunks; c += kWave) {
-            const float mc = part_ml[(base + c) * 2];
-            if (mc != -INFINITY) lsum = fmaf(__builtin_amdgcn_exp2f(mc - M), part_ml[(base + c) * 2 + 1], lsum);
-        }
+#pragma unroll
+        for (int i = 0; i < SPL; ++i)
+            if (mloc[i] != -INFINITY) lsum = fmaf(__builtin_amdgcn_exp2f(mloc[i] - M), lloc[i], lsum);
         lsum = wave_sum(lsum);
-        for (int c0 = 0; c0 < n_chunks; c0 += 8) {
+#pragma unroll
+        for (int u = 0; u < kMergeAhead; ++u) {
+            const float mc = __shfl(mloc[0], u);   // kMergeAhead <= 64: the chunk's statistics sit in lane u
+            if (u < n_chunks && mc != -INFINITY) {
+                const float wgt = __builtin_amdgcn_exp2f(mc - M);
+#pragma unroll
+                for (int e = 0; e < CPL; ++e) val[e] = fmaf(wgt, x0[u][e], val[e]);
+            }
+        }
+        for (int c0 = kMergeAhead; c0 < n_chunks; c0 += 8) {
             float mc[8], x[8][CPL];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {

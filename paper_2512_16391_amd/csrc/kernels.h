@@ -24,6 +24,8 @@ struct DecodePlan {
     int n_chunks;
 };
 
+constexpr int kMaxChunks = 256;   // chunks per (sequence, head) a plan may ask for; the merge keeps their statistics in registers
+
 struct DecodeRowsArgs {
     const void* q;
     const void* k;

@@ -137,6 +137,24 @@ def test_decode_reuse_many_chunks_and_empty_sequence():
     assert torch.equal(out, out2)
 
 
+def test_decode_reuse_many_chunks_fp32_and_wide_groups():
+    for dtype, d, Hq, Hkv in [(torch.float32, 64, 8, 1), (torch.float32, 128, 4, 2), (torch.bfloat16, 64, 16, 2)]:
+        lens, ks = [6000, 2500], [5000, 700]
+        q, k, v = random_case(90, 2, Hq, Hkv, d, dtype, lens)
+        rs = np.random.default_rng(91)
+        idx = torch.full((2, Hkv, 5000), -1, dtype=torch.int32)
+        sets = []
+        for b in range(2):
+            sets.append([np.sort(rs.choice(lens[b], ks[b], replace=False)) for _ in range(Hkv)])
+            for h in range(Hkv):
+                idx[b, h, : ks[b]] = torch.from_numpy(sets[b][h]).int()
+        print(f"case many chunks dtype={dtype} d={d} Hq={Hq} Hkv={Hkv}", flush=True)
+        for _ in range(2):
+            out = binding.kascade_decode_reuse(q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), 5000, idx.to(DEV))
+            torch.cuda.synchronize()
+            assert max_abs(f64(out), oracle_reuse(q, k, v, lens, sets)) <= TOL_OUT[dtype]
+
+
 # --------------------------------------------------------------------------- anchor
 
 def run_anchor_case(q, k, v, lens, ks, W, out_mode, dtype, max_seqlen=None, where=""):
