@@ -171,14 +171,11 @@ __device__ __forceinline__ void select_segment(const Segment& sg, SelectShared<N
     const uint32_t* bits = reinterpret_cast<const uint32_t*>(sg.scores);
     const int n = sg.n;
     const bool aligned = (reinterpret_cast<uintptr_t>(bits) & 15u) == 0;
-    const uint64_t lt = (1ull << lane) - 1ull;
 
     if (sg.k_sel > 0) {
         uint32_t rem = (uint32_t)sg.k_sel;
         // ---- round 1: bits 30..20 (bit 31 is the sign, always 0) ---------------------
-        if (sg.hist11) {
-            for (int i = tid; i < 2048; i += NT) sm.hist[i] = sg.hist11[i];
-        } else {
+        if (!sg.hist11) {
             for (int i = tid; i < 2048; i += NT) sm.hist[i] = 0;
             __syncthreads();
             for (int base = 0; base < n; base += NT * kEPT) {
@@ -192,7 +189,7 @@ __device__ __forceinline__ void select_segment(const Segment& sg, SelectShared<N
         if (tid == 0) sm.cand_n = 0;
         __syncthreads();
         uint32_t d1, cnt1;
-        find_digit<NT, 2048>(sm.hist, sm.wave_tot, &sm.sh_digit, &sm.sh_rem, &sm.sh_cnt, rem, d1, cnt1);
+        find_digit<NT, 2048>(sg.hist11 ? sg.hist11 : sm.hist, sm.wave_tot, &sm.sh_digit, &sm.sh_rem, &sm.sh_cnt, rem, d1, cnt1);
         __syncthreads();
         uint32_t thr;
         if (cnt1 <= (uint32_t)kCandCap) {
@@ -201,17 +198,24 @@ __device__ __forceinline__ void select_segment(const Segment& sg, SelectShared<N
                 const int i0 = base + tid * kEPT;
                 uint32_t u[kEPT];
                 load16(bits, n, i0, aligned, u);
+                uint32_t cm = 0;
+#pragma unroll
+                for (int e = 0; e < kEPT; ++e) cm |= (uint32_t)(i0 + e < n && ((u[e] >> 20) & 2047u) == d1) << e;
+                // one reservation per wave and step: prefix of the lanes' counts, the last lane claims the range
+                uint32_t inc = (uint32_t)__popc(cm);
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t y = __shfl_up(inc, o);
+                    if (lane >= o) inc += y;
+                }
+                uint32_t at = 0;
+                if (lane == 63 && inc) at = atomicAdd(&sm.cand_n, inc);
+                uint32_t slot = __shfl(at, 63) + inc - (uint32_t)__popc(cm);
 #pragma unroll
                 for (int e = 0; e < kEPT; ++e) {
-                    const bool is_c = i0 + e < n && ((u[e] >> 20) & 2047u) == d1;
-                    const uint64_t mk = __ballot(is_c);
-                    if (mk) {
-                        const int first = __ffsll((unsigned long long)mk) - 1;
-                        uint32_t at = 0;
-                        if (lane == first) at = atomicAdd(&sm.cand_n, (uint32_t)__popcll(mk));
-                        at = __shfl(at, first);
-                        const uint32_t slot = at + (uint32_t)__popcll(mk & lt);
-                        if (is_c && slot < (uint32_t)kCandCap) sm.cand[slot] = u[e] & 0xfffffu;
+                    if ((cm >> e) & 1u) {
+                        if (slot < (uint32_t)kCandCap) sm.cand[slot] = u[e] & 0xfffffu;
+                        ++slot;
                     }
                 }
             }
