@@ -29,7 +29,11 @@ Readings of the paper taken where it is silent or unclear:
   * prefill: the candidates of tile t are the keys strictly before the tile
     (Sec. 4.1: each tile attends to a fraction of the previous tokens), the
     tile's own diagonal block is always attended, causally, on top of k_t;
-    row normalisers used for pooling include the diagonal keys.
+    row normalisers used for pooling include the diagonal keys;
+  * Pre-Softmax pooling (Sec. 3.4, evaluated and rejected by the paper): the
+    pooled query is stored in the tensors' own type, and its distribution is
+    normalised over the tile's candidates (the keys before the tile) - the
+    ranking, which is all the method uses, does not depend on that choice.
 
 parity unpinned: none of the functions below - each has a pin in
 tests/test_oracle_pins.py that does not come from this file.  What stays
@@ -390,3 +394,76 @@ def prefill_shared_indices_tile(Q, Kp, t, T, scale, k_t):
     P = prefill_tile_probabilities(Q, Kp, t, T, scale)
     a = P[:, :, : t * T].mean(axis=(0, 1))
     return select_topk(a, k_t, 0), a
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.4, the alternative the paper evaluates and rejects: Pre-Softmax pooling
+# (average the tile's query vectors, run attention once with the pooled query)
+# ----------------------------------------------------------------------------
+
+def round_to_bf16(x):
+    """Nearest bfloat16 (ties to even) of float32 values, returned as float32.
+    bfloat16 is the upper half of the float32 pattern: add half of the dropped
+    part, plus the kept part's last bit on an exact tie, then cut."""
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    keep_lsb = (bits >> np.uint64(16)) & np.uint64(1)
+    rounded = (bits + np.uint64(0x7FFF) + keep_lsb) & np.uint64(0xFFFF0000)
+    return rounded.astype(np.uint32).view(np.float32)
+
+
+def pool_query_vectors(rows, storage):
+    """Pooled query of Pre-Softmax pooling (Sec. 3.4): the average of the given
+    query vectors [n, d].  The average is itself a query the attention kernels
+    consume, so it exists in the tensors' storage type: accumulated in float32
+    in the order given, divided by n in float32, then rounded to `storage`
+    ("fp32": as is, "bf16": nearest even).  The rounding decides index sets, so
+    it is taken here exactly as on the device.  Returns float64 [d]."""
+    rows = np.asarray(rows, dtype=np.float32)
+    acc = np.zeros(rows.shape[1], dtype=np.float32)
+    for r in rows:
+        acc = acc + r
+    mean = acc / np.float32(rows.shape[0])
+    if storage == "bf16":
+        mean = round_to_bf16(mean)
+    elif storage != "fp32":
+        raise ValueError("storage is 'fp32' or 'bf16'")
+    return mean.astype(np.float64)
+
+
+def decode_presoftmax_indices(q, K, scale, k, storage, recent_window=0):
+    """Anchor passes 1-3 with Pre-Softmax pooling, decode: per key head the G
+    query heads of its group are averaged into one query, Eq. 1 is evaluated
+    once with it, Top-k of that distribution.
+    Returns (idx [Hkv, k] ascending, a [Hkv, L])."""
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    Hq, d = q.shape
+    Hkv, L, _ = K.shape
+    G = Hq // Hkv
+    a = np.empty((Hkv, L), dtype=np.float64)
+    for hk in range(Hkv):
+        qbar = pool_query_vectors(q[hk * G:(hk + 1) * G], storage)
+        a[hk] = softmax_lastdim(scale * (K[hk] @ qbar))
+    idx = np.stack([select_topk(a[hk], k, recent_window) for hk in range(Hkv)])
+    return idx, a
+
+
+def prefill_presoftmax_indices_tile(Q, Kp, t, T, scale, k_t, storage):
+    """The same for prefill tile t: the tile's (token, head-in-group) query
+    vectors - tokens ascending, heads ascending inside a token - are averaged
+    per key head, Eq. 1 is evaluated once with the pooled query over the keys
+    strictly before the tile (the tile's Top-k candidates), Top-k_t of that.
+    Returns (idx [Hkv, k_t] ascending, a [Hkv, t*T])."""
+    Q = np.asarray(Q, dtype=np.float64)
+    Kp = np.asarray(Kp, dtype=np.float64)
+    S, Hq, d = Q.shape
+    Hkv = Kp.shape[0]
+    G = Hq // Hkv
+    lo, hi = tile_bounds(t, T, S)
+    a = np.empty((Hkv, lo), dtype=np.float64)
+    for hk in range(Hkv):
+        rows = Q[lo:hi, hk * G:(hk + 1) * G, :].reshape(-1, d)
+        qbar = pool_query_vectors(rows, storage)
+        a[hk] = softmax_lastdim(scale * (Kp[hk, :lo] @ qbar)) if lo > 0 else np.zeros(0)
+    idx = np.stack([select_topk(a[hk], k_t, 0) for hk in range(Hkv)])
+    return idx, a

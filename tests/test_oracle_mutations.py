@@ -148,6 +148,47 @@ def shared_indices_first_head_only(q, K, scale, k, recent_window=0):
 ORIGINAL = {name: getattr(ko, name) for name in dir(ko) if callable(getattr(ko, name))}
 
 P = pytest.param
+
+
+def bf16_truncates(x):
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32)
+    return (bits & np.uint32(0xFFFF0000)).view(np.float32)
+
+
+def bf16_ties_away(x):
+    bits = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((bits + np.uint64(0x8000)) & np.uint64(0xFFFF0000)).astype(np.uint32).view(np.float32)
+
+
+def pooled_query_is_the_sum(rows, storage):
+    rows = np.asarray(rows, dtype=np.float32)
+    acc = rows.sum(axis=0, dtype=np.float32)
+    return (ko.round_to_bf16(acc) if storage == "bf16" else acc).astype(np.float64)
+
+
+def pooled_query_first_row(rows, storage):
+    row = np.asarray(rows, dtype=np.float32)[0]
+    return (ko.round_to_bf16(row) if storage == "bf16" else row).astype(np.float64)
+
+
+def presoftmax_wrong_groups(q, K, scale, k, storage, recent_window=0):
+    q, K = np.asarray(q, dtype=np.float64), np.asarray(K, dtype=np.float64)
+    Hkv = K.shape[0]
+    a = np.stack([ko.softmax_lastdim(scale * (K[hk] @ ko.pool_query_vectors(q[hk::Hkv], storage))) for hk in range(Hkv)])
+    return np.stack([ko.select_topk(a[hk], k, recent_window) for hk in range(Hkv)]), a
+
+
+def presoftmax_tile_includes_diagonal(Q, Kp, t, T, scale, k_t, storage):
+    Q, Kp = np.asarray(Q, dtype=np.float64), np.asarray(Kp, dtype=np.float64)
+    S, Hq, d = Q.shape
+    Hkv = Kp.shape[0]
+    G = Hq // Hkv
+    lo, hi = ko.tile_bounds(t, T, S)
+    a = np.stack([ko.softmax_lastdim(scale * (Kp[hk, :hi] @ ko.pool_query_vectors(Q[lo:hi, hk * G:(hk + 1) * G].reshape(-1, d), storage)))[:lo]
+                  for hk in range(Hkv)])
+    return np.stack([ko.select_topk(a[hk], k_t, 0) for hk in range(Hkv)]), a
+
+
 MUTATIONS = [
     P("decode_logits", wrong_group_logits, id="heads grouped h mod Hkv"),
     P("decode_logits", unscaled_logits, id="softmax scale dropped"),
@@ -167,6 +208,12 @@ MUTATIONS = [
     P("weight_similarity", weight_by_anchor_layer, id="importance of the anchor instead of the served layer"),
     P("head_map_from_similarity", head_map_argmin, id="least similar head"),
     P("decode_shared_indices", shared_indices_first_head_only, id="shared set from one head"),
+    P("round_to_bf16", bf16_truncates, id="bf16 by truncation"),
+    P("round_to_bf16", bf16_ties_away, id="bf16 ties away from zero"),
+    P("pool_query_vectors", pooled_query_is_the_sum, id="pooled query not divided"),
+    P("pool_query_vectors", pooled_query_first_row, id="pooled query from one row"),
+    P("decode_presoftmax_indices", presoftmax_wrong_groups, id="pre-softmax pooling over the wrong heads"),
+    P("prefill_presoftmax_indices_tile", presoftmax_tile_includes_diagonal, id="pre-softmax candidates include the tile"),
 ]
 
 

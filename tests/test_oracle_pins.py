@@ -489,3 +489,103 @@ def test_shared_prefill_indices_match_decode_for_single_token_tiles():
     np.testing.assert_array_equal(idx, ko.select_topk(p[:t], k_t))
     per_head = ko.prefill_pooled_tile(Q, Kp, t, 1, 0.5)
     np.testing.assert_allclose(a, per_head.mean(axis=0), atol=1e-15)
+
+
+# ------------------------------------------------------------------ Sec. 3.4: Pre-Softmax pooling
+
+def test_round_to_bf16_matches_library_conversion():
+    r = rng(70)
+    x = np.concatenate([r.standard_normal(20000).astype(np.float32) * np.float32(10.0) ** r.integers(-20, 20, 20000).astype(np.float32),
+                        np.array([0.0, -0.0, 1.0, -1.0, 3.0e38, 1e-40, 65504.0], dtype=np.float32)])
+    # exact ties between two neighbours, with an even and with an odd kept part
+    ties = (np.array([0x3F808000, 0x3F818000, 0xBF808000, 0x40FF8000, 0x00018000], dtype=np.uint32)).view(np.float32)
+    x = np.concatenate([x, ties])
+    lib = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(ko.round_to_bf16(x).view(np.uint32), lib.view(np.uint32))
+    np.testing.assert_array_equal(ko.round_to_bf16(ties).view(np.uint32),
+                                  np.array([0x3F800000, 0x3F820000, 0xBF800000, 0x41000000, 0x00020000], dtype=np.uint32))
+
+
+def test_pooled_query_is_the_rounded_mean():
+    r = rng(71)
+    rows = r.standard_normal((12, 16)).astype(np.float32).astype(np.float64)
+    exact = rows.mean(axis=0)
+    np.testing.assert_allclose(ko.pool_query_vectors(rows, "fp32"), exact, rtol=0, atol=3e-7)
+    pb = ko.pool_query_vectors(rows, "bf16")
+    assert np.all(np.abs(pb - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-6)          # half a bf16 step, and a bit
+    assert np.all(pb.astype(np.float32).view(np.uint32) & 0xFFFF == 0)             # representable in bf16
+    # one vector, or equal vectors: the pooled query is that vector (already representable)
+    v = torch.randn(16, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(ko.pool_query_vectors(np.tile(v, (4, 1)), "bf16"), v)
+    np.testing.assert_array_equal(ko.pool_query_vectors(v[None], "fp32"), v)
+
+
+def test_presoftmax_decode_is_softmax_of_the_mean_logits():
+    r = rng(72)
+    Hq, Hkv, d, L, k = 8, 2, 16, 70, 9
+    q = r.standard_normal((Hq, d)).astype(np.float32).astype(np.float64)
+    K = r.standard_normal((Hkv, L, d))
+    idx, a = ko.decode_presoftmax_indices(q, K, 0.3, k, "fp32")
+    # the dot product is linear: the pooled query's logits are the mean of the group's logits (library softmax)
+    s = ko.decode_logits(q, K, 0.3).reshape(Hkv, Hq // Hkv, L).mean(axis=1)
+    lib = torch.softmax(torch.from_numpy(s), dim=-1).numpy()
+    np.testing.assert_allclose(a, lib, atol=1e-6)
+    np.testing.assert_allclose(a.sum(axis=1), 1.0, atol=1e-12)
+    # softmax is monotone: the set is the Top-k of the mean logits themselves
+    for hk in range(Hkv):
+        brute = sorted(sorted(range(L), key=lambda j: (-s[hk, j], j))[:k])
+        assert idx[hk].tolist() == brute
+    # it is NOT the post-softmax pooling (mean of softmaxes) unless the group has one head
+    _, post = ko.decode_anchor_indices(q, K, 0.3, k)
+    assert np.max(np.abs(post - a)) > 1e-3
+    idx1, a1 = ko.decode_presoftmax_indices(q[:2], K, 0.3, k, "fp32")           # G = 1
+    idx1p, a1p = ko.decode_anchor_indices(q[:2], K, 0.3, k)
+    np.testing.assert_allclose(a1, a1p, atol=1e-15)
+    np.testing.assert_array_equal(idx1, idx1p)
+    # recent window handled by the same selection rule
+    idxw, _ = ko.decode_presoftmax_indices(q, K, 0.3, k, "fp32", recent_window=4)
+    assert all(set(range(L - 4, L)) <= set(row.tolist()) for row in idxw)
+
+
+def test_presoftmax_decode_equal_queries_reduce_to_post_softmax_pooling():
+    r = rng(73)
+    Hkv, G, d, L, k = 2, 4, 16, 50, 7
+    base = torch.randn(Hkv, d, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16).to(torch.float64).numpy()
+    q = np.repeat(base, G, axis=0)                       # every head of a group asks the same query
+    K = r.standard_normal((Hkv, L, d))
+    idx, a = ko.decode_presoftmax_indices(q, K, 0.25, k, "bf16")
+    idxp, ap = ko.decode_anchor_indices(q, K, 0.25, k)
+    np.testing.assert_allclose(a, ap, atol=1e-15)
+    np.testing.assert_array_equal(idx, idxp)
+
+
+def test_presoftmax_prefill_tile_special_cases():
+    r = rng(74)
+    S, Hq, Hkv, d, T = 24, 4, 2, 8, 4
+    Q = r.standard_normal((S, Hq, d)).astype(np.float32).astype(np.float64)
+    Kp = r.standard_normal((Hkv, S, d))
+    G = Hq // Hkv
+    t, k_t = 4, 5
+    idx, a = ko.prefill_presoftmax_indices_tile(Q, Kp, t, T, 0.4, k_t, "fp32")
+    assert a.shape == (Hkv, t * T) and idx.shape == (Hkv, k_t)
+    np.testing.assert_allclose(a.sum(axis=1), 1.0, atol=1e-12)
+    for hk in range(Hkv):
+        # mean over the tile's T*G rows of their logits on the prefix keys, then a library softmax
+        s = np.mean([0.4 * (Kp[hk, : t * T] @ Q[i, hk * G + g]) for i in range(t * T, (t + 1) * T) for g in range(G)], axis=0)
+        np.testing.assert_allclose(a[hk], torch.softmax(torch.from_numpy(s), dim=-1).numpy(), atol=1e-6)
+        assert idx[hk].tolist() == sorted(sorted(range(t * T), key=lambda j: (-s[j], j))[:k_t])
+    # tiles of one token and one head per group: the tile's distribution is that token's causal row,
+    # renormalised over the keys before it; the sets agree with post-softmax pooling
+    Q1, K1 = Q[:, ::G], Kp
+    idx1, a1 = ko.prefill_presoftmax_indices_tile(Q1, K1, 9, 1, 0.4, 3, "fp32")
+    idx1p, a1p = ko.prefill_anchor_indices_tile(Q1, K1, 9, 1, 0.4, 3)
+    np.testing.assert_allclose(a1, a1p / a1p.sum(axis=1, keepdims=True), atol=1e-12)
+    np.testing.assert_array_equal(idx1, idx1p)
+    # a ragged last tile averages only the rows that exist
+    Qr, Kr = Q[:22], Kp[:, :22]
+    _, ar = ko.prefill_presoftmax_indices_tile(Qr, Kr, 5, T, 0.4, 2, "fp32")
+    s = np.mean([0.4 * (Kr[0, :20] @ Qr[i, g]) for i in (20, 21) for g in range(G)], axis=0)
+    np.testing.assert_allclose(ar[0], torch.softmax(torch.from_numpy(s), dim=-1).numpy(), atol=1e-6)
+    # tile 0 has no candidates
+    idx0, a0 = ko.prefill_presoftmax_indices_tile(Q, Kp, 0, T, 0.4, 0, "fp32")
+    assert a0.shape == (Hkv, 0) and idx0.shape == (Hkv, 0)
