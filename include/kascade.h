@@ -56,7 +56,8 @@ enum {
     KASCADE_OP_DECODE_REUSE = 1,
     KASCADE_OP_PREFILL_ANCHOR = 2,
     KASCADE_OP_PREFILL_REUSE = 3,
-    KASCADE_OP_DECODE_POOLED = 4
+    KASCADE_OP_DECODE_POOLED = 4,
+    KASCADE_OP_PREFILL_ANCHOR_PRESOFTMAX = 5
 };
 
 typedef struct {
@@ -158,6 +159,34 @@ int kascade_prefill_anchor_shared(const kascade_desc* desc, const void* q, const
                                   const int64_t* idx_offsets, int64_t idx_total, int32_t out_mode,
                                   int32_t* idx_out, void* out, void* workspace, size_t workspace_bytes,
                                   void* hip_stream);
+
+/*
+ * Pre-Softmax pooling (Sec. 3.4, the alternative the paper evaluates and rejects; here for the same
+ * comparison): instead of pooling post-softmax distributions, the query vectors of a pooling unit -
+ * decode: the G heads of a key head; prefill: the T tokens x G heads of a tile - are averaged into one
+ * query, attention scores (Eq. 1) are computed once with it, and the Top-k of that distribution is
+ * the unit's index set.  The pooled query is kept in the tensors' own type: summed in fp32 (tokens
+ * ascending, heads ascending inside a token), divided by the count, rounded once (bf16: to nearest
+ * even).  Same arguments, checks, outputs and out_mode meaning as kascade_decode_anchor /
+ * kascade_prefill_anchor; the sets feed the ordinary reuse calls.
+ *   decode   workspace: kascade_workspace_bytes(KASCADE_OP_DECODE_ANCHOR, ...), as for the anchor call.
+ *   prefill  candidates of tile t are the t*T keys before it, as in kascade_prefill_anchor.  Runs on
+ *            the decode kernels with tiles as sequences over one shared cache and is not tuned; it
+ *            keeps fp32 logits and pooled scores of every (tile, key head) over max prefix length:
+ *            kascade_workspace_bytes(KASCADE_OP_PREFILL_ANCHOR_PRESOFTMAX, desc, seqlen, idx_total, T),
+ *            about 8 * n_tiles * Hkv * seqlen bytes (2.1 GB at 32768 tokens, T = 32, 8 key heads).
+ *            At most 65535 tiles, else KASCADE_UNSUPPORTED.
+ */
+int kascade_decode_anchor_presoftmax(const kascade_desc* desc, const void* q, const void* k_cache,
+                                     const void* v_cache, const int32_t* seqlens, const int32_t* k_per_seq,
+                                     int32_t max_seqlen, int32_t k_max, int32_t recent_window,
+                                     int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream);
+int kascade_prefill_anchor_presoftmax(const kascade_desc* desc, const void* q, const void* k, const void* v,
+                                      int32_t seqlen, int32_t q_tile_tokens, const int32_t* k_per_tile,
+                                      const int64_t* idx_offsets, int64_t idx_total, int32_t out_mode,
+                                      int32_t* idx_out, void* out, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream);
 
 /*
  * Calibration path (Sec. 3.3): which layers become anchors is decided once per model from how

@@ -20,10 +20,12 @@ KASCADE_OK = 0
 KASCADE_F32, KASCADE_BF16 = 0, 1
 KASCADE_OUT_DENSE, KASCADE_OUT_SPARSE = 0, 1
 OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE, OP_DECODE_POOLED = 0, 1, 2, 3, 4
+OP_PREFILL_ANCHOR_PRESOFTMAX = 5
 
 EXPORTS = [
     "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
     "kascade_decode_anchor_shared", "kascade_prefill_anchor_shared",
+    "kascade_decode_anchor_presoftmax", "kascade_prefill_anchor_presoftmax",
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
     "kascade_decode_pooled", "kascade_topk_similarity", "kascade_select_anchor_layers",
     "kascade_head_similarity", "kascade_head_map", "kascade_layer_importance",
@@ -64,12 +66,16 @@ def load_library(path: Optional[str] = None):
     lib.kascade_decode_anchor.restype = ctypes.c_int
     lib.kascade_decode_anchor_shared.argtypes = lib.kascade_decode_anchor.argtypes
     lib.kascade_decode_anchor_shared.restype = ctypes.c_int
+    lib.kascade_decode_anchor_presoftmax.argtypes = lib.kascade_decode_anchor.argtypes
+    lib.kascade_decode_anchor_presoftmax.restype = ctypes.c_int
     lib.kascade_decode_reuse.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, sz, vp]
     lib.kascade_decode_reuse.restype = ctypes.c_int
     lib.kascade_prefill_anchor.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, i64, i32, vp, vp, vp, sz, vp]
     lib.kascade_prefill_anchor.restype = ctypes.c_int
     lib.kascade_prefill_anchor_shared.argtypes = lib.kascade_prefill_anchor.argtypes
     lib.kascade_prefill_anchor_shared.restype = ctypes.c_int
+    lib.kascade_prefill_anchor_presoftmax.argtypes = lib.kascade_prefill_anchor.argtypes
+    lib.kascade_prefill_anchor_presoftmax.restype = ctypes.c_int
     lib.kascade_prefill_reuse.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, i64, vp, i32, vp, vp, vp, sz, vp]
     lib.kascade_prefill_reuse.restype = ctypes.c_int
     lib.kascade_decode_pooled.argtypes = [dp, vp, vp, vp, i32, vp, i64, vp, sz, vp]
@@ -437,4 +443,44 @@ def kascade_prefill_anchor_shared(q, k, v, q_tile_tokens, k_per_tile, idx_offset
                                            _ptr(k_per_tile), _ptr(idx_offsets), int(idx_total), int(out_mode),
                                            _ptr(idx_out), _ptr(out), _ptr(workspace), nbytes, _stream())
     _check(st, "kascade_prefill_anchor_shared")
+    return idx_out, out
+
+
+def kascade_decode_anchor_presoftmax(q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window=0,
+                                     out_mode=KASCADE_OUT_SPARSE, idx_out=None, out=None, workspace=None,
+                                     softmax_scale=0.0, kv_layout="BHLD"):
+    """Anchor call with Pre-Softmax pooling.  Returns (idx_out [B,Hkv,k_max] int32, out [B,Hq,d])."""
+    _need_gpu(q, k_cache, v_cache, seqlens, k_per_seq, idx_out, out, workspace)
+    lib = load_library()
+    B = q.shape[0]
+    if out is None:
+        out = torch.empty_like(q)
+    desc = decode_desc(q, k_cache, out, softmax_scale, kv_layout)
+    if idx_out is None:
+        idx_out = torch.empty(B, desc.n_kv_heads, int(k_max), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(OP_DECODE_ANCHOR, desc, max_seqlen, k_max, 0, q.device, workspace)
+    st = lib.kascade_decode_anchor_presoftmax(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seqlens),
+                                              _ptr(k_per_seq), int(max_seqlen), int(k_max), int(recent_window),
+                                              int(out_mode), _ptr(idx_out), _ptr(out), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_decode_anchor_presoftmax")
+    return idx_out, out
+
+
+def kascade_prefill_anchor_presoftmax(q, k, v, q_tile_tokens, k_per_tile, idx_offsets, idx_total,
+                                      out_mode=KASCADE_OUT_SPARSE, idx_out=None, out=None, workspace=None,
+                                      softmax_scale=0.0):
+    """Prefill anchor call with Pre-Softmax pooling.  Returns (idx_out [Hkv, idx_total] int32, out [S,Hq,d])."""
+    _need_gpu(q, k, v, k_per_tile, idx_offsets, idx_out, out, workspace)
+    lib = load_library()
+    S = q.shape[0]
+    if out is None:
+        out = torch.empty_like(q)
+    desc = prefill_desc(q, k, out, softmax_scale)
+    if idx_out is None:
+        idx_out = torch.empty(desc.n_kv_heads, max(int(idx_total), 1), dtype=torch.int32, device=q.device)
+    workspace, nbytes = _workspace(OP_PREFILL_ANCHOR_PRESOFTMAX, desc, S, idx_total, q_tile_tokens, q.device, workspace)
+    st = lib.kascade_prefill_anchor_presoftmax(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), int(S), int(q_tile_tokens),
+                                               _ptr(k_per_tile), _ptr(idx_offsets), int(idx_total), int(out_mode),
+                                               _ptr(idx_out), _ptr(out), _ptr(workspace), nbytes, _stream())
+    _check(st, "kascade_prefill_anchor_presoftmax")
     return idx_out, out

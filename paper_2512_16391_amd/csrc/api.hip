@@ -2,6 +2,7 @@
 // No allocation, no synchronisation, no state kept between calls.
 #include "../../include/kascade.h"
 
+#include <limits.h>
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -14,6 +15,8 @@
 using namespace kascade;
 
 namespace {
+
+enum { kPerHeadSets = 0, kSharedSets = 1, kPreSoftmax = 2 };   // anchor variants behind one implementation
 
 constexpr size_t kAlign = 256;
 constexpr int kTargetBlocks = 1024;   // about four workgroups per compute unit (256 CUs)
@@ -133,6 +136,7 @@ DecodeReuseWs carve_decode_reuse(const Shape& s, const DecodePlan& plan, void* w
 
 struct DecodeAnchorWs {
     float* logits; float* pooled; float* st_ml; float* st_acc; uint32_t* hist11; int32_t* zero_map; int64_t pitch;
+    void* qbar;   // [B, Hkv, D] pooled queries (Pre-Softmax pooling), 4 bytes per element reserved
     uint32_t* topk_cand; uint32_t* topk_seg; uint32_t* topk_part; int topk_parts;
     DecodeReuseWs gather; size_t bytes;
 };
@@ -148,6 +152,7 @@ DecodeAnchorWs carve_decode_anchor(const Shape& s, const DecodePlan& stream, con
     r.st_acc = c.take<float>(rows * s.D);
     r.hist11 = c.take<uint32_t>((size_t)s.B * s.Hkv * 2048);
     r.zero_map = c.take<int32_t>((size_t)s.Hkv);
+    r.qbar = c.take<float>((size_t)s.B * s.Hkv * s.D);
     r.topk_parts = plan_topk_parts(s, max_seqlen);
     r.topk_cand = r.topk_seg = r.topk_part = nullptr;
     if (r.topk_parts > 1) {
@@ -174,6 +179,40 @@ PrefillWs carve_prefill_anchor(const Shape& s, int64_t S, int T, void* ws) {
     return r;
 }
 
+// The shape the decode kernels see when pooled queries stand in for the group's heads: one query head
+// per key head, rows [unit, Hkv, D] packed.
+Shape pooled_query_shape(const Shape& s, int units) {
+    Shape p = s;
+    p.B = units; p.Hq = s.Hkv; p.G = 1;
+    p.q_stride[0] = (int64_t)s.Hkv * s.D; p.q_stride[1] = 0; p.q_stride[2] = s.D;
+    return p;
+}
+
+// Pre-Softmax pooling of prefill tiles runs on the decode kernels: tile t is a "sequence" whose query is
+// the tile's pooled query and whose cache is the first t*T keys of the prompt (batch stride 0).
+struct PrefillPreWs {
+    void* qbar; int32_t* tile_lens; float* logits; float* pooled; float* st_ml; uint32_t* hist11;
+    int64_t pitch; int64_t max_len; Shape ds; DecodePlan sp; size_t bytes;
+};
+PrefillPreWs carve_prefill_presoftmax(const Shape& s, int64_t S, int T, void* ws) {
+    Carver c(ws);
+    PrefillPreWs r;
+    const int64_t n_tiles = (S + T - 1) / T;
+    r.max_len = (n_tiles - 1) * T > 0 ? (n_tiles - 1) * T : 1;
+    r.ds = pooled_query_shape(s, (int)n_tiles);
+    r.ds.kv_stride[0] = 0;
+    r.sp = plan_stream(r.ds, r.max_len);
+    r.pitch = round_up_i(r.max_len, 4);
+    r.qbar = c.take<float>((size_t)n_tiles * s.Hkv * s.D);
+    r.tile_lens = c.take<int32_t>((size_t)n_tiles);
+    r.logits = c.take<float>((size_t)n_tiles * s.Hkv * r.pitch);
+    r.pooled = c.take<float>((size_t)n_tiles * s.Hkv * r.pitch);
+    r.st_ml = c.take<float>((size_t)n_tiles * s.Hkv * r.sp.n_chunks * 2);
+    r.hist11 = c.take<uint32_t>((size_t)n_tiles * s.Hkv * 2048);
+    r.bytes = c.used;
+    return r;
+}
+
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
 // ---- optional per-kernel timing (measurement aid, off by default) -----------------
@@ -181,11 +220,11 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // Events are created on demand and kept until profiling is disabled; with profiling off
 // the library creates nothing.
 enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
-                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_POOL_HEADS, K_COUNT };
+                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_POOL_HEADS, K_POOL_QUERIES, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
     "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel",
-    "similarity", "head_map", "layer_importance", "pool_heads"};
+    "similarity", "head_map", "layer_importance", "pool_heads", "pool_queries"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
@@ -303,6 +342,9 @@ size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max
             return carve_decode_anchor(s, plan_stream(s, max_seqlen), plan_gather(s, k_or_idx_total), max_seqlen, nullptr).bytes;
         case KASCADE_OP_DECODE_POOLED:
             return carve_decode_anchor(s, plan_stream(s, max_seqlen), plan_gather(s, 1), max_seqlen, nullptr).bytes;
+        case KASCADE_OP_PREFILL_ANCHOR_PRESOFTMAX:
+            if (q_tile_tokens <= 0) return 0;
+            return carve_prefill_presoftmax(s, max_seqlen, q_tile_tokens, nullptr).bytes;
         default:
             return 0;
     }
@@ -338,7 +380,8 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
 static int decode_anchor_impl(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                               const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
                               int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
-                              size_t workspace_bytes, void* hip_stream, bool shared) {
+                              size_t workspace_bytes, void* hip_stream, int variant) {
+    const bool shared = variant == kSharedSets, presoftmax = variant == kPreSoftmax;
     int st = check_desc(desc, false);
     if (st != KASCADE_OK) return st;
     if (!q || !k_cache || !v_cache || !seqlens || !k_per_seq || !idx_out || !out) return KASCADE_INVALID_ARG;
@@ -360,9 +403,30 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens;
     a.logits = ws.logits; a.logit_pitch = ws.pitch;
     a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = out; a.hist11 = ws.hist11;
-    st = timed(dense ? K_STREAM_V : K_STREAM, stream, [&] { return launch_decode_rows(s, sp, a, false, dense, true, stream); });
+    // the shape passes 1-2 run on: the layer's own, or (Pre-Softmax pooling) one pooled query per key head
+    Shape sel = s;
+    if (presoftmax) {
+        // the dense output still needs every head's own query against every key: a pass of its own, whose
+        // logits and statistics are overwritten below
+        if (dense) {
+            st = timed(K_STREAM_V, stream, [&] { return launch_decode_rows(s, sp, a, false, true, true, stream); });
+            if (st != KASCADE_OK) return st;
+            if (sp.n_chunks > 1) {
+                st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream); });
+                if (st != KASCADE_OK) return st;
+            }
+        }
+        st = timed(K_POOL_QUERIES, stream, [&] {
+            return launch_pool_queries(s.dtype, q, s.q_stride[0], 0, s.q_stride[2], s.G, 1, 1, s.B, ws.qbar, s.Hkv, s.D, nullptr, stream);
+        });
+        if (st != KASCADE_OK) return st;
+        sel = pooled_query_shape(s, s.B);
+        a.q = ws.qbar;
+    }
+    const bool with_v = dense && !presoftmax;
+    st = timed(with_v ? K_STREAM_V : K_STREAM, stream, [&] { return launch_decode_rows(sel, sp, a, false, with_v, true, stream); });
     if (st != KASCADE_OK) return st;
-    if (dense && sp.n_chunks > 1) {
+    if (with_v && sp.n_chunks > 1) {
         st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream); });
         if (st != KASCADE_OK) return st;
     }
@@ -373,7 +437,7 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     pa.pooled_pitch = ws.pitch; pa.hist11 = ws.hist11; pa.max_seqlen = max_seqlen;
     const bool split = ws.topk_parts > 1 && !shared;
     pa.seg_info = split ? ws.topk_seg : nullptr;
-    st = timed(K_POOL, stream, [&] { return launch_decode_pool(s, sp.n_chunks, pa, stream); });
+    st = timed(K_POOL, stream, [&] { return launch_decode_pool(sel, sp.n_chunks, pa, stream); });
     if (st != KASCADE_OK) return st;
     // shared variant: one distribution per sequence = mean over the key heads (written over head 0's row)
     if (shared) {
@@ -414,7 +478,7 @@ int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k
                           int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
     return decode_anchor_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window, out_mode,
-                              idx_out, out, workspace, workspace_bytes, hip_stream, false);
+                              idx_out, out, workspace, workspace_bytes, hip_stream, kPerHeadSets);
 }
 
 int kascade_decode_anchor_shared(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
@@ -422,7 +486,15 @@ int kascade_decode_anchor_shared(const kascade_desc* desc, const void* q, const 
                                  int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
     return decode_anchor_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window, out_mode,
-                              idx_out, out, workspace, workspace_bytes, hip_stream, true);
+                              idx_out, out, workspace, workspace_bytes, hip_stream, kSharedSets);
+}
+
+int kascade_decode_anchor_presoftmax(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                     const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
+                                     int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return decode_anchor_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, max_seqlen, k_max, recent_window, out_mode,
+                              idx_out, out, workspace, workspace_bytes, hip_stream, kPreSoftmax);
 }
 
 }  // extern "C"
@@ -519,6 +591,56 @@ int kascade_prefill_anchor_shared(const kascade_desc* desc, const void* q, const
                                   size_t workspace_bytes, void* hip_stream) {
     return prefill_anchor_impl(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, out_mode, idx_out,
                                out, workspace, workspace_bytes, hip_stream, true);
+}
+
+int kascade_prefill_anchor_presoftmax(const kascade_desc* desc, const void* q, const void* k, const void* v,
+                                      int32_t seqlen, int32_t q_tile_tokens, const int32_t* k_per_tile,
+                                      const int64_t* idx_offsets, int64_t idx_total, int32_t out_mode, int32_t* idx_out,
+                                      void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int st = check_prefill(desc, q, k, v, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total, idx_out, out);
+    if (st != KASCADE_OK) return st;
+    if (out_mode != KASCADE_OUT_DENSE && out_mode != KASCADE_OUT_SPARSE) return KASCADE_INVALID_ARG;
+    const Shape s = make_shape(desc);
+    const PrefillPreWs ws = carve_prefill_presoftmax(s, seqlen, q_tile_tokens, workspace);
+    if (!workspace || workspace_bytes < ws.bytes) return KASCADE_WORKSPACE_TOO_SMALL;
+    if (!aligned16(workspace)) return KASCADE_MISALIGNED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool dense = out_mode == KASCADE_OUT_DENSE;
+    PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
+    if (a.n_tiles > 65535) return KASCADE_UNSUPPORTED;   // one grid row per tile in the decode kernels
+
+    // layer 0: plain causal attention for the output; it plays no part in the selection
+    if (dense) {
+        st = timed(K_PF_SWEEP1_V, stream, [&] { return launch_prefill_attend(s, a, false, true, stream); });
+        if (st != KASCADE_OK) return st;
+    }
+    // one pooled query per (tile, key head); tile_lens[t] = t*T keys precede tile t
+    st = timed(K_POOL_QUERIES, stream, [&] {
+        return launch_pool_queries(s.dtype, q, 0, s.q_stride[1], s.q_stride[2], s.G, q_tile_tokens, seqlen, a.n_tiles, ws.qbar,
+                                   s.Hkv, s.D, ws.tile_lens, stream);
+    });
+    if (st != KASCADE_OK) return st;
+    // passes 1-3 of the decode anchor with tiles as sequences over one shared cache
+    DecodeRowsArgs r = {};
+    r.q = ws.qbar; r.k = k; r.v = nullptr; r.seqlens = ws.tile_lens;
+    r.logits = ws.logits; r.logit_pitch = ws.pitch; r.part_ml = ws.st_ml; r.part_acc = nullptr; r.hist11 = ws.hist11;
+    st = timed(K_STREAM, stream, [&] { return launch_decode_rows(ws.ds, ws.sp, r, false, false, true, stream); });
+    if (st != KASCADE_OK) return st;
+    DecodePoolArgs pa = {};
+    pa.seqlens = ws.tile_lens; pa.k_per_seq = k_per_tile; pa.k_max = INT_MAX; pa.recent_window = 0;
+    pa.logits = ws.logits; pa.logit_pitch = ws.pitch; pa.part_ml = ws.st_ml; pa.pooled = ws.pooled;
+    pa.pooled_pitch = ws.pitch; pa.hist11 = ws.hist11; pa.max_seqlen = (int)ws.max_len;
+    st = timed(K_POOL, stream, [&] { return launch_decode_pool(ws.ds, ws.sp.n_chunks, pa, stream); });
+    if (st != KASCADE_OK) return st;
+    TopkArgs t = {};
+    t.scores = ws.pooled; t.hist11 = ws.hist11; t.idx_out = idx_out; t.seqlens = ws.tile_lens; t.k_per_seq = k_per_tile;
+    t.pitch = ws.pitch; t.k_max = INT_MAX; t.recent_window = 0;
+    t.out_offsets = idx_offsets; t.out_head_pitch = idx_total;
+    st = timed(K_TOPK, stream, [&] { return launch_topk_decode(ws.ds, t, stream); });
+    if (st != KASCADE_OK || dense) return st;
+    // pass 4: sparse attention over the fresh sets
+    a.idx = idx_out; a.head_map = nullptr; a.n_src_heads = s.Hkv;
+    return timed(K_PF_SPARSE, stream, [&] { return launch_prefill_attend(s, a, true, true, stream); });
 }
 
 int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k, const void* v, int32_t seqlen,

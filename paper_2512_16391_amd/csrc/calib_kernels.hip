@@ -1,6 +1,7 @@
 // Calibration-time kernels: similarity of two layers' Top-k sets (Eq. 3), head map from the
 // head-level similarity (Sec. 3.5), layer importance (Sec. 3.3); and the mean over heads behind the
-// shared (all heads pooled) index sets of Sec. 3.5.
+// shared (all heads pooled) index sets of Sec. 3.5; and the pooled query of Pre-Softmax pooling
+// (the alternative of Sec. 3.4).
 //
 // For one (sequence, key head) segment the similarity of layer a's set applied to layer b is
 // the pooled attention mass of layer b that a's set recovers, over the mass b's own set
@@ -121,7 +122,45 @@ __global__ __launch_bounds__(kSimBlock) void pool_heads_kernel(float* rows, int6
     }
 }
 
+// Pre-Softmax pooling (Sec. 3.4): the query vectors of one pooling unit - decode: the G heads of key
+// head hk for sequence `unit`; prefill: tokens [unit*T, min((unit+1)*T, S)) times those G heads - are
+// averaged into one query of the tensors' own type.  grid (Hkv, units), one thread per dimension; the
+// sum runs in fp32, tokens ascending and heads ascending inside a token, then one division and one
+// rounding, so the result is the same on every run and can be restated exactly on a CPU.
+// tile_lens (prefill): receives unit*T, the number of keys before the tile, for unit < n_units.
+template <typename T>
+__global__ void pool_queries_kernel(const T* q, int64_t unit_stride, int64_t token_stride, int64_t head_stride, int G,
+                                    int tokens_per_unit, int n_tokens, T* qbar, int Hkv, int D, int32_t* tile_lens) {
+    const int hk = blockIdx.x, unit = blockIdx.y, c = threadIdx.x;
+    const bool tiles = tile_lens != nullptr;     // else: one token per unit, units unit_stride apart
+    const int lo = tiles ? unit * tokens_per_unit : 0;
+    int hi = tiles ? lo + tokens_per_unit : 1;
+    if (tiles && hi > n_tokens) hi = n_tokens;
+    if (tiles && hk == 0 && c == 0) tile_lens[unit] = lo;
+    float acc = 0.f;
+    for (int i = lo; i < hi; ++i) {
+        const T* row = q + (tiles ? 0 : unit * unit_stride) + (int64_t)i * token_stride + (int64_t)hk * G * head_stride + c;
+        for (int g = 0; g < G; ++g) acc += widen1(row[g * head_stride]);
+    }
+    const float mean = acc / (float)((hi - lo) * G);
+    T* dst = qbar + ((int64_t)unit * Hkv + hk) * D + c;
+    if constexpr (sizeof(T) == 4) *dst = mean; else *dst = (T)f32_to_bf16_bits(mean);
+}
+
 }  // namespace
+
+hipError_t launch_pool_queries(int dtype, const void* q, int64_t unit_stride, int64_t token_stride, int64_t head_stride,
+                               int G, int tokens_per_unit, int n_tokens, int n_units, void* qbar, int Hkv, int D,
+                               int32_t* tile_lens, hipStream_t st) {
+    const dim3 grid(Hkv, n_units), block(D);
+    if (dtype == 0)
+        hipLaunchKernelGGL(pool_queries_kernel<float>, grid, block, 0, st, (const float*)q, unit_stride, token_stride,
+                           head_stride, G, tokens_per_unit, n_tokens, (float*)qbar, Hkv, D, tile_lens);
+    else
+        hipLaunchKernelGGL(pool_queries_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)q, unit_stride, token_stride,
+                           head_stride, G, tokens_per_unit, n_tokens, (bf16_t*)qbar, Hkv, D, tile_lens);
+    return hipGetLastError();
+}
 
 hipError_t launch_pool_heads(float* rows, int64_t batch_pitch, int64_t head_pitch, int n_heads, int n_batches, int64_t n,
                              const int32_t* lens, int32_t* zero_map, hipStream_t st) {

@@ -87,6 +87,10 @@ struct TopkArgs {
     int64_t pitch;
     int32_t k_max;
     int32_t recent_window;
+    // decode segments written in the prefill layout (Pre-Softmax pooling of prefill tiles, one "sequence"
+    // per tile): out at idx_out + hk*out_head_pitch + out_offsets[b], no padding; null = decode layout
+    const int64_t* out_offsets;
+    int64_t out_head_pitch;
     // decode, split selection (several workgroups per segment): null / 0 when unused
     uint32_t* cand;               // [B, Hkv, kTopkCandCap] threshold-bucket candidates: low 20 score bits | part << 20
     uint32_t* seg_info;           // [B, Hkv, 8]: candidate count, round-1 digit / rest / bucket size, THR, need_eq, fallback flag
@@ -128,6 +132,14 @@ hipError_t launch_head_map(int B, int Hkv, int Ha, const float* sim, float* mean
                            hipStream_t st);
 hipError_t launch_importance(int dtype, const void* x, const void* y, int64_t n_rows, int n_cols, int64_t x_stride,
                              int64_t y_stride, float* w_out, hipStream_t st);
+
+// ---- Pre-Softmax pooling (Sec. 3.4 alternative): pooled queries ----------------------------------
+// unit = sequence (decode: tokens_per_unit = n_tokens = 1, unit_stride = batch stride, tile_lens null)
+// or query tile (prefill: tokens [unit*T, min((unit+1)*T, n_tokens)), tile_lens receives unit*T).
+// qbar [n_units, Hkv, D] in the tensors' type.
+hipError_t launch_pool_queries(int dtype, const void* q, int64_t unit_stride, int64_t token_stride, int64_t head_stride,
+                               int G, int tokens_per_unit, int n_tokens, int n_units, void* qbar, int Hkv, int D,
+                               int32_t* tile_lens, hipStream_t st);
 
 // ---- shared index sets (Sec. 3.5, all heads pooled) --------------------------------------
 // rows[batch][head][j] (head_pitch apart, batch_pitch between batches): row 0 of every batch becomes

@@ -27,6 +27,10 @@ __global__ __launch_bounds__(kTopkBlock) void topk_decode_kernel(Shape s, TopkAr
     sg.k_sel = k - W;
     sg.forced = W;
     sg.pad_to = a.k_max;
+    if (a.out_offsets) {
+        sg.out = a.idx_out + hk * a.out_head_pitch + a.out_offsets[b];
+        sg.pad_to = k;
+    }
     __shared__ SelectShared<kTopkBlock> sm;
     select_segment<kTopkBlock>(sg, sm);
 }
