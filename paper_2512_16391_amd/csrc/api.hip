@@ -510,8 +510,9 @@ int check_prefill(const kascade_desc* desc, const void* q, const void* k, const 
     if (seqlen <= 0 || T <= 0 || idx_total < 0) return KASCADE_INVALID_ARG;
     if (idx_total > 0 && !idx) return KASCADE_INVALID_ARG;
     if (desc->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
-    // a query tile is 128 (token, head) rows: T tokens times the G heads of a key head
-    if ((int64_t)T * (desc->n_q_heads / desc->n_kv_heads) != 128) return KASCADE_UNSUPPORTED;
+    // a query tile is T tokens times the G heads of a key head; a workgroup owns 128 of those
+    // (token, head) rows, so a tile is one or several whole workgroups
+    if (((int64_t)T * (desc->n_q_heads / desc->n_kv_heads)) % 128 != 0) return KASCADE_UNSUPPORTED;
     // the kernels address the rows of one key head with 32-bit byte offsets
     if ((int64_t)seqlen * desc->kv_stride[2] * 2 >= ((int64_t)1 << 32)) return KASCADE_UNSUPPORTED;
     if ((desc->o_stride[1] * 2) % 8 || (desc->o_stride[2] * 2) % 8) return KASCADE_MISALIGNED;
@@ -519,11 +520,13 @@ int check_prefill(const kascade_desc* desc, const void* q, const void* k, const 
     return KASCADE_OK;
 }
 
-PrefillArgs prefill_args(const void* q, const void* k, const void* v, void* out, int32_t seqlen, int32_t T,
+PrefillArgs prefill_args(const Shape& s, const void* q, const void* k, const void* v, void* out, int32_t seqlen, int32_t T,
                          const int32_t* k_per_tile, const int64_t* idx_offsets, int64_t idx_total) {
     PrefillArgs a = {};
     a.q = q; a.k = k; a.v = v; a.out = out; a.seqlen = seqlen; a.tile_tokens = T;
     a.n_tiles = (seqlen + T - 1) / T;
+    a.sub_tokens = 128 / s.G;
+    a.n_sub = (seqlen + a.sub_tokens - 1) / a.sub_tokens;
     a.k_per_tile = k_per_tile; a.idx_offsets = idx_offsets; a.idx_total = idx_total;
     return a;
 }
@@ -546,7 +549,7 @@ static int prefill_anchor_impl(const kascade_desc* desc, const void* q, const vo
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool dense = out_mode == KASCADE_OUT_DENSE;
 
-    PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
+    PrefillArgs a = prefill_args(s, q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
     a.stats = ws.stats; a.pooled = ws.pooled; a.pooled_pitch = ws.pooled_pitch;
     // pass 1: causal scores -> row statistics (layer 0: plus the dense output)
     st = timed(dense ? K_PF_SWEEP1_V : K_PF_SWEEP1, stream, [&] { return launch_prefill_attend(s, a, false, dense, stream); });
@@ -606,7 +609,7 @@ int kascade_prefill_anchor_presoftmax(const kascade_desc* desc, const void* q, c
     if (!aligned16(workspace)) return KASCADE_MISALIGNED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool dense = out_mode == KASCADE_OUT_DENSE;
-    PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
+    PrefillArgs a = prefill_args(s, q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
     if (a.n_tiles > 65535) return KASCADE_UNSUPPORTED;   // one grid row per tile in the decode kernels
 
     // layer 0: plain causal attention for the output; it plays no part in the selection
@@ -654,7 +657,7 @@ int kascade_prefill_reuse(const kascade_desc* desc, const void* q, const void* k
     if (!head_map && n_anchor_heads != desc->n_kv_heads) return KASCADE_INVALID_ARG;
     const Shape s = make_shape(desc);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    PrefillArgs a = prefill_args(q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
+    PrefillArgs a = prefill_args(s, q, k, v, out, seqlen, q_tile_tokens, k_per_tile, idx_offsets, idx_total);
     a.idx = idx_in; a.head_map = head_map; a.n_src_heads = n_anchor_heads;
     return timed(K_PF_SPARSE, stream, [&] { return launch_prefill_attend(s, a, true, true, stream); });
 }

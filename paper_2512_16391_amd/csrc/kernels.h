@@ -163,7 +163,8 @@ struct PrefillArgs {
     const int32_t* head_map;      // [Hkv] or null
     int64_t idx_total;
     int32_t n_src_heads;
-    int32_t seqlen, tile_tokens, n_tiles;
+    int32_t seqlen, tile_tokens, n_tiles;   // a tile: tile_tokens tokens x G heads = a multiple of 128 rows
+    int32_t sub_tokens, n_sub;              // a workgroup's share: 128 / G tokens (x G heads = 128 rows); ceil(seqlen / sub_tokens)
     int32_t* topk_out;            // pool kernel: [Hkv, idx_total] receives the per-(tile, head) Top-k sets; null = pooled scores only
 };
 // sparse = false: all keys up to the diagonal (causal); with_v = false computes statistics only

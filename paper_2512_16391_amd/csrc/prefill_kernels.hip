@@ -1,8 +1,11 @@
 // Prefill kernels of the Kascade hot path (gfx950, bf16 MFMA 32x32x16, fp32 softmax).
 //
-// A query tile is T consecutive tokens times the G query heads of one key head = 128 rows
-// (paper Sec. 3.4).  One workgroup of four waves owns one (tile, key head); wave w owns rows
-// 32w..32w+31, row rho = g*T + token_in_tile.  Keys are processed in blocks of 64 held in LDS,
+// A query tile is T consecutive tokens times the G query heads of one key head (paper Sec. 3.4):
+// 128 rows in the paper's configuration, any multiple of 128 here.  One workgroup of four waves owns
+// 128 rows = Ts = 128/G consecutive tokens times the G heads (a whole tile, or one of its R = T/Ts
+// parts); wave w owns rows 32w..32w+31, row rho = g*Ts + token_in_part.  Index sets, their budget
+// and the Top-k candidates (the keys before the tile) belong to the tile; the causal diagonal of a
+// part runs from the tile's first token to the part's last.  Keys are processed in blocks of 64 held in LDS,
 // K and V row-major and XOR-swizzled against bank conflicts; V^T operand fragments come from the
 // transposing LDS read (ds_read_b64_tr_b16).  Tiles are double buffered and filled by direct
 // global-to-LDS loads, so block kb+1 streams in while block kb is multiplied and a block costs one
@@ -173,17 +176,21 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     __shared__ int smFlag[3];   // "block holds a slot without a key", rotating over three blocks
 
     const int hk = blockIdx.x % s.Hkv;
-    const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;   // long tiles first
-    const int T = a.tile_tokens, S = a.seqlen;
+    const int u = a.n_sub - 1 - blockIdx.x / s.Hkv;     // this workgroup's 128 rows; long ones first
+    const int Ts = a.sub_tokens, S = a.seqlen;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, held in a scalar register
     const int q = lane & 31, h = lane >> 5;
-    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
+    const RowMap rm = map_row(w * 32 + q, u, Ts, hk, s.G, S);
     const int q_token = rm.ok ? rm.token : INT_MAX - 1;
     const float c = s.scale_log2;
 
-    const int prefix = t * T;
-    const int diag_end = (prefix + T < S) ? prefix + T : S;
+    // sparse: the tile these rows belong to owns the index list and the candidates end where it starts;
+    // dense: plain causal attention, everything before the rows' own first token is unmasked
+    const int own = u * Ts;
+    const int t = own / a.tile_tokens;
+    const int prefix = SPARSE ? t * a.tile_tokens : own;
+    const int diag_end = (own + Ts < S) ? own + Ts : S;
     int n_sparse = 0, nb_gather = 0, n_blocks;
     const int32_t* idx = nullptr;
     if constexpr (SPARSE) {
@@ -469,8 +476,10 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
 // Anchor pass 2 with two K tiles in LDS filled by direct loads: block kb+1 streams in while block
 // kb is multiplied; one barrier per block.  The cross-wave sum of block kb's column partials is
 // taken after the next barrier (two partial buffers), so it needs no barrier of its own.
-template <int D>
-__global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillArgs a) {
+// MULTI: the tile has more than 128 rows and is swept in parts (kept out of the one-part kernel,
+// whose register budget it would break).
+template <int D, bool MULTI>
+__global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
     constexpr int PART = kPW * BK * (int)sizeof(float);
     // two K tiles and two buffers of column partials during the sweep; afterwards the same memory
@@ -484,76 +493,87 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
 
     const int hk = blockIdx.x % s.Hkv;
     const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
-    const int T = a.tile_tokens, S = a.seqlen;
+    const int T = a.tile_tokens, Ts = a.sub_tokens, S = a.seqlen;
     const int prefix = t * T;
     if (prefix == 0) return;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, held in a scalar register
     const int q = lane & 31, h = lane >> 5;
     const float c = s.scale_log2;
-    const int diag_end = (prefix + T < S) ? prefix + T : S;
-    const float inv_rows = 1.f / (float)((diag_end - prefix) * s.G);
+    const int tile_end = (prefix + T < S) ? prefix + T : S;
+    const float inv_rows = 1.f / (float)((tile_end - prefix) * s.G);
     const int n_blocks = (prefix + BK - 1) / BK;
+    const int n_parts = MULTI ? (tile_end - prefix + Ts - 1) / Ts : 1;   // 128 rows at a time
 
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
     const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
     const uint32_t coff = Dma<D>::chunk_off();
-    dma_rows_seq<D>(smK0, Kb, row_bytes, 0, prefix - 1, coff, w);
-
-    const RowMap rm = map_row(w * 32 + q, t, T, hk, s.G, S);
-    bf16x8_t qf[KSTEPS];
-    {
-        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
-            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
-        }
-    }
-    // e_r = m + log2(l * rows) of the query rows whose scores land in this lane's registers;
-    // rows beyond the sequence get weight 0
-    float e_r[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const RowMap rr = map_row(w * 32 + (r >> 2) * 8 + h * 4 + (r & 3), t, T, hk, s.G, S);
-        e_r[r] = INFINITY;
-        if (rr.ok) {
-            const float* st = a.stats + ((int64_t)rr.head * S + rr.token) * 2;
-            e_r[r] = st[0] + __builtin_amdgcn_logf(st[1] / inv_rows);
-        }
-    }
     const int key0 = perm_key(q), key1 = 32 + key0;
     float* dst = a.pooled + hk * a.pooled_pitch + (int64_t)T * t * (t - 1) / 2;
 
+    // Every part sweeps the tile's whole prefix with its own 128 rows; the first writes the column
+    // sums, the others add theirs to what is there (same thread, same address: program order).
+    for (int part = 0; part < n_parts; ++part) {
+        const int u = prefix / Ts + part;
+        dma_rows_seq<D>(smK0, Kb, row_bytes, 0, prefix - 1, coff, w);
+
+        const RowMap rm = map_row(w * 32 + q, u, Ts, hk, s.G, S);
+        bf16x8_t qf[KSTEPS];
+        {
+            const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rm.token * s.q_stride[1] + (int64_t)rm.head * s.q_stride[2];
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                uint4 raw = make_uint4(0, 0, 0, 0);
+                if (rm.ok) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+                qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+            }
+        }
+        // e_r = m + log2(l * rows) of the query rows whose scores land in this lane's registers;
+        // rows beyond the sequence get weight 0
+        float e_r[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const RowMap rr = map_row(w * 32 + (r >> 2) * 8 + h * 4 + (r & 3), u, Ts, hk, s.G, S);
+            e_r[r] = INFINITY;
+            if (rr.ok) {
+                const float* st = a.stats + ((int64_t)rr.head * S + rr.token) * 2;
+                e_r[r] = st[0] + __builtin_amdgcn_logf(st[1] / inv_rows);
+            }
+        }
+
+#define KASCADE_POOL_STORE(part_, kb_)                                                                         \
+        if (threadIdx.x < BK) {                                                                                \
+            const int j_ = (kb_) * BK + threadIdx.x;                                                           \
+            if (j_ < prefix) {                                                                                 \
+                const float sum_ = (part_[0][threadIdx.x] + part_[1][threadIdx.x]) +                           \
+                                   (part_[2][threadIdx.x] + part_[3][threadIdx.x]);                            \
+                dst[j_] = (!MULTI || part == 0) ? sum_ : dst[j_] + sum_;                                       \
+            }                                                                                                  \
+        }
 #define KASCADE_POOL_STEP(kb_, cur_, nxt_, part_cur_, part_prev_)                                              \
-    {                                                                                                          \
-        wait_vmem();                                                                                           \
-        __syncthreads();                                                                                       \
-        if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(nxt_, Kb, row_bytes, ((kb_) + 1) * BK, prefix - 1, coff, w);    \
-        if ((kb_) > 0 && threadIdx.x < BK) {                                                                   \
-            const int j_ = ((kb_) - 1) * BK + threadIdx.x;                                                     \
-            if (j_ < prefix)                                                                                   \
-                dst[j_] = (part_prev_[0][threadIdx.x] + part_prev_[1][threadIdx.x]) +                          \
-                          (part_prev_[2][threadIdx.x] + part_prev_[3][threadIdx.x]);                           \
-        }                                                                                                      \
-        pool_block<D>(cur_, part_cur_, qf, e_r, c, key0, key1, h, w);                                          \
-    }
-    int kb = 0;
-    for (; kb + 1 < n_blocks; kb += 2) {
-        KASCADE_POOL_STEP(kb, smK0, smK1, smPart0, smPart1)
-        KASCADE_POOL_STEP(kb + 1, smK1, smK0, smPart1, smPart0)
-    }
-    if (kb < n_blocks) {
-        KASCADE_POOL_STEP(kb, smK0, smK1, smPart0, smPart1)
-        ++kb;
-    }
+        {                                                                                                      \
+            wait_vmem();                                                                                       \
+            __syncthreads();                                                                                   \
+            if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(nxt_, Kb, row_bytes, ((kb_) + 1) * BK, prefix - 1, coff, w); \
+            if ((kb_) > 0) KASCADE_POOL_STORE(part_prev_, (kb_) - 1)                                           \
+            pool_block<D>(cur_, part_cur_, qf, e_r, c, key0, key1, h, w);                                      \
+        }
+        int kb = 0;
+        for (; kb + 1 < n_blocks; kb += 2) {
+            KASCADE_POOL_STEP(kb, smK0, smK1, smPart0, smPart1)
+            KASCADE_POOL_STEP(kb + 1, smK1, smK0, smPart1, smPart0)
+        }
+        if (kb < n_blocks) {
+            KASCADE_POOL_STEP(kb, smK0, smK1, smPart0, smPart1)
+            ++kb;
+        }
+        __syncthreads();   // the last block's partials are complete; every read of the K tiles is done
+        {
+            float (*last)[BK] = (kb & 1) ? smPart0 : smPart1;
+            KASCADE_POOL_STORE(last, kb - 1)
+        }
 #undef KASCADE_POOL_STEP
-    __syncthreads();
-    if (threadIdx.x < BK) {
-        float (*last)[BK] = (kb & 1) ? smPart0 : smPart1;
-        const int j = (kb - 1) * BK + threadIdx.x;
-        if (j < prefix) dst[j] = (last[0][threadIdx.x] + last[1][threadIdx.x]) + (last[2][threadIdx.x] + last[3][threadIdx.x]);
+#undef KASCADE_POOL_STORE
     }
     // anchor pass 3 for this (tile, key head): the pooled scores of the tile were all written by this
     // workgroup, so it selects right away - while it does, the other workgroups of the compute unit keep
@@ -575,7 +595,7 @@ __global__ __launch_bounds__(kPB, 4) void prefill_pool_kernel(Shape s, PrefillAr
 }  // namespace
 
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
-    dim3 grid(a.n_tiles * s.Hkv), block(kPB);
+    dim3 grid(a.n_sub * s.Hkv), block(kPB);   // one workgroup per 128 rows
 #define KASCADE_LAUNCH_ATTEND(DD)                                                                                      \
     if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true>), grid, block, 0, st, s, a);                 \
     else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true>), grid, block, 0, st, s, a);           \
@@ -589,8 +609,11 @@ hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool spar
 
 hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t st) {
     dim3 grid(a.n_tiles * s.Hkv), block(kPB);
-    if (s.D == 128) hipLaunchKernelGGL((prefill_pool_kernel<128>), grid, block, 0, st, s, a);
-    else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_kernel<64>), grid, block, 0, st, s, a);
+    const bool multi = a.tile_tokens != a.sub_tokens;
+    if (s.D == 128 && !multi) hipLaunchKernelGGL((prefill_pool_kernel<128, false>), grid, block, 0, st, s, a);
+    else if (s.D == 128) hipLaunchKernelGGL((prefill_pool_kernel<128, true>), grid, block, 0, st, s, a);
+    else if (s.D == 64 && !multi) hipLaunchKernelGGL((prefill_pool_kernel<64, false>), grid, block, 0, st, s, a);
+    else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_kernel<64, true>), grid, block, 0, st, s, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

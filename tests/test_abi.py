@@ -110,7 +110,8 @@ def test_prefill_argument_checks(lib):
     # fake pointers again: all of these return from validation
     bf = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=binding.KASCADE_BF16,
               q_stride=(0, 32 * 128, 128), kv_stride=(0, 4096 * 128, 128), o_stride=(0, 32 * 128, 128))
-    assert call_prefill_reuse(lib, make_desc(**bf), 4096, 64) == -2                       # T * G = 256
+    assert call_prefill_reuse(lib, make_desc(**bf), 4096, 16) == -2                       # T * G = 64
+    assert call_prefill_reuse(lib, make_desc(**bf), 4096, 48) == -2                       # T * G = 192
     assert call_prefill_reuse(lib, make_desc(**{**bf, "dtype": binding.KASCADE_F32}), 4096, 32) == -2
     assert call_prefill_reuse(lib, make_desc(**{**bf, "batch": 2}), 4096, 32) == -1
     assert call_prefill_reuse(lib, make_desc(**bf), 0, 32) == -1

@@ -82,6 +82,32 @@ def test_prefill_anchor_small(S, Hq, Hkv, d, T, out_mode):
     run_anchor(q, k, v, T, kpt, out_mode, where=f"S{S}")
 
 
+@pytest.mark.parametrize("S,Hq,Hkv,d,T", [
+    (700, 8, 2, 128, 128),     # 512 rows per tile (four workgroups), last tile 60 tokens = two parts, the second ragged
+    (500, 4, 2, 128, 128),     # G = 2: 256 rows, last tile 116 tokens
+    (600, 2, 2, 64, 256),      # G = 1: 256 rows, tiles of 256 tokens
+    (330, 16, 2, 64, 64),      # G = 8: 512 rows, parts of 16 tokens
+])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_prefill_anchor_tiles_larger_than_one_workgroup(S, Hq, Hkv, d, T, out_mode):
+    """Tiles of 256 and 512 (token, head) rows: one index set per tile, pooled over all of its rows,
+    shared by the two or four workgroups that attend for it; then a reuse layer on the same sets."""
+    print(f"case prefill large tiles S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} out_mode={out_mode}", flush=True)
+    q, k, v = random_prefill(S + 1, S, Hq, Hkv, d)
+    kpt = workloads.prefill_budgets(S, T, 150, 40)
+    idx, _ = run_anchor(q, k, v, T, kpt, out_mode, where=f"S{S} T{T}")
+    q2, k2, v2 = random_prefill(S + 2, S, Hq, Hkv, d)
+    off = offsets(kpt)
+    out = binding.kascade_prefill_reuse(q2.to(DEV), k2.to(DEV), v2.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                        torch.from_numpy(idx).to(DEV))
+    torch.cuda.synchronize()
+    Q, Kp, Vp, o = f64(q2), f64(k2), f64(v2), f64(out)
+    for t, kt in enumerate(kpt):
+        lo, hi = ko.tile_bounds(t, T, S)
+        ref = ko.prefill_sparse_tile(Q, Kp, Vp, t, T, [idx[h, off[t]:off[t] + kt] for h in range(Hkv)], ko.default_scale(d))
+        assert max_abs(o[lo:hi], ref) <= TOL_OUT[BF16]
+
+
 def test_prefill_anchor_tile_reduces_to_dense_when_k_covers_prefix():
     # k_t = whole prefix for every tile: the sparse output must equal dense causal attention
     S, Hq, Hkv, d, T = 256, 8, 2, 128, 32
@@ -172,8 +198,11 @@ def test_prefill_config4_shape_reduced_length():
 def test_prefill_rejects_unsupported():
     q, k, v = random_prefill(1, 64, 8, 2, 128)
     kpt, off = [0, 0], [0, 0, 0]
-    with pytest.raises(binding.KascadeError) as e:      # T * G must be 128
+    with pytest.raises(binding.KascadeError) as e:      # T * G must be a multiple of 128 (here 64)
         binding.kascade_prefill_anchor(q.to(DEV), k.to(DEV), v.to(DEV), 16, dev_i32([0] * 4), dev_i64([0] * 5), 0)
+    assert e.value.status == -2
+    with pytest.raises(binding.KascadeError) as e:      # 192 rows
+        binding.kascade_prefill_anchor(q.to(DEV), k.to(DEV), v.to(DEV), 48, dev_i32([0] * 2), dev_i64([0] * 3), 0)
     assert e.value.status == -2
     with pytest.raises(binding.KascadeError) as e:      # fp32 prefill is not built
         binding.kascade_prefill_anchor(q.float().to(DEV), k.float().to(DEV), v.float().to(DEV), 32, dev_i32(kpt),

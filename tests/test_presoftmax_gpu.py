@@ -71,7 +71,8 @@ def test_decode_presoftmax_differs_from_post_softmax_pooling_and_agrees_for_sing
         assert torch.equal(pre, post) == expect_same
 
 
-@pytest.mark.parametrize("S,Hq,Hkv,d,T", [(300, 8, 2, 128, 32), (200, 4, 2, 64, 64), (260, 2, 2, 64, 128), (1100, 8, 2, 128, 32)])
+@pytest.mark.parametrize("S,Hq,Hkv,d,T", [(300, 8, 2, 128, 32), (200, 4, 2, 64, 64), (260, 2, 2, 64, 128), (1100, 8, 2, 128, 32),
+                                          (520, 8, 2, 128, 128)])
 @pytest.mark.parametrize("out_mode", [0, 1])
 def test_prefill_presoftmax(S, Hq, Hkv, d, T, out_mode):
     print(f"case prefill pre-softmax S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} out_mode={out_mode}", flush=True)

@@ -53,7 +53,8 @@ def test_decode_shared_sets(dtype, d, Hq, Hkv, W):
         assert max_abs(f64(out)[b], want) <= TOL_OUT[dtype]
 
 
-@pytest.mark.parametrize("S,Hq,Hkv,d,T", [(300, 8, 2, 128, 32), (200, 4, 2, 64, 64), (260, 2, 2, 64, 128)])
+@pytest.mark.parametrize("S,Hq,Hkv,d,T", [(300, 8, 2, 128, 32), (200, 4, 2, 64, 64), (260, 2, 2, 64, 128),
+                                          (520, 8, 2, 128, 128)])
 @pytest.mark.parametrize("out_mode", [0, 1])
 def test_prefill_shared_sets(S, Hq, Hkv, d, T, out_mode):
     print(f"case prefill shared S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} out_mode={out_mode}", flush=True)
