@@ -136,17 +136,23 @@ def main():
     prefill_cases = [(S, 100) for S in (8192, 16384, 32768, 65536, 131072, 262144) if S <= args.max_prefill_context]
     if not args.quick and args.max_prefill_context >= 32768:
         prefill_cases += [(32768, 200), (32768, 300)]
-    for S, pm in prefill_cases:
+    if not args.quick and args.max_prefill_context >= 32768:
+        prefill_cases += [(32768, 100, 128)]      # tiles of 128 tokens x 4 heads = 512 rows (one index set per 512 rows)
+    for case in prefill_cases:
+        S, pm = case[0], case[1]
+        T = case[2] if len(case) > 2 else 32
         reps = 5 if S <= 32768 else (2 if S <= 131072 else 1)
-        row = finish(prefill_row(torch, binding, workloads, dev, S, pm, reps), PAPER_PREFILL)
+        row = finish(prefill_row(torch, binding, workloads, dev, S, pm, reps, T), PAPER_PREFILL if T == 32 else {})
         rows.append(row)
         print(json.dumps(row), flush=True)
         torch.cuda.empty_cache()
-    hdr = f"{'mode':8s}{'context':>9s}{'batch':>6s}{'topk':>6s}{'dense':>10s}{'anchor0':>10s}{'anchor':>10s}{'reuse':>10s}" \
+    print("prefill rows use tiles of 32 tokens x 4 heads = 128 rows unless tile_tokens says otherwise")
+    hdr = f"{'mode':12s}{'context':>9s}{'batch':>6s}{'topk':>6s}{'dense':>10s}{'anchor0':>10s}{'anchor':>10s}{'reuse':>10s}" \
           f"{'avg':>10s}{'speedup':>9s}{'paper avg':>11s}{'paper x':>9s}"
     print(hdr)
     for r in rows:
-        print(f"{r['mode']:8s}{r['context']:9d}{r['batch']:6d}{r['topk_permille'] // 10:5d}%{r['dense_ms']:10.3f}"
+        mode = r['mode'] if r.get('tile_tokens', 32) == 32 else f"{r['mode']}/T{r['tile_tokens']}"
+        print(f"{mode:12s}{r['context']:9d}{r['batch']:6d}{r['topk_permille'] // 10:5d}%{r['dense_ms']:10.3f}"
               f"{r['anchor0_ms']:10.3f}{r['anchor_ms']:10.3f}{r['reuse_ms']:10.3f}{r['kascade_avg_ms']:10.3f}"
               f"{r['speedup_vs_own_dense']:8.2f}x{r.get('paper_h100_avg_ms', float('nan')):11.2f}"
               f"{r.get('paper_h100_speedup_vs_fa3', float('nan')):8.2f}x")

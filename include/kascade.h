@@ -115,8 +115,9 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
  * post-softmax weight (row normalisers include the diagonal keys).  k_per_tile[t]
  * <= t*T keys are selected per key head; the diagonal block t*T..i is always
  * attended on top, causally.
- *   q [S,Hq,d] per q_stride;  k, v [Hkv,S,d] per kv_stride; bf16 only, T*G = 128, and the rows of one
- *   key head must span less than 4 GiB (S * kv_stride[2] * 2 bytes), else KASCADE_UNSUPPORTED
+ *   q [S,Hq,d] per q_stride;  k, v [Hkv,S,d] per kv_stride; bf16 only, T*G a multiple of 128 (the
+ *   paper's tile is T*G = 128 rows), and the rows of one key head must span less than 4 GiB
+ *   (S * kv_stride[2] * 2 bytes), else KASCADE_UNSUPPORTED
  *   k_per_tile  [n_tiles] int32 (device), idx_offsets [n_tiles+1] int64 (device),
  *               idx_offsets[t+1]-idx_offsets[t] = k_per_tile[t], idx_total = idx_offsets[n_tiles]
  *   idx_out  [Hkv, idx_total] int32: tile t of head hk at hk*idx_total + idx_offsets[t]
