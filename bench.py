@@ -244,6 +244,8 @@ def main():
 
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_seqs)
+        if prefill is not None:
+            rec["cpu_baseline_prefill"] = cpu_baseline_prefill(prefill)
     print(json.dumps(rec), flush=True)
 
 
@@ -392,6 +394,35 @@ def cpu_baseline(wl, n_seqs):
     return {"value": round(us_per_layer, 1), "unit": "us/layer (decode, scaled to the full batch)",
             "cores": _blas_threads(), "kind": "oracle",
             "sample": f"{n_seqs} of {wl.B} sequences, all heads, 1 anchor + 3 reuse layers, {dt:.2f} s measured"}
+
+
+def cpu_baseline_prefill(pb, tiles=(0, 1, 80, 81, 300, 600, 1023)):
+    """The fp64 oracle on a sample of query tiles of the prefill anchor layer (first tiles, the tiles
+    where 10 % of the prefix passes the minimum budget, some in between, the last one): pooled scores,
+    Top-k and sparse attention per tile.  A tile's work grows with the keys before it, so the sample
+    is extrapolated to the whole layer by (prefix + half a tile) and reported as such."""
+    import torch
+    from oracle import kascade_oracle as ko
+
+    wl = pb.wl
+    a = wl.layers[0]
+    f = lambda t: t.to("cpu").to(torch.float32).to(torch.float64).numpy()
+    Q, Kp, Vp = f(a.q), f(a.k), f(a.v)
+    scale = ko.default_scale(wl.d)
+    tiles = [t for t in tiles if t < wl.n_tiles]
+    weight = lambda t: t * wl.T + 0.5 * wl.T
+    t0 = time.perf_counter()
+    for t in tiles:
+        kt = wl.k_per_tile[t]
+        idx, _ = ko.prefill_anchor_indices_tile(Q, Kp, t, wl.T, scale, kt)
+        ko.prefill_sparse_tile(Q, Kp, Vp, t, wl.T, idx, scale)
+    dt = time.perf_counter() - t0
+    full_s = dt * sum(weight(t) for t in range(wl.n_tiles)) / sum(weight(t) for t in tiles)
+    flop = 2.0 * pb.U + pb.sparse_flop
+    return {"value": round(flop / full_s / 1e12, 5), "unit": "TFLOP/s (prefill anchor layer, sparse output, extrapolated)",
+            "cores": _blas_threads(), "kind": "oracle",
+            "sample": f"tiles {tiles} of {wl.n_tiles}, all heads, {dt:.2f} s measured, {full_s:.0f} s extrapolated by keys per tile",
+            "anchor_layer_s_extrapolated": round(full_s, 1)}
 
 
 if __name__ == "__main__":
