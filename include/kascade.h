@@ -61,7 +61,7 @@ enum {
 };
 
 typedef struct {
-    int32_t batch;          /* sequences (decode); must be 1 for prefill                 */
+    int32_t batch;          /* sequences (decode), at most 65535; must be 1 for prefill  */
     int32_t n_q_heads;      /* Hq                                                        */
     int32_t n_kv_heads;     /* Hkv, divides Hq; G = Hq/Hkv in {1,2,4,8}                  */
     int32_t head_dim;       /* d in {64, 128}                                            */

@@ -36,6 +36,8 @@ int check_desc(const kascade_desc* d, bool prefill) {
     if (d->batch <= 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0) return KASCADE_INVALID_ARG;
     if (d->n_q_heads % d->n_kv_heads) return KASCADE_INVALID_ARG;
     if (prefill && d->batch != 1) return KASCADE_INVALID_ARG;
+    // sequences and key heads are grid dimensions y / z of the decode kernels
+    if (d->batch > 65535 || d->n_kv_heads > 65535) return KASCADE_UNSUPPORTED;
     const int G = d->n_q_heads / d->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return KASCADE_UNSUPPORTED;
     if (d->head_dim != 64 && d->head_dim != 128) return KASCADE_UNSUPPORTED;

@@ -117,6 +117,9 @@ int main() {
     bad = good; bad.n_q_heads = 32; bad.n_kv_heads = 2;   // G = 16
     EXPECT(kascade_decode_anchor(&bad, fake, fake, fake, (int32_t*)fake, (int32_t*)fake, 4096, 400, 0, 1, (int32_t*)fake, fake,
                                  fake, (size_t)1 << 40, nullptr) == KASCADE_UNSUPPORTED);
+    bad = good; bad.batch = 70000;
+    EXPECT(kascade_decode_anchor(&bad, fake, fake, fake, (int32_t*)fake, (int32_t*)fake, 4096, 400, 0, 1, (int32_t*)fake, fake,
+                                 fake, (size_t)1 << 40, nullptr) == KASCADE_UNSUPPORTED);
     bad = good; bad.head_dim = 96;
     EXPECT(kascade_decode_anchor(&bad, fake, fake, fake, (int32_t*)fake, (int32_t*)fake, 4096, 400, 0, 1, (int32_t*)fake, fake,
                                  fake, (size_t)1 << 40, nullptr) == KASCADE_UNSUPPORTED);
