@@ -411,3 +411,51 @@ def test_decode_anchor_split_and_single_selection_agree(monkeypatch):
     for parts in ("7", "64"):
         assert torch.equal(res[parts][0], res["1"][0])
         assert torch.equal(res[parts][1], res["1"][1])
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [(torch.bfloat16, 128, 8, 2), (torch.float32, 64, 4, 4)])
+@pytest.mark.parametrize("variant", ["per_head", "shared", "presoftmax"])
+def test_decode_anchor_degenerate_sequences(dtype, d, Hq, Hkv, variant):
+    """Sequences of zero, one and a few keys, k = 0, k = 1, k = L and a window as large as k, next to an
+    ordinary sequence in the same batch: empty sets give a zero output and an all -1 index row, the rest
+    matches the oracle."""
+    print(f"case degenerate decode dtype={dtype} d={d} Hq={Hq} Hkv={Hkv} variant={variant}", flush=True)
+    lens = [0, 1, 5, 300, 64, 7]
+    ks = [0, 1, 5, 30, 0, 3]
+    storage = {torch.float32: "fp32", torch.bfloat16: "bf16"}[dtype]
+    q, k, v = random_case(99, len(lens), Hq, Hkv, d, dtype, lens, Lmax=320)
+    call = {"per_head": binding.kascade_decode_anchor, "shared": binding.kascade_decode_anchor_shared,
+            "presoftmax": binding.kascade_decode_anchor_presoftmax}[variant]
+    scale = ko.default_scale(d)
+    for W in (0, 3):
+        ks_w = ks       # where the window exceeds k the kernels shrink it to k, as the oracle call below does
+        for mode in (binding.KASCADE_OUT_SPARSE, binding.KASCADE_OUT_DENSE):
+            idx, out = call(q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks_w), 320, max(ks_w), recent_window=W,
+                            out_mode=mode)
+            torch.cuda.synchronize()
+            idx_h, o = idx.cpu().numpy(), f64(out)
+            n_sets = 1 if variant == "shared" else Hkv
+            for b, (L, kb) in enumerate(zip(lens, ks_w)):
+                assert (idx_h[b, :, kb:] == -1).all()
+                if L == 0:
+                    assert np.all(o[b] == 0.0)
+                    continue
+                qb, kb_, vb = f64(q[b]), f64(k[b, :, :L]), f64(v[b, :, :L])
+                if kb > 0:
+                    if variant == "per_head":
+                        ref_idx, a = ko.decode_anchor_indices(qb, kb_, scale, kb, min(W, kb))
+                    elif variant == "presoftmax":
+                        ref_idx, a = ko.decode_presoftmax_indices(qb, kb_, scale, kb, storage, min(W, kb))
+                    else:
+                        ri, aa = ko.decode_shared_indices(qb, kb_, scale, kb, min(W, kb))
+                        ref_idx, a = ri[None], aa[None]
+                    for h in range(n_sets):
+                        check_index_set(idx_h[b, h, :kb], ref_idx[h], a[h], n_forced=min(W, kb), where=f"b{b} h{h}")
+                if mode == binding.KASCADE_OUT_DENSE:
+                    want = ko.dense_decode(qb, kb_, vb, scale)
+                elif kb == 0:
+                    want = np.zeros_like(o[b])
+                else:
+                    sets = [idx_h[b, h, :kb] for h in range(n_sets)]
+                    want = ko.sparse_decode(qb, kb_, vb, sets, scale, None if variant != "shared" else [0] * Hkv)
+                assert max_abs(o[b], want) <= TOL_OUT[dtype], f"b{b} L{L} k{kb} mode{mode}"
