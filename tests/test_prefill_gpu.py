@@ -405,3 +405,26 @@ def test_prefill_anchor_random_shapes(seed):
     print(f"case prefill anchor random seed={seed}: S={S} Hq={Hq} Hkv={Hkv} d={d} T={T} k_t={kpt}", flush=True)
     q, k, v = random_prefill(4000 + seed, S, Hq, Hkv, d)
     run_anchor(q, k, v, T, kpt, seed % 2, where=f"random {seed}")
+
+
+@pytest.mark.parametrize("S", [1, 31, 32, 33, 64, 65])
+def test_prefill_anchor_and_reuse_tiny_prompts(S):
+    """Prompts of one token, just under / exactly / just over one tile and two tiles: tile 0 never has
+    candidates, a tile with k_t = 0 attends its diagonal only."""
+    print(f"case prefill tiny S={S}", flush=True)
+    Hq, Hkv, d, T = 8, 2, 128, 32
+    q, k, v = random_prefill(700 + S, S, Hq, Hkv, d)
+    n_tiles = (S + T - 1) // T
+    for kpt in ([min(t * T, 5) for t in range(n_tiles)], [0] * n_tiles):
+        for mode in (0, 1):
+            idx, _ = run_anchor(q, k, v, T, kpt, mode, where=f"S{S} k_t={kpt} mode{mode}")
+        off = offsets(kpt)
+        out = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                            torch.from_numpy(idx).to(DEV))
+        torch.cuda.synchronize()
+        o = f64(out)
+        for t, kt in enumerate(kpt):
+            lo, hi = ko.tile_bounds(t, T, S)
+            ref = ko.prefill_sparse_tile(f64(q), f64(k), f64(v), t, T, [idx[h, off[t]:off[t] + kt] for h in range(Hkv)],
+                                         ko.default_scale(d))
+            assert max_abs(o[lo:hi], ref) <= TOL_OUT[BF16]
