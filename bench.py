@@ -92,6 +92,14 @@ def main():
     cal_dst = torch.empty_like(cal_src)
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
+    # the same copy timed: what a plain device-to-device copy reaches on this machine (read + write bytes)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        cal_dst.copy_(cal_src)
+    c1.record()
+    c1.synchronize()
+    copy_gbs = 5 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del cal_src, cal_dst
 
     for _ in range(args.warmup):
@@ -197,6 +205,7 @@ def main():
                          "pair's reading around an empty kernel",
         "event_pair_overhead_us": round(pair_us, 2),
         "decode_reuse_hbm_GBps": roofline_reuse["achieved"],
+        "device_copy_GBps_measured": round(copy_gbs, 1),
         "kernel_us": kernels_us,
         "kernel_us_raw_event_pairs": kernels_us_raw,
         "roofline": roofline,
