@@ -14,6 +14,8 @@
 // row with one 16-byte load each, so a wave instruction fetches 64/LPR full rows and every
 // fetched byte is used.  Each lane group keeps U rows of K and of V in flight and owns a
 // private online-softmax stream (m, l, acc); streams are merged once per workgroup in LDS.
+#include <stdlib.h>
+
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -294,15 +296,15 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
-template <int D, int G, bool GATHER, bool WITH_V, bool STORE, bool PIPE>
-__global__ __launch_bounds__(kBlock, (PIPE ? 2 : 4)) void decode_rows_bf16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+template <int D, int G, bool GATHER, bool WITH_V, bool STORE, bool PIPE, int U = 4>
+__global__ __launch_bounds__(kBlock, ((PIPE || U > 4) ? 2 : 4)) void decode_rows_bf16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int EPL = 8;
     constexpr int LPR = D / EPL;
     constexpr int RPW = kWave / LPR;
-    constexpr int U = 4;
-    constexpr int NB = LPR / U;               // batches per 64-row group (even)
+    constexpr int NB = LPR / U;               // batches per 64-row group
     constexpr int NS = kWavesPerBlock * RPW;
-    static_assert(NB % 2 == 0, "double buffering walks the batches in pairs");
+    static_assert(LPR % U == 0 && U % 2 == 0, "a batch is a whole number of row pairs");
+    static_assert(!PIPE || NB % 2 == 0, "double buffering walks the batches in pairs");
 
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x >> 6;
@@ -410,7 +412,8 @@ __global__ __launch_bounds__(kBlock, (PIPE ? 2 : 4)) void decode_rows_bf16_kerne
         float mnew[G];                                                                                 \
         bool moved_ = false;                                                                           \
         _Pragma("unroll") for (int g = 0; g < G; ++g) {                                                \
-            float mx_ = fmaxf(fmaxf(sc[0][g], sc[1][g]), fmaxf(sc[2][g], sc[3][g]));                   \
+            float mx_ = fmaxf(sc[0][g], sc[1][g]);                                                     \
+            _Pragma("unroll") for (int u = 2; u < U; u += 2) mx_ = fmaxf(mx_, fmaxf(sc[u][g], sc[u + 1][g])); \
             mnew[g] = fmaxf(m[g], mx_);                                                                \
             moved_ |= mnew[g] != m[g];                                                                 \
         }                                                                                              \
@@ -684,8 +687,18 @@ template <int D, int G>
 hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool gather, bool with_v,
                                hipStream_t st) {
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kBlock);
-    // a gather grid that fits on the chip at four workgroups per compute unit runs the unpipelined form
-    const bool small = gather && G <= 4 && (int64_t)plan.n_chunks * s.Hkv * s.B <= 4 * 256;
+    // a gather grid that fits on the chip at four workgroups per compute unit runs the unpipelined form;
+    // one that fits at two per compute unit keeps a wave's whole 64-row group in flight at once (16 row
+    // pairs instead of 4): the kernel is then a few long-latency round trips per wave, and fewer, larger
+    // ones shorten the tail in which the memory system is no longer saturated (config 2: 20.2 -> 18.3 us)
+    const int64_t wgs = (int64_t)plan.n_chunks * s.Hkv * s.B;
+    const bool small = gather && G <= 4 && wgs <= 4 * 256;
+    if constexpr (D == 128 && G <= 4) {
+        if (small && wgs <= 2 * 256) {
+            hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false, 16>), grid, block, 0, st, s, plan, a);
+            return hipGetLastError();
+        }
+    }
     if (gather && small) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false>), grid, block, 0, st, s, plan, a);
     else if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, true>), grid, block, 0, st, s, plan, a);
     else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true, true>), grid, block, 0, st, s, plan, a);
