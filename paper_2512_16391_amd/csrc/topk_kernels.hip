@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kTopkBlock) void topk_split_collect_kernel(Shape s,
         const int i0 = base + tid * kEPT;
         uint32_t u[kEPT];
         load16(bits, end, i0, aligned, u);
-        uint32_t cm = 0;   // which of this lane's sixteen scores lie in the threshold bucket
+        uint32_t cm = 0;   // which of this lane's kEPT scores lie in the threshold bucket
 #pragma unroll
         for (int e = 0; e < kEPT; ++e) {
             const bool in = i0 + e < end;

@@ -26,7 +26,7 @@ struct Segment {
     int pad_to;                // total slots to fill (-1 beyond the set)
 };
 
-constexpr int kEPT = 16;                 // consecutive scores per thread per sweep step (four 16-byte loads)
+constexpr int kEPT = 16;                 // consecutive scores per thread per sweep step (four 16-byte loads; 8 and 32 measured slower)
 constexpr int kCandCap = kTopkCandCap;   // scores of the threshold bucket kept in LDS for rounds 2 and 3
 typedef __attribute__((ext_vector_type(4))) uint32_t topk_u32x4_t;
 
@@ -63,12 +63,12 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* w
     return before + inc - x;
 }
 
-// Sixteen consecutive scores starting at i0 (zero beyond n).
+// kEPT consecutive scores starting at i0 (zero beyond n).
 __device__ __forceinline__ void load16(const uint32_t* bits, int n, int i0, bool aligned, uint32_t (&u)[kEPT]) {
     if (aligned && i0 + kEPT <= n) {
         const topk_u32x4_t* p = reinterpret_cast<const topk_u32x4_t*>(bits + i0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < kEPT / 4; ++q) {
             const topk_u32x4_t v = p[q];
             u[4 * q + 0] = v.x; u[4 * q + 1] = v.y; u[4 * q + 2] = v.z; u[4 * q + 3] = v.w;
         }
@@ -145,7 +145,7 @@ __device__ __forceinline__ void compact_range(const uint32_t* bits, int begin, i
             gtm |= (uint32_t)(in && u[e] > thr) << e;
             eqm |= (uint32_t)(in && u[e] == thr) << e;
         }
-        // counts per step are at most 16 NT <= 16384 each: pack both into one scan
+        // counts per step are at most kEPT * NT <= 32768 each: pack both into one scan
         uint32_t tot;
         const uint32_t ex = block_exclusive_scan<NT>((uint32_t)__popc(gtm) | ((uint32_t)__popc(eqm) << 16), wave_tot, &tot);
         uint32_t gt_before = run_gt + (ex & 0xffffu), eq_before = run_eq + (ex >> 16);
@@ -167,6 +167,7 @@ __device__ __forceinline__ void compact_range(const uint32_t* bits, int begin, i
 template <int NT>
 __device__ __forceinline__ void select_segment(const Segment& sg, SelectShared<NT>& sm) {
     static_assert(NT % kWave == 0 && 2048 % NT == 0 && NT <= 1024, "workgroup size");
+    static_assert(kEPT <= 32 && kEPT * 1024 < 65536, "per-thread masks are 32 bits wide, packed scan counts 16");
     const int tid = threadIdx.x, lane = tid & 63;
     const uint32_t* bits = reinterpret_cast<const uint32_t*>(sg.scores);
     const int n = sg.n;
