@@ -240,27 +240,26 @@ def config5_layer_kind(layer: int):
     return ("anchor" if layer in CONFIG5_ANCHORS else "reuse"), src
 
 
-def config5_prefill(device="cuda", layers=(0, 1, 2, 3), S=131072, T=32, decode_steps=256):
-    """Attention-only stack, 32/8 heads, d128, bf16: causal prefill of S tokens, k_t = 10 % of the prefix,
-    anchors {0, 1, 4, 12, 20}, hitters drifting 15 % per layer.  Returns a PrefillWorkload holding only
-    the requested layers (layer 0 is the dense-output anchor); K/V are allocated with room for
-    `decode_steps` more tokens so that decode steps can append to the same cache."""
+def iter_config5_layers(device="cuda", n_layers=32, S=131072, decode_steps=256, keep=None):
+    """Yields (layer index, PrefillLayer or None) for layers 0..n_layers-1 of the config-5 stack, one at a
+    time (a 131072-token layer is 1.6 GB): hitters drift 15 % per layer; None for layers not in `keep`
+    (their random draws are still consumed, so a layer's tensors do not depend on which others are kept).
+    K/V have room for `decode_steps` more tokens."""
     device = torch.device(device)
     Hq, Hkv, d = 32, 8, 128
     G = Hq // Hkv
-    wl = PrefillWorkload(f"cfg5-prefill-bf16-S{S}-T{T}", S, Hq, Hkv, d, torch.bfloat16, T, prefill_budgets(S, T, 100, 0))
     prev = [None] * Hkv
-    for layer in range(max(layers) + 1):
+    for layer in range(n_layers):
         gen = torch.Generator(device=device)
         gen.manual_seed(layer_seed(BASE_SEED, 5, layer))
-        keep = layer in layers
         pos_all = []
         us = []
         for hk in range(Hkv):
             us.append(_unit(gen, d, device))
             prev[hk] = _next_hitters(gen, prev[hk], S, 64, 0.85, device)
             pos_all.append(prev[hk])
-        if not keep:
+        if keep is not None and layer not in keep:
+            yield layer, None
             continue
         q = torch.randn(S, Hq, d, generator=gen, device=device, dtype=torch.float32)
         k = torch.zeros(Hkv, S + decode_steps, d, device=device, dtype=torch.bfloat16)
@@ -271,7 +270,18 @@ def config5_prefill(device="cuda", layers=(0, 1, 2, 3), S=131072, T=32, decode_s
             k[hk, :S] = kh.to(torch.bfloat16)
             v[hk, :S] = torch.randn(S, d, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
             q[:, hk * G:(hk + 1) * G] += us[hk]
-        wl.layers.append(PrefillLayer(q.to(torch.bfloat16), k, v))
+        yield layer, PrefillLayer(q.to(torch.bfloat16), k, v)
+
+
+def config5_prefill(device="cuda", layers=(0, 1, 2, 3), S=131072, T=32, decode_steps=256):
+    """Attention-only stack, 32/8 heads, d128, bf16: causal prefill of S tokens, k_t = 10 % of the prefix,
+    anchors {0, 1, 4, 12, 20}, hitters drifting 15 % per layer.  Returns a PrefillWorkload holding only
+    the requested layers (layer 0 is the dense-output anchor); K/V are allocated with room for
+    `decode_steps` more tokens so that decode steps can append to the same cache."""
+    wl = PrefillWorkload(f"cfg5-prefill-bf16-S{S}-T{T}", S, 32, 8, 128, torch.bfloat16, T, prefill_budgets(S, T, 100, 0))
+    for _, layer in iter_config5_layers(device, max(layers) + 1, S, decode_steps, keep=set(layers)):
+        if layer is not None:
+            wl.layers.append(layer)
     return wl
 
 
