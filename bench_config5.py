@@ -79,31 +79,57 @@ def main():
     q0 = torch.empty(1, Hq, d, dtype=torch.bfloat16, device=dev)
     ddesc = binding.decode_desc(q0, caches[0][0].unsqueeze(0))
     dws = torch.empty(binding.kascade_workspace_bytes(binding.OP_DECODE_ANCHOR, ddesc, Lmax, kmax), dtype=torch.uint8, device=dev)
-    # all of a step's random rows are drawn before the step is timed
-    step_ms = []
-    for step in range(steps):
-        L = S + step + 1
-        k_b = workloads.budget(L, 100)
-        sl = torch.tensor([L], dtype=torch.int32, device=dev)
-        kp = torch.tensor([k_b], dtype=torch.int32, device=dev)
-        qs = torch.randn(NL, 1, Hq, d, generator=gen, device=dev).to(torch.bfloat16)
-        rows = torch.randn(NL, 2, Hkv, d, generator=gen, device=dev).to(torch.bfloat16)
-        for layer, (kc, vc) in enumerate(caches):
-            kc[:, L - 1] = rows[layer, 0]
-            vc[:, L - 1] = rows[layer, 1]
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
+    # all of a step's random rows are drawn before the step is timed; lengths and budgets live in device
+    # tensors, the host arguments (max_seqlen, k_max) are the same for every step - so the step's launches
+    # can also be captured once into a HIP graph and replayed
+    sl = torch.zeros(1, dtype=torch.int32, device=dev)
+    kp = torch.zeros(1, dtype=torch.int32, device=dev)
+    qs = torch.zeros(NL, 1, Hq, d, dtype=torch.bfloat16, device=dev)
+
+    def decode_step():
         for layer, (kc, vc) in enumerate(caches):
             kb, vb = kc.unsqueeze(0), vc.unsqueeze(0)
             if layer in anchors:
                 mode = binding.KASCADE_OUT_DENSE if layer == 0 else binding.KASCADE_OUT_SPARSE
-                binding.kascade_decode_anchor(qs[layer], kb, vb, sl, kp, L, kmax, 0, mode, didx, dout, dws)
+                binding.kascade_decode_anchor(qs[layer], kb, vb, sl, kp, Lmax, kmax, 0, mode, didx, dout, dws)
             else:
                 binding.kascade_decode_reuse(qs[layer], kb, vb, sl, kp, kmax, didx, None, dout, dws)
-        e1.record()
-        e1.synchronize()
-        step_ms.append(e0.elapsed_time(e1))
+
+    def run_steps(launch):
+        times = []
+        for step in range(steps):
+            L = S + step + 1
+            sl.fill_(L)
+            kp.fill_(workloads.budget(L, 100))
+            qs.copy_(torch.randn(NL, 1, Hq, d, generator=gen, device=dev))
+            rows = torch.randn(NL, 2, Hkv, d, generator=gen, device=dev).to(torch.bfloat16)
+            for layer, (kc, vc) in enumerate(caches):
+                kc[:, L - 1] = rows[layer, 0]
+                vc[:, L - 1] = rows[layer, 1]
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            launch()
+            e1.record()
+            e1.synchronize()
+            times.append(e0.elapsed_time(e1))
+        return times
+
+    step_ms = run_steps(decode_step)
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            decode_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            decode_step()
+        graph_ms = sorted(run_steps(g.replay))
+    except Exception as exc:
+        print(f"bench_config5.py: graph replay skipped: {exc}", file=sys.stderr)
     step_sorted = sorted(step_ms)
     n_anchor = len(anchors)
     rec = {
@@ -117,6 +143,8 @@ def main():
         "decode_ms_per_step_p10_p50_p90": [round(step_sorted[int(f * (len(step_sorted) - 1))], 4) for f in (0.1, 0.5, 0.9)],
         "decode_tokens_per_s": round(1e3 / step_sorted[len(step_sorted) // 2], 1),
         "decode_us_per_layer": round(step_sorted[len(step_sorted) // 2] * 1e3 / NL, 2),
+        "decode_step_as_hip_graph_ms_p50": round(graph_ms[len(graph_ms) // 2], 4) if graph_ms else None,
+        "decode_tokens_per_s_hip_graph": round(1e3 / graph_ms[len(graph_ms) // 2], 1) if graph_ms else None,
     }
     print(json.dumps(rec), flush=True)
 
