@@ -14,8 +14,6 @@
 // row with one 16-byte load each, so a wave instruction fetches 64/LPR full rows and every
 // fetched byte is used.  Each lane group keeps U rows of K and of V in flight and owns a
 // private online-softmax stream (m, l, acc); streams are merged once per workgroup in LDS.
-#include <stdlib.h>
-
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -702,7 +700,12 @@ hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const Dec
     if (gather && small) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false>), grid, block, 0, st, s, plan, a);
     else if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, true>), grid, block, 0, st, s, plan, a);
     else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true, true>), grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, false, true, true>), grid, block, 0, st, s, plan, a);
+    else {
+        // the K stream without V has registers to spare: 8 rows per batch halve a wave's round trips, which
+        // shortens the tail of the launch (2 % at batch 64; no difference at batch 8)
+        constexpr int US = (D == 128 && G <= 4) ? 8 : 4;
+        hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, false, true, true, US>), grid, block, 0, st, s, plan, a);
+    }
     return hipGetLastError();
 }
 
