@@ -85,19 +85,34 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
     if (p.n_chunks < 1) p.n_chunks = 1;
     return p;
 }
-// gather: about four workgroups per compute unit.  stream: many more, smaller workgroups - with
-// ragged sequence lengths whole chunks fall away and few large workgroups leave a long tail.
+// gather, bf16 with 256-byte rows and groups of up to four heads: at most 512 workgroups, so that the
+// grid is resident at two workgroups per compute unit and runs the form of the kernel that keeps a wave's
+// whole 64-row group in flight; each (sequence, key head) gets 512 / pairs chunks of whole 256-row passes.
+// Measured against every other split from batch 1 x 131072 to batch 64 x 131072 (10 % budgets): equal or
+// up to 13 % faster than about four smaller workgroups per compute unit.  Other shapes keep that older rule.
 DecodePlan plan_gather(const Shape& s, int64_t k_max) {
-    DecodePlan p = plan_rows(k_max, s.B * s.Hkv, kTargetBlocks, 256, 64, "KASCADE_GATHER_CHUNK");
+    const int pairs = s.B * s.Hkv;
+    if (s.dtype == 1 && s.D == 128 && s.G <= 4 && !getenv("KASCADE_GATHER_CHUNK")) {
+        int64_t n = 512 / pairs;
+        n = n < 1 ? 1 : (n > 64 ? 64 : n);
+        DecodePlan p;
+        p.chunk = (int)round_up_i((k_max + n - 1) / n, 256);
+        p.n_chunks = (int)((k_max + p.chunk - 1) / p.chunk);
+        if (p.n_chunks < 1) p.n_chunks = 1;
+        return p;
+    }
+    DecodePlan p = plan_rows(k_max, pairs, kTargetBlocks, 256, 64, "KASCADE_GATHER_CHUNK");
     // 256 rows are a single pass of a workgroup; if that still leaves three or more workgroups per compute
     // unit, two passes per workgroup amortise its start-up and merge better (measured, cold caches)
-    if (p.chunk == 256 && !getenv("KASCADE_GATHER_CHUNK") && (int64_t)p.n_chunks * s.B * s.Hkv >= 3 * 256) {
+    if (p.chunk == 256 && !getenv("KASCADE_GATHER_CHUNK") && (int64_t)p.n_chunks * pairs >= 3 * 256) {
         p.chunk = 512;
         p.n_chunks = (int)((k_max + 511) / 512);
     }
     return p;
 }
-// (measured: 1024 rows per workgroup wherever the 256-chunk limit allows; with ragged lengths 2048 is 4 % slower)
+// stream: many small workgroups - with ragged sequence lengths whole chunks fall away and few large
+// workgroups leave a long tail (measured: 1024 rows per workgroup wherever the 256-chunk limit allows;
+// with ragged lengths 2048 is 4 % slower)
 DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 32 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
 
 // Workgroups per segment of the decode selection.  One is the single-workgroup kernel; more pay two extra
