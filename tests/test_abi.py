@@ -120,3 +120,21 @@ def test_prefill_argument_checks(lib):
     # one key head's rows must stay below 4 GiB: 2^24 tokens of 256 bytes are exactly 4 GiB
     huge = {**bf, "kv_stride": (0, (1 << 24) * 128, 128)}
     assert call_prefill_reuse(lib, make_desc(**huge), 1 << 24, 32) == -2
+
+
+def test_binding_fails_loudly_without_library_or_gpu(tmp_path):
+    """There is no fallback path: a missing library and host tensors are errors, not detours."""
+    import torch
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.load_library(str(tmp_path / "libkascade_missing.so"))
+    q = torch.zeros(1, 8, 64)
+    k = torch.zeros(1, 2, 16, 64)
+    lens = torch.tensor([16], dtype=torch.int32)
+    with pytest.raises(RuntimeError, match="GPU"):
+        binding.kascade_decode_anchor(q, k, k, lens, lens, 16, 16)
+    with pytest.raises(RuntimeError, match="GPU"):
+        binding.kascade_decode_reuse(q, k, k, lens, lens, 16, torch.zeros(1, 2, 16, dtype=torch.int32))
+    with pytest.raises(RuntimeError, match="GPU"):
+        binding.kascade_prefill_reuse(torch.zeros(32, 8, 64), torch.zeros(2, 32, 64), torch.zeros(2, 32, 64), 16,
+                                      torch.zeros(2, dtype=torch.int32), torch.zeros(3, dtype=torch.int64), 0,
+                                      torch.zeros(2, 1, dtype=torch.int32))
