@@ -85,14 +85,15 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
     if (p.n_chunks < 1) p.n_chunks = 1;
     return p;
 }
-// gather, bf16 with 256-byte rows and groups of up to four heads: at most 512 workgroups, so that the
+// gather, bf16 with 256-byte rows: at most 512 workgroups, so that the
 // grid is resident at two workgroups per compute unit and runs the form of the kernel that keeps a wave's
 // whole 64-row group in flight; each (sequence, key head) gets 512 / pairs chunks of whole 256-row passes.
 // Measured against every other split from batch 1 x 131072 to batch 64 x 131072 (10 % budgets): equal or
-// up to 13 % faster than about four smaller workgroups per compute unit.  Other shapes keep that older rule.
+// up to 13 % faster than about four smaller workgroups per compute unit (groups of eight heads: 8-28 %).
+// Other shapes keep that older rule.
 DecodePlan plan_gather(const Shape& s, int64_t k_max) {
     const int pairs = s.B * s.Hkv;
-    if (s.dtype == 1 && s.D == 128 && s.G <= 4 && !getenv("KASCADE_GATHER_CHUNK")) {
+    if (s.dtype == 1 && s.D == 128 && !getenv("KASCADE_GATHER_CHUNK")) {
         int64_t n = 512 / pairs;
         n = n < 1 ? 1 : (n > 64 ? 64 : n);
         DecodePlan p;

@@ -697,6 +697,12 @@ hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const Dec
             return hipGetLastError();
         }
     }
+    if constexpr (D == 128 && G == 8) {   // eight heads leave registers for 8 row pairs per batch, not 16
+        if (gather && wgs <= 2 * 256) {
+            hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false, 8>), grid, block, 0, st, s, plan, a);
+            return hipGetLastError();
+        }
+    }
     if (gather && small) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false>), grid, block, 0, st, s, plan, a);
     else if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, true>), grid, block, 0, st, s, plan, a);
     else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true, true>), grid, block, 0, st, s, plan, a);
