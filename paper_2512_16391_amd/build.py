@@ -8,7 +8,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libkascade.so")
 
-SOURCES = ["api.hip", "decode_kernels.hip", "topk_kernels.hip", "prefill_kernels.hip", "calib_kernels.hip"]
+SOURCES = ["api.hip", "decode_kernels.hip", "decode_mfma_kernels.hip", "topk_kernels.hip", "prefill_kernels.hip", "calib_kernels.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -89,8 +89,8 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
 // grid is resident at two workgroups per compute unit and runs the form of the kernel that keeps a wave's
 // whole 64-row group in flight; each (sequence, key head) gets 512 / pairs chunks of whole 256-row passes.
 // Measured against every other split from batch 1 x 131072 to batch 64 x 131072 (10 % budgets): equal or
-// up to 13 % faster than about four smaller workgroups per compute unit (groups of eight heads: 8-28 %).
-// Other shapes keep that older rule.
+// up to 13 % faster than about four smaller workgroups per compute unit; the matrix-unit kernel that
+// serves groups of eight heads is fastest with the same split.  Other shapes keep that older rule.
 DecodePlan plan_gather(const Shape& s, int64_t k_max) {
     const int pairs = s.B * s.Hkv;
     if (s.dtype == 1 && s.D == 128 && !getenv("KASCADE_GATHER_CHUNK")) {
@@ -233,6 +233,17 @@ PrefillPreWs carve_prefill_presoftmax(const Shape& s, int64_t S, int T, void* ws
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
+
+// Attention over a gathered index list.  The vector-ALU row kernel keeps more bytes in flight (registers
+// instead of LDS tiles) and is the faster one up to four heads per key head; its arithmetic grows with the
+// group, and from eight heads on the matrix-unit kernel, whose cost does not depend on the group, wins
+// (batch 8 x 32768, eight heads: 39 -> 29 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
+    bool mfma = s.G >= 8;
+    if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
+    if (mfma && s.dtype == 1 && s.D == 128 && s.G <= 16) return launch_decode_gather_mfma(s, plan, a, st);
+    return launch_decode_rows(s, plan, a, true, true, false, st);
+}
 
 // ---- optional per-kernel timing (measurement aid, off by default) -----------------
 // When enabled every kernel launch is bracketed by two hipEvents on the call's stream.
@@ -389,7 +400,7 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
     a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens; a.k_per_seq = k_per_seq;
     a.idx = idx_in; a.head_map = head_map; a.k_max = k_max; a.n_src_heads = n_anchor_heads;
     a.part_ml = ws.part_ml; a.part_acc = ws.part_acc; a.out = out;
-    st = timed(K_GATHER, stream, [&] { return launch_decode_rows(s, plan, a, true, true, false, stream); });
+    st = timed(K_GATHER, stream, [&] { return launch_gather(s, plan, a, stream); });
     if (st != KASCADE_OK) return st;
     if (plan.n_chunks > 1)
         st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, plan.n_chunks, ws.part_ml, ws.part_acc, out, stream); });
@@ -485,7 +496,7 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     g.q = q; g.k = k_cache; g.v = v_cache; g.seqlens = seqlens; g.k_per_seq = k_per_seq;
     g.idx = idx_out; g.head_map = shared ? ws.zero_map : nullptr; g.k_max = k_max; g.n_src_heads = shared ? 1 : s.Hkv;
     g.part_ml = ws.gather.part_ml; g.part_acc = ws.gather.part_acc; g.out = out;
-    st = timed(K_GATHER, stream, [&] { return launch_decode_rows(s, gp, g, true, true, false, stream); });
+    st = timed(K_GATHER, stream, [&] { return launch_gather(s, gp, g, stream); });
     if (st != KASCADE_OK) return st;
     if (gp.n_chunks > 1)
         st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, gp.n_chunks, ws.gather.part_ml, ws.gather.part_acc, out, stream); });

@@ -9,6 +9,8 @@
 //  decode_merge_kernel  combines per-chunk (max, sum, acc) triples into the output.
 //  decode_pool_kernel   anchor pass 2: softmax from logits + statistics, mean over the GQA
 //                       group (Sec. 3.4).
+//  (Gather mode for groups of eight heads and more runs on the matrix unit instead:
+//  decode_mfma_kernels.hip.)
 //
 // Data movement: a K or V row is 128..512 bytes.  LPR = row_bytes/16 adjacent lanes read one
 // row with one 16-byte load each, so a wave instruction fetches 64/LPR full rows and every
@@ -694,12 +696,6 @@ hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const Dec
     if constexpr (D == 128 && G <= 4) {
         if (small && wgs <= 2 * 256) {
             hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false, 16>), grid, block, 0, st, s, plan, a);
-            return hipGetLastError();
-        }
-    }
-    if constexpr (D == 128 && G == 8) {   // eight heads leave registers for 8 row pairs per batch, not 16
-        if (gather && wgs <= 2 * 256) {
-            hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false, 8>), grid, block, 0, st, s, plan, a);
             return hipGetLastError();
         }
     }

@@ -1,0 +1,222 @@
+// Decode reuse / anchor pass 4 on the matrix unit (paper Sec. 3.6: attention over the K/V rows named
+// by a Top-k index list), for bf16 caches with 256-byte rows.
+//
+// The vector-ALU row kernels spend arithmetic in proportion to the number of query heads per key
+// head; from four heads up that arithmetic, not HBM, sets their speed.  Here the G query heads of
+// a key head are the columns of one 32-wide MFMA operand (zero padded), so q.k and P.V cost the
+// same for any G <= 32:
+//   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]       (8 x v_mfma_f32_32x32x16_bf16)
+//   O^T[d x 32 heads]      += V^T[d x 32 keys] P^T[32 keys x 32 heads] (8 more)
+// One workgroup = one chunk of a (sequence, key head) index list, as in the row kernels.  Per pass it
+// gathers 128 K rows and 128 V rows into LDS with direct global-to-LDS loads (swizzled on the source
+// side, same tile layouts as the prefill kernels), and each of its four waves attends to 32 of those
+// keys with its own online-softmax state; the four states merge through LDS at the end and leave
+// either the output or this chunk's partial (max, sum, acc) triple for decode_merge_kernel.
+#include "device_utils.h"
+#include "kernels.h"
+#include "mfma_tiles.h"
+
+namespace kascade {
+
+namespace {
+
+using namespace mfma;
+
+constexpr int kMB = 256;              // threads per workgroup
+constexpr int kMW = kMB / kWave;      // waves
+constexpr int kWaveKeys = 32;         // keys per wave and pass
+constexpr int kPassKeys = kMW * kWaveKeys;
+
+__device__ __forceinline__ int mfma_rows_per_chunk(int n_rows, int n_chunks) {
+    const int c = (n_rows + n_chunks - 1) / n_chunks;
+    return (c + 63) & ~63;
+}
+
+template <int D>
+__global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+    constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = kPassKeys * D * 2;
+    constexpr int PPR = D / 8, RPP = kMB / PPR, PASSES = kPassKeys / RPP;
+    __shared__ __align__(16) unsigned char smK[TILE];
+    __shared__ __align__(16) unsigned char smV[TILE];
+    __shared__ int smOk[kPassKeys];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane & 31, h = lane >> 5;
+    const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
+    const int n_chunks = plan.n_chunks, G = s.G;
+
+    const int L = a.seqlens[b];
+    int n_rows = a.k_per_seq[b];
+    n_rows = n_rows < a.k_max ? n_rows : a.k_max;
+    if (L <= 0 || n_rows < 0) n_rows = 0;
+    const int chunk = mfma_rows_per_chunk(n_rows, n_chunks);
+    const int begin = chunk_id * chunk;
+    const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
+    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
+    if (begin >= end) {   // an empty chunk: mark it for the merge (and define the output of an empty set)
+        if ((int)threadIdx.x < G) {
+            float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        if (n_chunks == 1) {
+            for (int e = threadIdx.x; e < G * D; e += kMB) {
+                bf16_t* o = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + e / D) * s.o_stride[2] + e % D;
+                *o = 0;
+            }
+        }
+        return;
+    }
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const uint64_t row_bytes = (uint64_t)s.kv_stride[2] * 2u;
+    int src = a.head_map ? a.head_map[hk] : hk;
+    src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+    const int32_t* idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+
+    // staging role of this thread: 16-byte piece pp of the rows r0, r0 + RPP, ... of a pass; the piece it
+    // fetches is the one the swizzled tile layout wants at that position
+    const int r0 = threadIdx.x / PPR, pp = threadIdx.x % PPR;
+    const uint32_t koff = (uint32_t)((pp ^ ((D == 128) ? (r0 & 15) : ((r0 >> 1) & 7))) << 4);
+    const uint32_t voff = (uint32_t)((pp ^ ((D == 128) ? ((r0 & 3) << 2) : (((r0 >> 1) & 1) << 2))) << 4);
+
+    // query fragments (B operand of S^T = K Q^T): column = head q of the group (zero beyond G)
+    bf16x8_t qf[KSTEPS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + b * s.q_stride[0] + (int64_t)(hk * G + q) * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (q < G) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    const float c = s.scale_log2;
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16_t acc_o[DBLK];
+#pragma unroll
+    for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+    const int key0 = w * kWaveKeys + perm_key(q);
+
+    for (int j0 = begin; j0 < end; j0 += kPassKeys) {
+        // ---- gather this pass's rows into the tiles
+        int rows[PASSES];
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const int j = j0 + i * RPP + r0;
+            int row = j < end ? idx[j] : -1;
+            rows[i] = (row >= 0 && row < L) ? row : -1;
+        }
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const uint64_t off = (uint64_t)(rows[i] < 0 ? 0 : rows[i]) * row_bytes;
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + off + koff), (lds_ptr_t)(smK + (i * kMB + w * kWave) * 16), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, 0);
+            if (pp == 0) smOk[i * RPP + r0] = rows[i] >= 0;
+        }
+        wait_vmem();
+        __syncthreads();
+
+        // ---- S^T for this wave's 32 keys, masks for slots without a key
+        f32x16_t s0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s0[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(smK + k_off<D>(key0, kk * 2 + h)), qf[kk], s0, 0, 0, 0);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int slot = w * kWaveKeys + (r >> 3) * 16 + h * 8 + (r & 7);
+            s0[r] = smOk[slot] ? s0[r] * c : -INFINITY;
+            mx = fmaxf(mx, s0[r]);
+        }
+        mx = half_swap_max(mx);
+        // ---- online softmax, base 2; this lane owns head q (the other half-wave holds the other keys)
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {   // wave-uniform: rescale only when a maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+            m_run = m_new;
+        }
+        float rs = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s0[r] = __builtin_amdgcn_exp2f(s0[r] - m_safe);
+            rs += s0[r];
+        }
+        l_run += half_swap_sum(rs);
+        // ---- O^T += V^T P^T
+        const bf16x8_t pf0 = pack_p(s0, 0), pf1 = pack_p(s0, 8);
+#pragma unroll
+        for (int i = 0; i < DBLK; ++i) {
+            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys), pf0, acc_o[i], 0, 0, 0);
+            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys + 16), pf1, acc_o[i], 0, 0, 0);
+        }
+        __syncthreads();   // the tiles are free for the next pass
+    }
+
+    // ---- merge the four waves' states through LDS (the tiles are free), fixed order
+    float* sm_m = reinterpret_cast<float*>(smV);                 // [kMW][32]
+    float* sm_l = sm_m + kMW * 32;                               // [kMW][32]
+    float* sm_acc = reinterpret_cast<float*>(smK);               // [kMW][G][D], at most 4 * 32 * 128 floats = 64 KB > tile: G <= 16 here
+    if (h == 0) { sm_m[w * 32 + q] = m_run; sm_l[w * 32 + q] = l_run; }
+    if (q < G) {
+#pragma unroll
+        for (int i = 0; i < DBLK; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int d = i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                sm_acc[(w * G + q) * D + d] = acc_o[i][r];
+            }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < G * D; e += kMB) {
+        const int g = e / D, col = e % D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kMW; ++t) M = fmaxf(M, sm_m[t * 32 + g]);
+        const float Ms = (M == -INFINITY) ? 0.f : M;
+        float lsum = 0.f, val = 0.f;
+#pragma unroll
+        for (int t = 0; t < kMW; ++t) {
+            const float wgt = __builtin_amdgcn_exp2f(sm_m[t * 32 + g] - Ms);
+            lsum = fmaf(wgt, sm_l[t * 32 + g], lsum);
+            val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
+        }
+        const int hq = hk * G + g;
+        const int64_t pidx = ((int64_t)(b * s.Hq + hq)) * n_chunks + chunk_id;
+        if (n_chunks == 1) {
+            const float o = lsum > 0.f ? val / lsum : 0.f;
+            bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
+            *op = (bf16_t)f32_to_bf16_bits(o);
+        } else {
+            a.part_acc[pidx * D + col] = val;
+        }
+        if (col == 0) {
+            a.part_ml[pidx * 2 + 0] = M;
+            a.part_ml[pidx * 2 + 1] = lsum;
+        }
+    }
+}
+
+}  // namespace
+
+// Gather-mode attention for bf16, head dimension 128, groups of up to 16 heads.
+hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
+    if (s.dtype != 1 || s.D != 128 || s.G > 16) return hipErrorInvalidValue;
+    dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
+    hipLaunchKernelGGL((decode_gather_mfma_kernel<128>), grid, block, 0, st, s, plan, a);
+    return hipGetLastError();
+}
+
+}  // namespace kascade

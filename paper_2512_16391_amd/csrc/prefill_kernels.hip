@@ -26,6 +26,7 @@
 
 #include "device_utils.h"
 #include "kernels.h"
+#include "mfma_tiles.h"
 #include "topk_select.h"
 
 namespace kascade {
@@ -37,75 +38,9 @@ constexpr int kPW = kPB / kWave;  // waves
 constexpr int BK = 64;            // keys per block
 constexpr int kTileRows = 128;
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // one 16-byte piece in flight
-
-// MFMA 32x32x16 output: lane (col = lane%32, half = lane/32), register r holds row
-// (r/4)*8 + half*4 + r%4.  perm_key maps an operand row/col index rho to the key slot that
-// makes register r of half h hold key slot (r/8)*16 + h*8 + r%8, i.e. eight consecutive keys
-// per group of eight registers - the order the P^T operand of the second MFMA needs.
-__device__ __forceinline__ int perm_key(int rho) {
-    const int r = (rho >> 3) * 4 + (rho & 3);
-    const int h = (rho >> 2) & 1;
-    return (r >> 3) * 16 + h * 8 + (r & 7);
-}
-
-// K tile: [BK][D] bf16 row-major, the 16-byte chunks of a row XOR-swizzled by the key index so
-// that the 16 lanes served together by one LDS read (16 different keys, same chunk) fall into 16
-// different 16-byte slots of the 256-byte bank window (64 banks x 4 bytes).
-template <int D>
-__device__ __forceinline__ int k_off(int key, int chunk) {
-    const int f = (D == 128) ? (key & 15) : ((key >> 1) & 7);   // D = 64: two rows share a window
-    return key * (D * 2) + ((chunk ^ f) << 4);
-}
-// V tile: [BK][D] bf16 row-major like K.  The MFMA needs V^T fragments (for one d, eight
-// consecutive keys); ds_read_b64_tr_b16 delivers them from the row-major tile: within each group
-// of 16 lanes, lane j points at four consecutive elements of one row, and lane i receives element
-// i%4 of the segments named by lanes i/4, i/4+4, i/4+8, i/4+12.  The 64-byte groups of a row are
-// XOR-swizzled by key%4 so that the four rows one read touches fall into different banks.
-template <int D>
-__device__ __forceinline__ int v_off(int key, int d) {
-    const int f = (D == 128) ? ((key & 3) << 2) : (((key >> 1) & 1) << 2);
-    return key * (D * 2) + ((((d >> 3) ^ f)) << 4) + ((d & 7) << 1);
-}
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-// V^T fragment for MFMA row (lane%32) = d index dblk*32 + lane%32, keys key0 + (lane/32)*8 + 0..7
-template <int D>
-__device__ __forceinline__ bf16x8_t vt_frag(const unsigned char* smV, int dblk, int key0) {
-    const int lane = threadIdx.x & 63;
-    const int g = lane >> 4, a = lane & 3, e = (lane >> 2) & 3;
-    const int key = key0 + (g >> 1) * 8 + e;
-    const int d0 = dblk * 32 + (g & 1) * 16 + 4 * a;
-    typedef s16x4_t __attribute__((address_space(3))) * lds_v4;
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smV + v_off<D>(key, d0)));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(smV + v_off<D>(key + 4, d0)));
-    struct { s16x4_t lo, hi; } both = {lo, hi};
-    return __builtin_bit_cast(bf16x8_t, both);
-}
-
-// max / sum across the two half-waves (lanes i and i+32) on the vector ALU: v_permlane32_swap
-// exchanges the upper half of its first operand with the lower half of the second
-__device__ __forceinline__ float half_swap_max(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float half_swap_sum(float x) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-__device__ __forceinline__ bf16x8_t lds_frag(const unsigned char* p) {
-    return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(p));
-}
-
-__device__ __forceinline__ bf16x8_t pack_p(const f32x16_t& s, int base) {
-    bf16x8_t r;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (__bf16)s[base + e];
-    return r;
-}
+using namespace mfma;
 
 struct RowMap {   // which (token, head) a tile row is
     int token, head;
@@ -124,8 +59,6 @@ __device__ __forceinline__ RowMap map_row(int rho, int t, int T, int hk, int G, 
 // side is linear in the thread index and the XOR swizzle is applied on the source side: the
 // thread that fills chunk position pp of a row fetches logical chunk pp ^ f(row).  The resulting
 // LDS image is the one k_off<D> addresses.  No staging registers, no LDS write instructions.
-typedef __attribute__((address_space(1))) const void* gmem_ptr_t;
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 template <int D> struct Dma {
     static constexpr int PPR = D / 8, RPP = kPB / PPR, PASSES = BK / RPP;
@@ -160,7 +93,6 @@ __device__ __forceinline__ void dma_rows_seq(unsigned char* tile, const unsigned
     }
 }
 
-__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only
 
 // Flash-style attention over a key list with both tiles (K, and V when an output is wanted) double
 // buffered in LDS and filled by direct loads: block kb+1 streams in while block kb is multiplied,

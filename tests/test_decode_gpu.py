@@ -459,3 +459,51 @@ def test_decode_anchor_degenerate_sequences(dtype, d, Hq, Hkv, variant):
                     sets = [idx_h[b, h, :kb] for h in range(n_sets)]
                     want = ko.sparse_decode(qb, kb_, vb, sets, scale, None if variant != "shared" else [0] * Hkv)
                 assert max_abs(o[b], want) <= TOL_OUT[dtype], f"b{b} L{L} k{kb} mode{mode}"
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 3), (2, 2), (4, 2), (8, 2), (8, 1)])
+def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv):
+    """The gather kernel that runs q.k and P.V on the matrix unit (the default from eight heads per key
+    head on), forced for every group size: ragged batch, one and many chunks, a head map, unordered
+    lists with entries to ignore, an empty sequence; and the same bits as the unforced default where
+    that is the same kernel."""
+    print(f"case decode reuse on the matrix unit G={G} Hkv={Hkv}", flush=True)
+    monkeypatch.setenv("KASCADE_DECODE_MFMA", "1")
+    dtype, d = torch.bfloat16, 128
+    Hq = G * Hkv
+    lens, ks = [9000, 0, 777, 131, 40000], [4100, 0, 777, 5, 2000]
+    B, k_max = len(lens), max(ks)
+    q, k, v = random_case(40 + G, B, Hq, Hkv, d, dtype, lens)
+    rs = np.random.default_rng(41 + G)
+    n_anchor = max(1, Hkv - 1)
+    hm = rs.integers(0, n_anchor, size=Hkv).tolist()
+    idx = torch.full((B, n_anchor, k_max), -1, dtype=torch.int32)
+    sets = []
+    for b in range(B):
+        sb = []
+        for h in range(n_anchor):
+            n_bad = min(ks[b], 2)
+            good = rs.permutation(rs.choice(lens[b], ks[b] - n_bad, replace=False)) if ks[b] - n_bad > 0 else np.zeros(0, np.int64)
+            row = rs.permutation(np.concatenate([good, [-1, lens[b] + 3][:n_bad]]).astype(np.int64))
+            idx[b, h, : ks[b]] = torch.from_numpy(row).int()
+            sb.append(np.asarray(good, dtype=np.int64))
+        sets.append(sb)
+    args = (q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), k_max, idx.to(DEV))
+    out = binding.kascade_decode_reuse(*args, head_map=i32(hm))
+    torch.cuda.synchronize()
+    o = f64(out)
+    assert np.all(o[1] == 0.0)
+    for b in range(B):
+        if lens[b] == 0:
+            continue
+        L = lens[b]
+        ref = ko.sparse_decode(f64(q[b]), f64(k[b, :, :L]), f64(v[b, :, :L]), sets[b], ko.default_scale(d), hm)
+        assert max_abs(o[b], ref) <= TOL_OUT[dtype], f"sequence {b}"
+    out2 = binding.kascade_decode_reuse(*args, head_map=i32(hm))
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    if G >= 8:
+        monkeypatch.delenv("KASCADE_DECODE_MFMA")
+        out3 = binding.kascade_decode_reuse(*args, head_map=i32(hm))
+        torch.cuda.synchronize()
+        assert torch.equal(out, out3)
