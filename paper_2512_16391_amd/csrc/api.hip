@@ -234,15 +234,25 @@ PrefillPreWs carve_prefill_presoftmax(const Shape& s, int64_t S, int T, void* ws
 
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
-// Attention over a gathered index list.  The vector-ALU row kernel keeps more bytes in flight (registers
-// instead of LDS tiles) and is the faster one up to four heads per key head; its arithmetic grows with the
-// group, and from eight heads on the matrix-unit kernel, whose cost does not depend on the group, wins
-// (batch 8 x 32768, eight heads: 39 -> 29 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
-hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
+// Which family runs the decode row passes.  The vector-ALU row kernels keep more bytes in flight (registers
+// instead of LDS tiles) and are equal or faster up to four heads per key head; their arithmetic grows with
+// the group, and from eight heads on the matrix-unit kernels, whose cost does not depend on the group, win
+// (batch 8 x 32768, eight heads: gather 34.5 -> 21.4 us, key sweep 163 -> 112 us, sweep with dense output
+// 388 -> 219 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+bool use_matrix_unit(const Shape& s) {
     bool mfma = s.G >= 8;
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
-    if (mfma && s.dtype == 1 && s.D == 128 && s.G <= 16) return launch_decode_gather_mfma(s, plan, a, st);
+    return mfma && s.dtype == 1 && s.D == 128 && s.G <= 16;
+}
+// Attention over a gathered index list.
+hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
+    if (use_matrix_unit(s)) return launch_decode_gather_mfma(s, plan, a, st);
     return launch_decode_rows(s, plan, a, true, true, false, st);
+}
+// The anchor's sweep over every key (logits stored), with the same choice of kernel.
+hipError_t launch_stream(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st) {
+    if (use_matrix_unit(s)) return launch_decode_stream_mfma(s, plan, a, with_v, st);
+    return launch_decode_rows(s, plan, a, false, with_v, true, st);
 }
 
 // ---- optional per-kernel timing (measurement aid, off by default) -----------------
@@ -439,7 +449,7 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
         // the dense output still needs every head's own query against every key: a pass of its own, whose
         // logits and statistics are overwritten below
         if (dense) {
-            st = timed(K_STREAM_V, stream, [&] { return launch_decode_rows(s, sp, a, false, true, true, stream); });
+            st = timed(K_STREAM_V, stream, [&] { return launch_stream(s, sp, a, true, stream); });
             if (st != KASCADE_OK) return st;
             if (sp.n_chunks > 1) {
                 st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream); });
@@ -454,7 +464,7 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
         a.q = ws.qbar;
     }
     const bool with_v = dense && !presoftmax;
-    st = timed(with_v ? K_STREAM_V : K_STREAM, stream, [&] { return launch_decode_rows(sel, sp, a, false, with_v, true, stream); });
+    st = timed(with_v ? K_STREAM_V : K_STREAM, stream, [&] { return launch_stream(sel, sp, a, with_v, stream); });
     if (st != KASCADE_OK) return st;
     if (with_v && sp.n_chunks > 1) {
         st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, sp.n_chunks, ws.st_ml, ws.st_acc, out, stream); });
@@ -657,7 +667,7 @@ int kascade_prefill_anchor_presoftmax(const kascade_desc* desc, const void* q, c
     DecodeRowsArgs r = {};
     r.q = ws.qbar; r.k = k; r.v = nullptr; r.seqlens = ws.tile_lens;
     r.logits = ws.logits; r.logit_pitch = ws.pitch; r.part_ml = ws.st_ml; r.part_acc = nullptr; r.hist11 = ws.hist11;
-    st = timed(K_STREAM, stream, [&] { return launch_decode_rows(ws.ds, ws.sp, r, false, false, true, stream); });
+    st = timed(K_STREAM, stream, [&] { return launch_stream(ws.ds, ws.sp, r, false, stream); });
     if (st != KASCADE_OK) return st;
     DecodePoolArgs pa = {};
     pa.seqlens = ws.tile_lens; pa.k_per_seq = k_per_tile; pa.k_max = INT_MAX; pa.recent_window = 0;
@@ -712,7 +722,7 @@ int kascade_decode_pooled(const kascade_desc* desc, const void* q, const void* k
     a.q = q; a.k = k_cache; a.v = nullptr; a.seqlens = seqlens;
     a.logits = ws.logits; a.logit_pitch = ws.pitch;
     a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = nullptr; a.hist11 = ws.hist11;
-    st = timed(K_STREAM, stream, [&] { return launch_decode_rows(s, sp, a, false, false, true, stream); });
+    st = timed(K_STREAM, stream, [&] { return launch_stream(s, sp, a, false, stream); });
     if (st != KASCADE_OK) return st;
     DecodePoolArgs pa = {};
     pa.seqlens = seqlens; pa.k_per_seq = seqlens; pa.k_max = max_seqlen; pa.recent_window = 0;

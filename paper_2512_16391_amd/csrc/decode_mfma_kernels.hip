@@ -1,5 +1,7 @@
-// Decode reuse / anchor pass 4 on the matrix unit (paper Sec. 3.6: attention over the K/V rows named
-// by a Top-k index list), for bf16 caches with 256-byte rows.
+// The decode row passes on the matrix unit, for bf16 caches with 256-byte rows: attention over the
+// K/V rows named by a Top-k index list (paper Sec. 3.6, reuse layers and anchor pass 4) and the
+// anchor's sweep over every key (Sec. 3.6 pass 1: logits and softmax statistics, with P.V when the
+// layer's output is dense).
 //
 // The vector-ALU row kernels spend arithmetic in proportion to the number of query heads per key
 // head; from four heads up that arithmetic, not HBM, sets their speed.  Here the G query heads of
@@ -7,8 +9,8 @@
 // same for any G <= 32:
 //   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]       (8 x v_mfma_f32_32x32x16_bf16)
 //   O^T[d x 32 heads]      += V^T[d x 32 keys] P^T[32 keys x 32 heads] (8 more)
-// One workgroup = one chunk of a (sequence, key head) index list, as in the row kernels.  Per pass it
-// gathers 128 K rows and 128 V rows into LDS with direct global-to-LDS loads (swizzled on the source
+// One workgroup = one chunk of a (sequence, key head) row list, as in the row kernels.  Per pass it
+// brings 128 K rows (and 128 V rows) into LDS with direct global-to-LDS loads (swizzled on the source
 // side, same tile layouts as the prefill kernels), and each of its four waves attends to 32 of those
 // keys with its own online-softmax state; the four states merge through LDS at the end and leave
 // either the output or this chunk's partial (max, sum, acc) triple for decode_merge_kernel.
@@ -32,13 +34,19 @@ __device__ __forceinline__ int mfma_rows_per_chunk(int n_rows, int n_chunks) {
     return (c + 63) & ~63;
 }
 
-template <int D>
-__global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+// GATHER: rows from the index list, split evenly over the chunks; otherwise rows begin .. end of a
+// fixed-length chunk.  STORE: the base-2 scaled logits go to a.logits (stream mode).
+template <int D, bool GATHER, bool WITH_V, bool STORE>
+__global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = kPassKeys * D * 2;
     constexpr int PPR = D / 8, RPP = kMB / PPR, PASSES = kPassKeys / RPP;
     __shared__ __align__(16) unsigned char smK[TILE];
-    __shared__ __align__(16) unsigned char smV[TILE];
+    __shared__ __align__(16) unsigned char smV[WITH_V ? TILE : 2 * kMW * 32 * 4];
     __shared__ int smOk[kPassKeys];
+    // cache policy of the direct loads (the instruction's nt bit = 2): gathered rows are touched once per call
+    // and should not displace what the neighbouring kernels keep in L2 (batch 64 x 32768: 158 -> 136 us); for
+    // the sweep over every key it makes no difference to the sweep and slows the pooling pass that follows
+    constexpr int kPolicy = GATHER ? 2 : 0;
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -47,10 +55,18 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
     const int n_chunks = plan.n_chunks, G = s.G;
 
     const int L = a.seqlens[b];
-    int n_rows = a.k_per_seq[b];
-    n_rows = n_rows < a.k_max ? n_rows : a.k_max;
-    if (L <= 0 || n_rows < 0) n_rows = 0;
-    const int chunk = mfma_rows_per_chunk(n_rows, n_chunks);
+    int n_rows = L < 0 ? 0 : L;
+    if constexpr (GATHER) {
+        n_rows = a.k_per_seq[b];
+        n_rows = n_rows < a.k_max ? n_rows : a.k_max;
+        if (L <= 0 || n_rows < 0) n_rows = 0;
+    } else {
+        if (chunk_id == 0 && a.hist11) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
+            uint32_t* hg = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
+            for (int i = threadIdx.x; i < 2048; i += kMB) hg[i] = 0u;
+        }
+    }
+    const int chunk = GATHER ? mfma_rows_per_chunk(n_rows, n_chunks) : plan.chunk;
     const int begin = chunk_id * chunk;
     const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
     const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
@@ -60,7 +76,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
             ml[0] = -INFINITY;
             ml[1] = 0.f;
         }
-        if (n_chunks == 1) {
+        if (WITH_V && n_chunks == 1) {
             for (int e = threadIdx.x; e < G * D; e += kMB) {
                 bf16_t* o = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + e / D) * s.o_stride[2] + e % D;
                 *o = 0;
@@ -72,9 +88,12 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
     const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
     const uint64_t row_bytes = (uint64_t)s.kv_stride[2] * 2u;
-    int src = a.head_map ? a.head_map[hk] : hk;
-    src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
-    const int32_t* idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+    const int32_t* idx = nullptr;
+    if constexpr (GATHER) {
+        int src = a.head_map ? a.head_map[hk] : hk;
+        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+        idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+    }
 
     // staging role of this thread: 16-byte piece pp of the rows r0, r0 + RPP, ... of a pass; the piece it
     // fetches is the one the swizzled tile layout wants at that position
@@ -95,27 +114,32 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
     }
     const float c = s.scale_log2;
     float m_run = -INFINITY, l_run = 0.f;
-    f32x16_t acc_o[DBLK];
+    f32x16_t acc_o[WITH_V ? DBLK : 1];
 #pragma unroll
-    for (int i = 0; i < DBLK; ++i)
+    for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
     const int key0 = w * kWaveKeys + perm_key(q);
 
     for (int j0 = begin; j0 < end; j0 += kPassKeys) {
-        // ---- gather this pass's rows into the tiles
+        // ---- bring this pass's rows into the tiles
         int rows[PASSES];
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
             const int j = j0 + i * RPP + r0;
-            int row = j < end ? idx[j] : -1;
-            rows[i] = (row >= 0 && row < L) ? row : -1;
+            if constexpr (GATHER) {
+                int row = j < end ? idx[j] : -1;
+                rows[i] = (row >= 0 && row < L) ? row : -1;
+            } else {
+                rows[i] = j < end ? j : -1;
+            }
         }
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
             const uint64_t off = (uint64_t)(rows[i] < 0 ? 0 : rows[i]) * row_bytes;
-            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + off + koff), (lds_ptr_t)(smK + (i * kMB + w * kWave) * 16), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + off + koff), (lds_ptr_t)(smK + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
+            if constexpr (WITH_V)
+                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
             if (pp == 0) smOk[i * RPP + r0] = rows[i] >= 0;
         }
         wait_vmem();
@@ -135,6 +159,23 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
             s0[r] = smOk[slot] ? s0[r] * c : -INFINITY;
             mx = fmaxf(mx, s0[r]);
         }
+        if constexpr (STORE) {   // a lane holds two runs of eight consecutive keys of its head
+            if (q < G) {
+                float* lg = a.logits + ((int64_t)b * s.Hq + hk * G + q) * a.logit_pitch;
+#pragma unroll
+                for (int r8 = 0; r8 < 16; r8 += 8) {
+                    const int j = j0 + w * kWaveKeys + (r8 >> 3) * 16 + h * 8;
+                    if (j + 8 <= end) {
+                        *reinterpret_cast<float4*>(lg + j) = make_float4(s0[r8], s0[r8 + 1], s0[r8 + 2], s0[r8 + 3]);
+                        *reinterpret_cast<float4*>(lg + j + 4) = make_float4(s0[r8 + 4], s0[r8 + 5], s0[r8 + 6], s0[r8 + 7]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (j + e < end) lg[j + e] = s0[r8 + e];
+                    }
+                }
+            }
+        }
         mx = half_swap_max(mx);
         // ---- online softmax, base 2; this lane owns head q (the other half-wave holds the other keys)
         const float m_new = fmaxf(m_run, mx);
@@ -142,10 +183,12 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
         if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {   // wave-uniform: rescale only when a maximum moved
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
             l_run *= alpha;
+            if constexpr (WITH_V) {
 #pragma unroll
-            for (int i = 0; i < DBLK; ++i)
+                for (int i = 0; i < DBLK; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+                    for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+            }
             m_run = m_new;
         }
         float rs = 0.f;
@@ -155,12 +198,13 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
             rs += s0[r];
         }
         l_run += half_swap_sum(rs);
-        // ---- O^T += V^T P^T
-        const bf16x8_t pf0 = pack_p(s0, 0), pf1 = pack_p(s0, 8);
+        if constexpr (WITH_V) {   // ---- O^T += V^T P^T
+            const bf16x8_t pf0 = pack_p(s0, 0), pf1 = pack_p(s0, 8);
 #pragma unroll
-        for (int i = 0; i < DBLK; ++i) {
-            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys), pf0, acc_o[i], 0, 0, 0);
-            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys + 16), pf1, acc_o[i], 0, 0, 0);
+            for (int i = 0; i < DBLK; ++i) {
+                acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys), pf0, acc_o[i], 0, 0, 0);
+                acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys + 16), pf1, acc_o[i], 0, 0, 0);
+            }
         }
         __syncthreads();   // the tiles are free for the next pass
     }
@@ -170,18 +214,20 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
     float* sm_l = sm_m + kMW * 32;                               // [kMW][32]
     float* sm_acc = reinterpret_cast<float*>(smK);               // [kMW][G][D], at most 4 * 32 * 128 floats = 64 KB > tile: G <= 16 here
     if (h == 0) { sm_m[w * 32 + q] = m_run; sm_l[w * 32 + q] = l_run; }
-    if (q < G) {
+    if constexpr (WITH_V) {
+        if (q < G) {
 #pragma unroll
-        for (int i = 0; i < DBLK; ++i)
+            for (int i = 0; i < DBLK; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int d = i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                sm_acc[(w * G + q) * D + d] = acc_o[i][r];
-            }
+                for (int r = 0; r < 16; ++r) {
+                    const int d = i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                    sm_acc[(w * G + q) * D + d] = acc_o[i][r];
+                }
+        }
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < G * D; e += kMB) {
-        const int g = e / D, col = e % D;
+    for (int e = threadIdx.x; e < (WITH_V ? G * D : G); e += kMB) {
+        const int g = WITH_V ? e / D : e, col = WITH_V ? e % D : 0;
         float M = -INFINITY;
 #pragma unroll
         for (int t = 0; t < kMW; ++t) M = fmaxf(M, sm_m[t * 32 + g]);
@@ -191,16 +237,18 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
         for (int t = 0; t < kMW; ++t) {
             const float wgt = __builtin_amdgcn_exp2f(sm_m[t * 32 + g] - Ms);
             lsum = fmaf(wgt, sm_l[t * 32 + g], lsum);
-            val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
+            if constexpr (WITH_V) val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
         }
         const int hq = hk * G + g;
         const int64_t pidx = ((int64_t)(b * s.Hq + hq)) * n_chunks + chunk_id;
-        if (n_chunks == 1) {
-            const float o = lsum > 0.f ? val / lsum : 0.f;
-            bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
-            *op = (bf16_t)f32_to_bf16_bits(o);
-        } else {
-            a.part_acc[pidx * D + col] = val;
+        if constexpr (WITH_V) {
+            if (n_chunks == 1) {
+                const float o = lsum > 0.f ? val / lsum : 0.f;
+                bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
+                *op = (bf16_t)f32_to_bf16_bits(o);
+            } else {
+                a.part_acc[pidx * D + col] = val;
+            }
         }
         if (col == 0) {
             a.part_ml[pidx * 2 + 0] = M;
@@ -215,7 +263,18 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma_kernel(Shape s, Dec
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
     if (s.dtype != 1 || s.D != 128 || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    hipLaunchKernelGGL((decode_gather_mfma_kernel<128>), grid, block, 0, st, s, plan, a);
+    hipLaunchKernelGGL((decode_rows_mfma_kernel<128, true, true, false>), grid, block, 0, st, s, plan, a);
+    return hipGetLastError();
+}
+
+// Stream mode (every row of a sequence, logits stored), same restrictions; the logit rows must be
+// 16-byte aligned (pitch a multiple of 4 floats) and the chunk length a multiple of 8.
+hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st) {
+    if (s.dtype != 1 || s.D != 128 || s.G > 16) return hipErrorInvalidValue;
+    if ((a.logit_pitch & 3) || (reinterpret_cast<uintptr_t>(a.logits) & 15) || (plan.chunk & 7)) return hipErrorInvalidValue;
+    dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
+    if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, true, true>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, false, true>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 

@@ -51,6 +51,9 @@ hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const Deco
 // Gather mode on the matrix unit (bf16, head dimension 128, up to 16 heads per key head): same plan,
 // arguments and partial-result format as launch_decode_rows(gather = true).
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st);
+// Stream mode with stored logits on the matrix unit, same restrictions; same plan, arguments and results as
+// launch_decode_rows(gather = false, store_logits = true).
+hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st);
 
 // Merge the per-chunk partial results into the final output [B, Hq, D].
 hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_ml,

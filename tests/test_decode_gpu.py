@@ -507,3 +507,47 @@ def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv):
         out3 = binding.kascade_decode_reuse(*args, head_map=i32(hm))
         torch.cuda.synchronize()
         assert torch.equal(out, out3)
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (4, 2), (8, 2), (8, 1)])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv, out_mode):
+    """The anchor's sweep over every key on the matrix unit (the default from eight heads per key head
+    on), forced for every group size, with dense and sparse output: ragged lengths that end inside a
+    pass, inside a run of eight logits and after a single key, an empty sequence, several chunks per
+    sequence; and the same bits as the unforced default where that is the same kernel."""
+    print(f"case decode anchor on the matrix unit G={G} Hkv={Hkv} out_mode={out_mode}", flush=True)
+    monkeypatch.setenv("KASCADE_DECODE_MFMA", "1")
+    dtype, d = torch.bfloat16, 128
+    lens = [5000, 0, 1027, 1, 133, 2048]
+    ks = [500, 0, 103, 1, 133, 64]
+    W = 8
+    ks = [max(k_, min(W, L)) for k_, L in zip(ks, lens)]
+    q, k, v = random_case(60 + G, len(lens), G * Hkv, Hkv, d, dtype, lens)
+    live = [b for b in range(len(lens)) if lens[b] > 0]
+    # the oracle has no empty sequences: check those rows by hand, the others against it
+    idx, out = binding.kascade_decode_anchor(q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), max(lens), max(ks),
+                                             recent_window=W, out_mode=out_mode)
+    torch.cuda.synchronize()
+    assert (idx[1] == -1).all() and (out[1] == 0).all()
+    scale = ko.default_scale(d)
+    swaps, worst = 0, 0.0
+    idx_np, o = idx.cpu().numpy(), f64(out)
+    for b in live:
+        L, kb = lens[b], ks[b]
+        qb, kb_, vb = f64(q[b]), f64(k[b, :, :L]), f64(v[b, :, :L])
+        idx_ref, a = ko.decode_anchor_indices(qb, kb_, scale, kb, min(W, kb))
+        for h in range(Hkv):
+            assert (idx_np[b, h, kb:] == -1).all()
+            swaps += check_index_set(idx_np[b, h, :kb], idx_ref[h], a[h], n_forced=min(W, kb), where=f"b{b} h{h}")
+        ref = ko.dense_decode(qb, kb_, vb, scale) if out_mode == binding.KASCADE_OUT_DENSE else \
+            ko.sparse_decode(qb, kb_, vb, [idx_np[b, h, :kb] for h in range(Hkv)], scale)
+        worst = max(worst, max_abs(o[b], ref))
+    print(f"  swaps {swaps}, max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[dtype]
+    if G >= 8:
+        monkeypatch.delenv("KASCADE_DECODE_MFMA")
+        idx2, out2 = binding.kascade_decode_anchor(q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), max(lens),
+                                                   max(ks), recent_window=W, out_mode=out_mode)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx2) and torch.equal(out, out2)
