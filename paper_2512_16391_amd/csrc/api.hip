@@ -38,10 +38,14 @@ int check_desc(const kascade_desc* d, bool prefill) {
     if (prefill && d->batch != 1) return KASCADE_INVALID_ARG;
     // sequences and key heads are grid dimensions y / z of the decode kernels
     if (d->batch > 65535 || d->n_kv_heads > 65535) return KASCADE_UNSUPPORTED;
-    const int G = d->n_q_heads / d->n_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return KASCADE_UNSUPPORTED;
     if (d->head_dim != 64 && d->head_dim != 128) return KASCADE_UNSUPPORTED;
     if (d->dtype != KASCADE_F32 && d->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    // heads per key head: the vector-ALU kernels are built for 1, 2, 4 and 8; the matrix-unit decode kernels
+    // (bf16, head dimension 128) take any group up to 16; prefill workgroups hold 128 / G whole tokens
+    const int G = d->n_q_heads / d->n_kv_heads;
+    const bool pow2 = G == 1 || G == 2 || G == 4 || G == 8;
+    const bool any_group = !prefill && d->dtype == KASCADE_BF16 && d->head_dim == 128 && G <= 16;
+    if (!pow2 && !any_group) return KASCADE_UNSUPPORTED;
     if (!(d->softmax_scale >= 0.f) || isinf(d->softmax_scale)) return KASCADE_INVALID_ARG;
     const int64_t es = d->dtype == KASCADE_F32 ? 4 : 2;
     const int64_t strides[] = {d->q_stride[0], d->q_stride[2], d->kv_stride[0], d->kv_stride[1], d->kv_stride[2],
@@ -240,9 +244,11 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // (batch 8 x 32768, eight heads: gather 34.5 -> 21.4 us, key sweep 163 -> 112 us, sweep with dense output
 // 388 -> 219 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
 bool use_matrix_unit(const Shape& s) {
+    if (s.dtype != 1 || s.D != 128 || s.G > 16) return false;
+    if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
     bool mfma = s.G >= 8;
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
-    return mfma && s.dtype == 1 && s.D == 128 && s.G <= 16;
+    return mfma;
 }
 // Attention over a gathered index list.
 hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {

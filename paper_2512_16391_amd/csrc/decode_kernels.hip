@@ -597,8 +597,10 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(Shape s, int n_chun
 // grid (ceil(max_seqlen/1024), Hkv, B), block 256: four consecutive keys per thread.
 // Writes the pooled scores and counts the Top-k candidates (positions before the forced
 // recent window) by the top 11 value bits of their score.
-template <int G>
+// G = 0: the group size is read from the shape (up to 16 heads per key head).
+template <int G_>
 __global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, DecodePoolArgs a) {
+    const int G = G_ ? G_ : s.G;
     const int b = blockIdx.z, hk = blockIdx.y;
     const int L = a.seqlens[b];
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.seg_info) a.seg_info[((int64_t)b * s.Hkv + hk) * 8] = 0u;
@@ -608,7 +610,7 @@ __global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chun
     k = k > a.k_max ? a.k_max : k;
     const int n_cand = L - (a.recent_window < k ? a.recent_window : k);
     const int j = (blockIdx.x * kBlock + threadIdx.x) * 4;
-    __shared__ float sh_M[G], sh_inv[G];
+    __shared__ float sh_M[G_ ? G_ : 16], sh_inv[G_ ? G_ : 16];
     __shared__ uint32_t lh[2048];
     for (int i = threadIdx.x; i < 2048; i += kBlock) lh[i] = 0u;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -756,7 +758,10 @@ hipError_t launch_decode_pool(const Shape& s, int n_chunks, const DecodePoolArgs
         case 2: hipLaunchKernelGGL((decode_pool_kernel<2>), grid, block, 0, st, s, n_chunks, a); break;
         case 4: hipLaunchKernelGGL((decode_pool_kernel<4>), grid, block, 0, st, s, n_chunks, a); break;
         case 8: hipLaunchKernelGGL((decode_pool_kernel<8>), grid, block, 0, st, s, n_chunks, a); break;
-        default: return hipErrorInvalidValue;
+        default:
+            if (s.G > 16) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((decode_pool_kernel<0>), grid, block, 0, st, s, n_chunks, a);
+            break;
     }
     return hipGetLastError();
 }

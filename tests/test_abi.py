@@ -66,7 +66,10 @@ def test_argument_checks_happen_before_any_launch(lib):
     # the pointers are fake: every call below must return from validation
     assert call_reuse(lib, make_desc(head_dim=96)) == -2
     assert call_reuse(lib, make_desc(dtype=7)) == -2
-    assert call_reuse(lib, make_desc(n_q_heads=6, n_kv_heads=2)) == -2          # G = 3 not built
+    assert call_reuse(lib, make_desc(n_q_heads=6, n_kv_heads=2)) == -2          # G = 3 in fp32 / head_dim 64: not built
+    wide = dict(head_dim=128, dtype=binding.KASCADE_BF16, q_stride=(34 * 128, 0, 128), o_stride=(34 * 128, 0, 128),
+                kv_stride=(2 * 100 * 128, 100 * 128, 128))
+    assert call_reuse(lib, make_desc(n_q_heads=34, n_kv_heads=2, **wide)) == -2    # G = 17: beyond the matrix-unit kernels
     assert call_reuse(lib, make_desc(n_q_heads=7)) == -1
     assert call_reuse(lib, make_desc(batch=0)) == -1
     assert call_reuse(lib, make_desc(), q=0) == -1
@@ -113,6 +116,8 @@ def test_prefill_argument_checks(lib):
     assert call_prefill_reuse(lib, make_desc(**bf), 4096, 16) == -2                       # T * G = 64
     assert call_prefill_reuse(lib, make_desc(**bf), 4096, 48) == -2                       # T * G = 192
     assert call_prefill_reuse(lib, make_desc(**{**bf, "dtype": binding.KASCADE_F32}), 4096, 32) == -2
+    assert call_prefill_reuse(lib, make_desc(**{**bf, "n_q_heads": 24, "q_stride": (0, 24 * 128, 128),
+                                                "o_stride": (0, 24 * 128, 128)}), 4096, 128) == -2   # G = 3: decode only
     assert call_prefill_reuse(lib, make_desc(**{**bf, "batch": 2}), 4096, 32) == -1
     assert call_prefill_reuse(lib, make_desc(**bf), 0, 32) == -1
     assert call_prefill_reuse(lib, make_desc(**bf), 4096, 32, idx=0) == -1

@@ -551,3 +551,63 @@ def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv,
                                                    max(ks), recent_window=W, out_mode=out_mode)
         torch.cuda.synchronize()
         assert torch.equal(idx, idx2) and torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("G,Hkv", [(3, 2), (5, 1), (6, 2), (7, 4), (12, 1), (16, 2)])
+def test_decode_group_sizes_that_are_not_powers_of_two(G, Hkv):
+    """bf16 caches with 128-wide heads take any number of query heads per key head up to 16 (the matrix-unit
+    kernels and the pooling kernel with a run-time group size): anchor layer with both output modes, the
+    shared-set and Pre-Softmax variants, and a reuse layer with a head map, on a ragged batch with an empty
+    sequence."""
+    print(f"case decode G={G} Hkv={Hkv}", flush=True)
+    dtype, d = torch.bfloat16, 128
+    lens, ks, W = [4100, 0, 700, 9], [410, 0, 70, 9], 4
+    B, Hq = len(lens), G * Hkv
+    q, k, v = random_case(70 + G, B, Hq, Hkv, d, dtype, lens)
+    scale = ko.default_scale(d)
+    args = (q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), max(lens), max(ks))
+    for variant in ("per_head", "shared", "presoftmax"):
+        call = {"per_head": binding.kascade_decode_anchor, "shared": binding.kascade_decode_anchor_shared,
+                "presoftmax": binding.kascade_decode_anchor_presoftmax}[variant]
+        n_sets = 1 if variant == "shared" else Hkv
+        for mode in (binding.KASCADE_OUT_SPARSE, binding.KASCADE_OUT_DENSE):
+            idx, out = call(*args, recent_window=W, out_mode=mode)
+            torch.cuda.synchronize()
+            idx_h, o = idx.cpu().numpy(), f64(out)
+            assert (idx_h[1] == -1).all() and np.all(o[1] == 0.0)
+            swaps = 0
+            for b, (L, kb) in enumerate(zip(lens, ks)):
+                if L == 0:
+                    continue
+                qb, kb_, vb = f64(q[b]), f64(k[b, :, :L]), f64(v[b, :, :L])
+                if variant == "per_head":
+                    ref_idx, a = ko.decode_anchor_indices(qb, kb_, scale, kb, W)
+                elif variant == "presoftmax":
+                    ref_idx, a = ko.decode_presoftmax_indices(qb, kb_, scale, kb, "bf16", W)
+                else:
+                    ri, aa = ko.decode_shared_indices(qb, kb_, scale, kb, W)
+                    ref_idx, a = ri[None], aa[None]
+                for h in range(n_sets):
+                    assert (idx_h[b, h, kb:] == -1).all()
+                    swaps += check_index_set(idx_h[b, h, :kb], ref_idx[h], a[h], n_forced=W, where=f"{variant} b{b} h{h}")
+                if mode == binding.KASCADE_OUT_DENSE:
+                    want = ko.dense_decode(qb, kb_, vb, scale)
+                else:
+                    sets = [idx_h[b, h, :kb] for h in range(n_sets)]
+                    want = ko.sparse_decode(qb, kb_, vb, sets, scale, None if variant != "shared" else [0] * Hkv)
+                assert max_abs(o[b], want) <= TOL_OUT[dtype], f"{variant} b{b} mode{mode}"
+            print(f"  {variant} mode {mode}: swaps {swaps}", flush=True)
+    # a reuse layer over the per-head sets of another layer, heads mapped
+    idx, _ = binding.kascade_decode_anchor(*args, recent_window=W, out_mode=binding.KASCADE_OUT_SPARSE)
+    q2, k2, v2 = random_case(170 + G, B, Hq, Hkv, d, dtype, lens)
+    hm = [(h + 1) % Hkv for h in range(Hkv)]
+    out = binding.kascade_decode_reuse(q2.to(DEV), k2.to(DEV), v2.to(DEV), i32(lens), i32(ks), max(ks), idx, head_map=i32(hm))
+    torch.cuda.synchronize()
+    idx_h, o = idx.cpu().numpy(), f64(out)
+    for b, (L, kb) in enumerate(zip(lens, ks)):
+        if L == 0:
+            assert np.all(o[b] == 0.0)
+            continue
+        sets = [idx_h[b, h, :kb] for h in range(Hkv)]
+        want = ko.sparse_decode(f64(q2[b]), f64(k2[b, :, :L]), f64(v2[b, :, :L]), sets, scale, hm)
+        assert max_abs(o[b], want) <= TOL_OUT[dtype], f"reuse b{b}"
