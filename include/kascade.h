@@ -63,8 +63,8 @@ enum {
 typedef struct {
     int32_t batch;          /* sequences (decode), at most 65535; must be 1 for prefill  */
     int32_t n_q_heads;      /* Hq                                                        */
-    int32_t n_kv_heads;     /* Hkv, divides Hq; G = Hq/Hkv in {1,2,4,8}; decode with     *
-                             * bf16 and head_dim 128: any G <= 16                         */
+    int32_t n_kv_heads;     /* Hkv, divides Hq; G = Hq/Hkv in {1,2,4,8}; bf16 decode:    *
+                             * any G <= 16                                                */
     int32_t head_dim;       /* d in {64, 128}                                            */
     int32_t dtype;          /* KASCADE_F32 or KASCADE_BF16; Q, K, V, O share it          */
     float   softmax_scale;  /* 0 -> 1/sqrt(head_dim) (Eq. 1)                             */

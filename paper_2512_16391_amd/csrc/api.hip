@@ -41,10 +41,10 @@ int check_desc(const kascade_desc* d, bool prefill) {
     if (d->head_dim != 64 && d->head_dim != 128) return KASCADE_UNSUPPORTED;
     if (d->dtype != KASCADE_F32 && d->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
     // heads per key head: the vector-ALU kernels are built for 1, 2, 4 and 8; the matrix-unit decode kernels
-    // (bf16, head dimension 128) take any group up to 16; prefill workgroups hold 128 / G whole tokens
+    // (bf16) take any group up to 16; prefill workgroups hold 128 / G whole tokens
     const int G = d->n_q_heads / d->n_kv_heads;
     const bool pow2 = G == 1 || G == 2 || G == 4 || G == 8;
-    const bool any_group = !prefill && d->dtype == KASCADE_BF16 && d->head_dim == 128 && G <= 16;
+    const bool any_group = !prefill && d->dtype == KASCADE_BF16 && G <= 16;
     if (!pow2 && !any_group) return KASCADE_UNSUPPORTED;
     if (!(d->softmax_scale >= 0.f) || isinf(d->softmax_scale)) return KASCADE_INVALID_ARG;
     const int64_t es = d->dtype == KASCADE_F32 ? 4 : 2;
@@ -242,9 +242,9 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // instead of LDS tiles) and are equal or faster up to four heads per key head; their arithmetic grows with
 // the group, and from eight heads on the matrix-unit kernels, whose cost does not depend on the group, win
 // (batch 8 x 32768, eight heads: gather 34.5 -> 21.4 us, key sweep 163 -> 112 us, sweep with dense output
-// 388 -> 219 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+// 388 -> 219 us; 64-wide heads: 20.4 -> 12.9, 83 -> 63, 215 -> 122 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
 bool use_matrix_unit(const Shape& s) {
-    if (s.dtype != 1 || s.D != 128 || s.G > 16) return false;
+    if (s.dtype != 1 || s.G > 16) return false;
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
     bool mfma = s.G >= 8;
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
@@ -373,7 +373,7 @@ const char* kascade_status_string(int32_t status) {
 
 size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max_seqlen, int64_t k_or_idx_total,
                                int32_t q_tile_tokens) {
-    const bool prefill = op == KASCADE_OP_PREFILL_ANCHOR || op == KASCADE_OP_PREFILL_REUSE;
+    const bool prefill = op == KASCADE_OP_PREFILL_ANCHOR || op == KASCADE_OP_PREFILL_REUSE || op == KASCADE_OP_PREFILL_ANCHOR_PRESOFTMAX;
     if (check_desc(desc, prefill) != KASCADE_OK || max_seqlen <= 0 || k_or_idx_total < 0) return 0;
     const Shape s = make_shape(desc);
     switch (op) {

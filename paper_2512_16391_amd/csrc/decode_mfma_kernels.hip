@@ -1,4 +1,4 @@
-// The decode row passes on the matrix unit, for bf16 caches with 256-byte rows: attention over the
+// The decode row passes on the matrix unit, for bf16 caches (head dimension 64 or 128): attention over the
 // K/V rows named by a Top-k index list (paper Sec. 3.6, reuse layers and anchor pass 4) and the
 // anchor's sweep over every key (Sec. 3.6 pass 1: logits and softmax statistics, with P.V when the
 // layer's output is dense).
@@ -259,22 +259,28 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
 
 }  // namespace
 
-// Gather-mode attention for bf16, head dimension 128, groups of up to 16 heads.
+// Gather-mode attention for bf16, groups of up to 16 heads.
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
-    if (s.dtype != 1 || s.D != 128 || s.G > 16) return hipErrorInvalidValue;
+    if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    hipLaunchKernelGGL((decode_rows_mfma_kernel<128, true, true, false>), grid, block, 0, st, s, plan, a);
+    if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, true, true, false>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, true, true, false>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 
 // Stream mode (every row of a sequence, logits stored), same restrictions; the logit rows must be
 // 16-byte aligned (pitch a multiple of 4 floats) and the chunk length a multiple of 8.
 hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st) {
-    if (s.dtype != 1 || s.D != 128 || s.G > 16) return hipErrorInvalidValue;
+    if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     if ((a.logit_pitch & 3) || (reinterpret_cast<uintptr_t>(a.logits) & 15) || (plan.chunk & 7)) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, true, true>), grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, false, true>), grid, block, 0, st, s, plan, a);
+    if (s.D == 128) {
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, true, true>), grid, block, 0, st, s, plan, a);
+        else hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, false, true>), grid, block, 0, st, s, plan, a);
+    } else {
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, true, true>), grid, block, 0, st, s, plan, a);
+        else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, false, true>), grid, block, 0, st, s, plan, a);
+    }
     return hipGetLastError();
 }
 

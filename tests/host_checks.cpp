@@ -113,8 +113,13 @@ int main() {
                     1024, nullptr) == KASCADE_WORKSPACE_TOO_SMALL);
     }
     kascade_desc bad = good;
-    bad.n_q_heads = 6; EXPECT(kascade_workspace_bytes(KASCADE_OP_DECODE_ANCHOR, &bad, 100, 10, 0) == 0);
-    bad = good; bad.n_q_heads = 32; bad.n_kv_heads = 2;   // G = 16
+    bad.n_q_heads = 6; bad.dtype = KASCADE_F32;           // G = 3 exists for bf16 only
+    EXPECT(kascade_workspace_bytes(KASCADE_OP_DECODE_ANCHOR, &bad, 100, 10, 0) == 0);
+    bad = good; bad.n_q_heads = 6;
+    EXPECT(kascade_workspace_bytes(KASCADE_OP_DECODE_ANCHOR, &bad, 100, 10, 0) > 0);
+    EXPECT(kascade_workspace_bytes(KASCADE_OP_PREFILL_ANCHOR, &bad, 4096, 1000, 128) == 0);   // and for decode only
+    EXPECT(kascade_workspace_bytes(KASCADE_OP_PREFILL_ANCHOR_PRESOFTMAX, &bad, 4096, 1000, 128) == 0);
+    bad = good; bad.n_q_heads = 34; bad.n_kv_heads = 2;   // G = 17
     EXPECT(kascade_decode_anchor(&bad, fake, fake, fake, (int32_t*)fake, (int32_t*)fake, 4096, 400, 0, 1, (int32_t*)fake, fake,
                                  fake, (size_t)1 << 40, nullptr) == KASCADE_UNSUPPORTED);
     bad = good; bad.batch = 70000;

@@ -461,15 +461,15 @@ def test_decode_anchor_degenerate_sequences(dtype, d, Hq, Hkv, variant):
                 assert max_abs(o[b], want) <= TOL_OUT[dtype], f"b{b} L{L} k{kb} mode{mode}"
 
 
-@pytest.mark.parametrize("G,Hkv", [(1, 3), (2, 2), (4, 2), (8, 2), (8, 1)])
-def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv):
+@pytest.mark.parametrize("G,Hkv,d", [(1, 3, 128), (2, 2, 128), (4, 2, 128), (8, 2, 128), (8, 1, 128), (2, 2, 64), (8, 2, 64)])
+def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv, d):
     """The gather kernel that runs q.k and P.V on the matrix unit (the default from eight heads per key
     head on), forced for every group size: ragged batch, one and many chunks, a head map, unordered
     lists with entries to ignore, an empty sequence; and the same bits as the unforced default where
     that is the same kernel."""
-    print(f"case decode reuse on the matrix unit G={G} Hkv={Hkv}", flush=True)
+    print(f"case decode reuse on the matrix unit G={G} Hkv={Hkv} d={d}", flush=True)
     monkeypatch.setenv("KASCADE_DECODE_MFMA", "1")
-    dtype, d = torch.bfloat16, 128
+    dtype = torch.bfloat16
     Hq = G * Hkv
     lens, ks = [9000, 0, 777, 131, 40000], [4100, 0, 777, 5, 2000]
     B, k_max = len(lens), max(ks)
@@ -509,16 +509,16 @@ def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv):
         assert torch.equal(out, out3)
 
 
-@pytest.mark.parametrize("G,Hkv", [(1, 2), (2, 2), (4, 2), (8, 2), (8, 1)])
+@pytest.mark.parametrize("G,Hkv,d", [(1, 2, 128), (2, 2, 128), (4, 2, 128), (8, 2, 128), (8, 1, 128), (4, 2, 64), (8, 1, 64)])
 @pytest.mark.parametrize("out_mode", [0, 1])
-def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv, out_mode):
+def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv, d, out_mode):
     """The anchor's sweep over every key on the matrix unit (the default from eight heads per key head
     on), forced for every group size, with dense and sparse output: ragged lengths that end inside a
     pass, inside a run of eight logits and after a single key, an empty sequence, several chunks per
     sequence; and the same bits as the unforced default where that is the same kernel."""
-    print(f"case decode anchor on the matrix unit G={G} Hkv={Hkv} out_mode={out_mode}", flush=True)
+    print(f"case decode anchor on the matrix unit G={G} Hkv={Hkv} d={d} out_mode={out_mode}", flush=True)
     monkeypatch.setenv("KASCADE_DECODE_MFMA", "1")
-    dtype, d = torch.bfloat16, 128
+    dtype = torch.bfloat16
     lens = [5000, 0, 1027, 1, 133, 2048]
     ks = [500, 0, 103, 1, 133, 64]
     W = 8
@@ -553,14 +553,15 @@ def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv,
         assert torch.equal(idx, idx2) and torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("G,Hkv", [(3, 2), (5, 1), (6, 2), (7, 4), (12, 1), (16, 2)])
-def test_decode_group_sizes_that_are_not_powers_of_two(G, Hkv):
-    """bf16 caches with 128-wide heads take any number of query heads per key head up to 16 (the matrix-unit
+@pytest.mark.parametrize("G,Hkv,d", [(3, 2, 128), (5, 1, 128), (6, 2, 128), (7, 4, 128), (12, 1, 128), (16, 2, 128),
+                                     (7, 2, 64), (16, 1, 64)])
+def test_decode_group_sizes_that_are_not_powers_of_two(G, Hkv, d):
+    """bf16 caches take any number of query heads per key head up to 16 (the matrix-unit
     kernels and the pooling kernel with a run-time group size): anchor layer with both output modes, the
     shared-set and Pre-Softmax variants, and a reuse layer with a head map, on a ragged batch with an empty
     sequence."""
-    print(f"case decode G={G} Hkv={Hkv}", flush=True)
-    dtype, d = torch.bfloat16, 128
+    print(f"case decode G={G} Hkv={Hkv} d={d}", flush=True)
+    dtype = torch.bfloat16
     lens, ks, W = [4100, 0, 700, 9], [410, 0, 70, 9], 4
     B, Hq = len(lens), G * Hkv
     q, k, v = random_case(70 + G, B, Hq, Hkv, d, dtype, lens)
