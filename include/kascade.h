@@ -85,7 +85,8 @@ typedef struct {
  *   idx_out  [B,Hkv,k_max] int32, ascending, entries past k_per_seq[b] set to -1
  *   out      [B,Hq,d]: dense attention (Eq. 2) if out_mode = KASCADE_OUT_DENSE, else
  *            attention renormalised over the fresh index set (Sec. 3.1)
- *   max_seqlen  host upper bound of seqlens (sizes the grid and the workspace)
+ *   max_seqlen  host upper bound of seqlens (sizes the grid and the workspace); a sequence whose
+ *               seqlens[b] exceeds it is processed as if it were max_seqlen long
  */
 int kascade_decode_anchor(const kascade_desc* desc, const void* q, const void* k_cache,
                           const void* v_cache, const int32_t* seqlens, const int32_t* k_per_seq,

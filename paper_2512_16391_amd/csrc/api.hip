@@ -446,7 +446,7 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
 
     // pass 1: logits of every key + per-chunk softmax statistics (dense: also P.V)
     DecodeRowsArgs a = {};
-    a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens;
+    a.q = q; a.k = k_cache; a.v = v_cache; a.seqlens = seqlens; a.max_seqlen = max_seqlen;
     a.logits = ws.logits; a.logit_pitch = ws.pitch;
     a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = out; a.hist11 = ws.hist11;
     // the shape passes 1-2 run on: the layer's own, or (Pre-Softmax pooling) one pooled query per key head
@@ -497,11 +497,10 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     Shape ts = s;
     TopkArgs t = {};
     t.scores = ws.pooled; t.hist11 = ws.hist11; t.idx_out = idx_out; t.seqlens = seqlens; t.k_per_seq = k_per_seq;
-    t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window;
+    t.pitch = ws.pitch; t.k_max = k_max; t.recent_window = recent_window; t.max_seqlen = max_seqlen;
     if (shared) { ts.Hkv = 1; t.hist11 = nullptr; t.pitch = (int64_t)s.Hkv * ws.pitch; }
     if (split) {
         t.cand = ws.topk_cand; t.seg_info = ws.topk_seg; t.part_info = ws.topk_part; t.n_parts = ws.topk_parts;
-        t.max_seqlen = max_seqlen;
         st = timed(K_TOPK, stream, [&] { return launch_topk_decode_split(ts, t, stream); });
     } else {
         st = timed(K_TOPK, stream, [&] { return launch_topk_decode(ts, t, stream); });
@@ -509,7 +508,7 @@ static int decode_anchor_impl(const kascade_desc* desc, const void* q, const voi
     if (st != KASCADE_OK || dense) return st;
     // pass 4: attention over the fresh index set
     DecodeRowsArgs g = {};
-    g.q = q; g.k = k_cache; g.v = v_cache; g.seqlens = seqlens; g.k_per_seq = k_per_seq;
+    g.q = q; g.k = k_cache; g.v = v_cache; g.seqlens = seqlens; g.max_seqlen = max_seqlen; g.k_per_seq = k_per_seq;
     g.idx = idx_out; g.head_map = shared ? ws.zero_map : nullptr; g.k_max = k_max; g.n_src_heads = shared ? 1 : s.Hkv;
     g.part_ml = ws.gather.part_ml; g.part_acc = ws.gather.part_acc; g.out = out;
     st = timed(K_GATHER, stream, [&] { return launch_gather(s, gp, g, stream); });
@@ -725,7 +724,7 @@ int kascade_decode_pooled(const kascade_desc* desc, const void* q, const void* k
     if (!aligned16(workspace)) return KASCADE_MISALIGNED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     DecodeRowsArgs a = {};
-    a.q = q; a.k = k_cache; a.v = nullptr; a.seqlens = seqlens;
+    a.q = q; a.k = k_cache; a.v = nullptr; a.seqlens = seqlens; a.max_seqlen = max_seqlen;
     a.logits = ws.logits; a.logit_pitch = ws.pitch;
     a.part_ml = ws.st_ml; a.part_acc = ws.st_acc; a.out = nullptr; a.hist11 = ws.hist11;
     st = timed(K_STREAM, stream, [&] { return launch_stream(s, sp, a, false, stream); });

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kSimBlock) void pool_heads_kernel(float* rows, int6
                                                                int32_t* zero_map) {
     const int b = blockIdx.y;
     if (blockIdx.x == 0 && b == 0 && threadIdx.x < n_heads) zero_map[threadIdx.x] = 0;
-    const int64_t len = lens ? (int64_t)lens[b] : n;
+    const int64_t len = lens ? (int64_t)bounded_len(lens[b], n > 0x7fffffff ? 0 : (int)n) : n;
     const int64_t j = ((int64_t)blockIdx.x * kSimBlock + threadIdx.x) * 4;
     if (j >= len) return;
     float* base = rows + b * batch_pitch + j;

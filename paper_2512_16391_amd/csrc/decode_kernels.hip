@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(Shape s, DecodePlan
     const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
     const int n_chunks = plan.n_chunks;
 
-    const int L = a.seqlens[b];
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
     int n_rows = L;
     if constexpr (GATHER) {
         int kb = a.k_per_seq[b];
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(kBlock, ((PIPE || U > 4) ? 2 : 4)) void decode_rows
     const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
     const int n_chunks = plan.n_chunks;
 
-    const int L = a.seqlens[b];
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
     int n_rows = L;
     if constexpr (GATHER) {
         n_rows = a.k_per_seq[b];
@@ -602,7 +602,7 @@ template <int G_>
 __global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, DecodePoolArgs a) {
     const int G = G_ ? G_ : s.G;
     const int b = blockIdx.z, hk = blockIdx.y;
-    const int L = a.seqlens[b];
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.seg_info) a.seg_info[((int64_t)b * s.Hkv + hk) * 8] = 0u;
     if (blockIdx.x * kBlock * 4 >= L) return;   // uniform per workgroup
     int k = a.k_per_seq[b];

@@ -54,8 +54,8 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
     const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
     const int n_chunks = plan.n_chunks, G = s.G;
 
-    const int L = a.seqlens[b];
-    int n_rows = L < 0 ? 0 : L;
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
+    int n_rows = L;
     if constexpr (GATHER) {
         n_rows = a.k_per_seq[b];
         n_rows = n_rows < a.k_max ? n_rows : a.k_max;

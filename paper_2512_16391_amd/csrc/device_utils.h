@@ -9,6 +9,13 @@ constexpr int kWave = 64;
 
 typedef uint16_t bf16_t;   // storage only; arithmetic is fp32
 
+// A sequence length read from device memory, held to the host-side bound that sized the grid and the
+// buffers (bound <= 0: none): a length beyond it must not become a write beyond them.
+__device__ __forceinline__ int bounded_len(int len, int bound) {
+    len = len < 0 ? 0 : len;
+    return (bound > 0 && len > bound) ? bound : len;
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 

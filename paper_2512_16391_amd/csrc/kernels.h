@@ -31,6 +31,7 @@ struct DecodeRowsArgs {
     const void* k;
     const void* v;
     const int32_t* seqlens;
+    int32_t max_seqlen;           // lengths above this host bound are treated as the bound (it sized the buffers); 0 = none
     const int32_t* k_per_seq;     // gather mode: rows per (b, hk); null in stream mode
     const int32_t* idx;           // gather mode: [B, n_src_heads, k_max]
     const int32_t* head_map;      // gather mode: [Hkv] or null

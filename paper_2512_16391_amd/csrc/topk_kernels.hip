@@ -13,8 +13,7 @@ constexpr int kTopkWaves = kTopkBlock / kWave;
 
 __global__ __launch_bounds__(kTopkBlock) void topk_decode_kernel(Shape s, TopkArgs a) {
     const int hk = blockIdx.x, b = blockIdx.y;
-    int L = a.seqlens[b];
-    L = L < 0 ? 0 : L;
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
     int k = a.k_per_seq[b];
     k = k < 0 ? 0 : (k > L ? L : k);
     k = k > a.k_max ? a.k_max : k;
@@ -74,8 +73,7 @@ struct DecodeSeg {
     int n, k_sel, forced;
 };
 __device__ __forceinline__ DecodeSeg decode_segment(const TopkArgs& a, int b) {
-    int L = a.seqlens[b];
-    L = L < 0 ? 0 : L;
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
     int k = a.k_per_seq[b];
     k = k < 0 ? 0 : (k > L ? L : k);
     k = k > a.k_max ? a.k_max : k;

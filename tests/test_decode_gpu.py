@@ -630,3 +630,25 @@ def test_decode_group_sizes_that_are_not_powers_of_two(G, Hkv, d):
         sets = [idx_h[b, h, :kb] for h in range(Hkv)]
         want = ko.sparse_decode(f64(q2[b]), f64(k2[b, :, :L]), f64(v2[b, :, :L]), sets, scale, hm)
         assert max_abs(o[b], want) <= TOL_OUT[dtype], f"reuse b{b}"
+
+
+@pytest.mark.parametrize("dtype,d,G", [(torch.bfloat16, 128, 4), (torch.bfloat16, 128, 8), (torch.float32, 64, 2)])
+@pytest.mark.parametrize("variant", ["per_head", "shared", "presoftmax"])
+def test_decode_anchor_holds_lengths_to_max_seqlen(dtype, d, G, variant):
+    """max_seqlen sizes the grid and the workspace; a device-side length above it is processed as
+    max_seqlen (same bits as the call with the lengths already cut), never written past the buffers."""
+    print(f"case lengths above max_seqlen dtype={dtype} d={d} G={G} variant={variant}", flush=True)
+    Hkv, max_seqlen = 2, 1500
+    q, k, v = random_case(321, 3, G * Hkv, Hkv, d, dtype, [max_seqlen] * 3)
+    call = {"per_head": binding.kascade_decode_anchor, "shared": binding.kascade_decode_anchor_shared,
+            "presoftmax": binding.kascade_decode_anchor_presoftmax}[variant]
+    ks = [150, 20, 150]
+    for mode in (binding.KASCADE_OUT_SPARSE, binding.KASCADE_OUT_DENSE):
+        res = []
+        for lens in ([max_seqlen + 500, 77, max_seqlen + 1], [max_seqlen, 77, max_seqlen]):
+            idx, out = call(q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), max_seqlen, max(ks), recent_window=4,
+                            out_mode=mode)
+            torch.cuda.synchronize()
+            res.append((idx.clone(), out.clone()))
+        assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+        assert int(res[0][0].max()) < max_seqlen
