@@ -122,6 +122,8 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
  *   (S * kv_stride[2] * 2 bytes), else KASCADE_UNSUPPORTED
  *   k_per_tile  [n_tiles] int32 (device), idx_offsets [n_tiles+1] int64 (device),
  *               idx_offsets[t+1]-idx_offsets[t] = k_per_tile[t], idx_total = idx_offsets[n_tiles]
+ *               (host value; a device-side offset or budget that would reach past idx_total
+ *               entries is cut to what fits)
  *   idx_out  [Hkv, idx_total] int32: tile t of head hk at hk*idx_total + idx_offsets[t]
  *   out [S,Hq,d]: causal dense attention (KASCADE_OUT_DENSE) or sparse attention over the
  *       fresh sets (KASCADE_OUT_SPARSE)

@@ -15,6 +15,21 @@ __device__ __forceinline__ int bounded_len(int len, int bound) {
     len = len < 0 ? 0 : len;
     return (bound > 0 && len > bound) ? bound : len;
 }
+// The same for a prefill tile's budget and its offset into the index arrays (idx_total entries per head):
+// at most `prefix` candidates, and never a slot beyond the arrays.
+struct TileSlot {
+    int k;
+    int64_t off;
+};
+__device__ __forceinline__ TileSlot bounded_tile_slot(int k, int64_t off, int64_t prefix, int64_t idx_total) {
+    TileSlot r;
+    r.off = off < 0 ? 0 : (off > idx_total ? idx_total : off);
+    int64_t kk = k < 0 ? 0 : k;
+    kk = kk > prefix ? prefix : kk;
+    kk = kk > idx_total - r.off ? idx_total - r.off : kk;
+    r.k = (int)kk;
+    return r;
+}
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

@@ -126,13 +126,13 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     int n_sparse = 0, nb_gather = 0, n_blocks;
     const int32_t* idx = nullptr;
     if constexpr (SPARSE) {
-        int kt = a.k_per_tile[t];
-        n_sparse = kt < 0 ? 0 : (kt > prefix ? prefix : kt);
+        const TileSlot slot = bounded_tile_slot(a.k_per_tile[t], a.idx_offsets[t], prefix, a.idx_total);
+        n_sparse = slot.k;
         nb_gather = (n_sparse + BK - 1) / BK;
         n_blocks = nb_gather + (diag_end - prefix + BK - 1) / BK;
         int src = a.head_map ? a.head_map[hk] : hk;
         src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
-        idx = a.idx + (int64_t)src * a.idx_total + a.idx_offsets[t];
+        idx = a.idx + (int64_t)src * a.idx_total + slot.off;
     } else {
         n_blocks = (diag_end + BK - 1) / BK;
     }
@@ -513,13 +513,12 @@ __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shap
     // bound) is needed
     if (a.topk_out) {
         __syncthreads();   // the pooled scores are visible to the whole workgroup; LDS is free
-        int k = a.k_per_tile[t];
-        k = k < 0 ? 0 : (k > prefix ? prefix : k);
+        const TileSlot slot = bounded_tile_slot(a.k_per_tile[t], a.idx_offsets[t], prefix, a.idx_total);
         Segment sg;
         sg.scores = dst;
-        sg.out = a.topk_out + hk * a.idx_total + a.idx_offsets[t];
+        sg.out = a.topk_out + hk * a.idx_total + slot.off;
         sg.hist11 = nullptr;
-        sg.n = prefix; sg.k_sel = k; sg.forced = 0; sg.pad_to = k;
+        sg.n = prefix; sg.k_sel = slot.k; sg.forced = 0; sg.pad_to = slot.k;
         select_segment<kPB>(sg, *reinterpret_cast<SelectShared<kPB>*>(smem));
     }
 }

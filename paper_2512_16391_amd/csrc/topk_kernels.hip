@@ -27,8 +27,10 @@ __global__ __launch_bounds__(kTopkBlock) void topk_decode_kernel(Shape s, TopkAr
     sg.forced = W;
     sg.pad_to = a.k_max;
     if (a.out_offsets) {
-        sg.out = a.idx_out + hk * a.out_head_pitch + a.out_offsets[b];
-        sg.pad_to = k;
+        const TileSlot slot = bounded_tile_slot(k, a.out_offsets[b], L, a.out_head_pitch);
+        sg.out = a.idx_out + hk * a.out_head_pitch + slot.off;
+        sg.k_sel = slot.k - W;
+        sg.pad_to = slot.k;
     }
     __shared__ SelectShared<kTopkBlock> sm;
     select_segment<kTopkBlock>(sg, sm);
@@ -40,13 +42,13 @@ __global__ __launch_bounds__(kTopkBlock) void topk_prefill_kernel(Shape s, TopkA
     const int hk = blockIdx.x % s.Hkv;
     const int t = a.n_tiles - 1 - blockIdx.x / s.Hkv;
     const int64_t prefix = (int64_t)t * a.tile_tokens;
-    int k = a.k_per_tile[t];
-    k = k < 0 ? 0 : (k > prefix ? (int)prefix : k);
+    const TileSlot slot = bounded_tile_slot(a.k_per_tile[t], a.idx_offsets[t], prefix, a.idx_total);
+    const int k = slot.k;
     // pooled scores of tile t start after those of tiles 0..t-1: sum_{u<t} u*T = T*t*(t-1)/2
     const int64_t seg_off = (int64_t)a.tile_tokens * t * (t - 1) / 2;
     Segment sg;
     sg.scores = a.scores + hk * a.pooled_pitch + seg_off;
-    sg.out = a.idx_out + hk * a.idx_total + a.idx_offsets[t];
+    sg.out = a.idx_out + hk * a.idx_total + slot.off;
     sg.hist11 = nullptr;
     sg.n = (int)prefix;
     sg.k_sel = k;

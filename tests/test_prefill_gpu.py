@@ -428,3 +428,35 @@ def test_prefill_anchor_and_reuse_tiny_prompts(S):
             ref = ko.prefill_sparse_tile(f64(q), f64(k), f64(v), t, T, [idx[h, off[t]:off[t] + kt] for h in range(Hkv)],
                                          ko.default_scale(d))
             assert max_abs(o[lo:hi], ref) <= TOL_OUT[BF16]
+
+
+@pytest.mark.parametrize("variant", ["per_head", "shared", "presoftmax"])
+def test_prefill_holds_device_side_budgets_to_the_index_arrays(variant):
+    """idx_total sizes the index arrays on the host; a device-side budget or offset that would reach
+    past them is cut to what fits (the last tile here asks for 1000 entries more than its slot has):
+    same bits as the consistent call, nothing written or read beyond the arrays."""
+    print(f"case prefill budgets above the index arrays, {variant}", flush=True)
+    S, Hq, Hkv, d, T = 640, 8, 2, 128, 32
+    q, k, v = random_prefill(77, S, Hq, Hkv, d)
+    n_tiles = S // T
+    kpt = [min(t * T, 48) for t in range(n_tiles)]
+    off = offsets(kpt)
+    bad = list(kpt)
+    bad[-1] += 1000
+    call = {"per_head": binding.kascade_prefill_anchor, "shared": binding.kascade_prefill_anchor_shared,
+            "presoftmax": binding.kascade_prefill_anchor_presoftmax}[variant]
+    res = []
+    for budgets in (bad, kpt):
+        idx, out = call(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(budgets), dev_i64(off), off[-1],
+                        out_mode=binding.KASCADE_OUT_SPARSE)
+        torch.cuda.synchronize()
+        res.append((idx.clone(), out.clone()))
+    assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
+    idx = res[1][0]
+    n_src = idx.shape[0]
+    out = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(bad), dev_i64(off), off[-1], idx,
+                                        head_map=dev_i32([0] * Hkv) if n_src == 1 else None)
+    out_ok = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1], idx,
+                                           head_map=dev_i32([0] * Hkv) if n_src == 1 else None)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_ok)
