@@ -121,19 +121,24 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
         for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
     const int key0 = w * kWaveKeys + perm_key(q);
 
-    for (int j0 = begin; j0 < end; j0 += kPassKeys) {
-        // ---- bring this pass's rows into the tiles
-        int rows[PASSES];
+    // the rows of a pass: positions begin .. end of the chunk, or (gather) the entries of the index list at
+    // those positions, fetched one pass ahead so that a pass waits for its rows only, not for its indices first
+    auto rows_of = [&](int j0, int* rows) {
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
             const int j = j0 + i * RPP + r0;
             if constexpr (GATHER) {
-                int row = j < end ? idx[j] : -1;
+                const int row = j < end ? idx[j] : -1;
                 rows[i] = (row >= 0 && row < L) ? row : -1;
             } else {
                 rows[i] = j < end ? j : -1;
             }
         }
+    };
+    int rows[PASSES];
+    rows_of(begin, rows);
+    for (int j0 = begin; j0 < end; j0 += kPassKeys) {
+        // ---- bring this pass's rows into the tiles
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
             const uint64_t off = (uint64_t)(rows[i] < 0 ? 0 : rows[i]) * row_bytes;
@@ -142,6 +147,7 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
                 __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
             if (pp == 0) smOk[i * RPP + r0] = rows[i] >= 0;
         }
+        rows_of(j0 + kPassKeys, rows);   // past the end: all -1, no loads
         wait_vmem();
         __syncthreads();
 
