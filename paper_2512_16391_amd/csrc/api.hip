@@ -241,23 +241,26 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // Which family runs the decode row passes.  The vector-ALU row kernels keep more bytes in flight (registers
 // instead of LDS tiles) and are equal or faster up to four heads per key head; their arithmetic grows with
 // the group, and from eight heads on the matrix-unit kernels, whose cost does not depend on the group, win
-// (batch 8 x 32768, eight heads: gather 34.5 -> 21.4 us, key sweep 163 -> 112 us, sweep with dense output
-// 388 -> 219 us; 64-wide heads: 20.4 -> 12.9, 83 -> 63, 215 -> 122 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
-bool use_matrix_unit(const Shape& s) {
+// (batch 8 x 32768, eight heads: gather 34.5 -> 20.8 us, sweep with dense output 388 -> 219 us; 64-wide
+// heads: 20.4 -> 11.6, 215 -> 122 us).  The key sweep without P.V has a matrix-unit kernel that is staged
+// through registers as well; with 128-wide heads it is ahead from four heads on (batch 8 x 32768: 101 -> 96 us
+// at four heads, 161 -> 101 us at eight).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+enum RowPass { kGatherPass, kSweepPass, kSweepWithVPass };
+bool use_matrix_unit(const Shape& s, RowPass pass) {
     if (s.dtype != 1 || s.G > 16) return false;
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
-    bool mfma = s.G >= 8;
+    bool mfma = s.G >= 8 || (pass == kSweepPass && s.G >= 4 && s.D == 128);
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
     return mfma;
 }
 // Attention over a gathered index list.
 hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
-    if (use_matrix_unit(s)) return launch_decode_gather_mfma(s, plan, a, st);
+    if (use_matrix_unit(s, kGatherPass)) return launch_decode_gather_mfma(s, plan, a, st);
     return launch_decode_rows(s, plan, a, true, true, false, st);
 }
 // The anchor's sweep over every key (logits stored), with the same choice of kernel.
 hipError_t launch_stream(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st) {
-    if (use_matrix_unit(s)) return launch_decode_stream_mfma(s, plan, a, with_v, st);
+    if (use_matrix_unit(s, with_v ? kSweepWithVPass : kSweepPass)) return launch_decode_stream_mfma(s, plan, a, with_v, st);
     return launch_decode_rows(s, plan, a, false, with_v, true, st);
 }
 

@@ -9,11 +9,13 @@
 // same for any G <= 32:
 //   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]       (8 x v_mfma_f32_32x32x16_bf16)
 //   O^T[d x 32 heads]      += V^T[d x 32 keys] P^T[32 keys x 32 heads] (8 more)
-// One workgroup = one chunk of a (sequence, key head) row list, as in the row kernels.  Per pass it
-// brings 128 K rows (and 128 V rows) into LDS with direct global-to-LDS loads (swizzled on the source
-// side, same tile layouts as the prefill kernels), and each of its four waves attends to 32 of those
-// keys with its own online-softmax state; the four states merge through LDS at the end and leave
-// either the output or this chunk's partial (max, sum, acc) triple for decode_merge_kernel.
+// One workgroup = one chunk of a (sequence, key head) row list, as in the row kernels.
+//   decode_rows_mfma_kernel   attention with P.V (gather, or the sweep with dense output): per pass it
+//     brings 128 K rows and 128 V rows into LDS with direct global-to-LDS loads (swizzled on the source
+//     side, same tile layouts as the prefill kernels), and each of its four waves attends to 32 of those
+//     keys with its own online-softmax state; the four states merge through LDS at the end and leave
+//     either the output or this chunk's partial (max, sum, acc) triple for decode_merge_kernel.
+//   decode_sweep_mfma_kernel  the sweep without P.V (logits + statistics), staged through registers.
 #include "device_utils.h"
 #include "kernels.h"
 #include "mfma_tiles.h"
@@ -34,14 +36,14 @@ __device__ __forceinline__ int mfma_rows_per_chunk(int n_rows, int n_chunks) {
     return (c + 63) & ~63;
 }
 
-// GATHER: rows from the index list, split evenly over the chunks; otherwise rows begin .. end of a
-// fixed-length chunk.  STORE: the base-2 scaled logits go to a.logits (stream mode).
-template <int D, bool GATHER, bool WITH_V, bool STORE>
-__global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+// Attention with P.V.  GATHER: rows from the index list, split evenly over the chunks; otherwise rows
+// begin .. end of a fixed-length chunk.  STORE: the base-2 scaled logits go to a.logits (stream mode).
+template <int D, bool GATHER, bool STORE>
+__global__ __launch_bounds__(kMB, 2) void decode_rows_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = kPassKeys * D * 2;
     constexpr int PPR = D / 8, RPP = kMB / PPR, PASSES = kPassKeys / RPP;
     __shared__ __align__(16) unsigned char smK[TILE];
-    __shared__ __align__(16) unsigned char smV[WITH_V ? TILE : 2 * kMW * 32 * 4];
+    __shared__ __align__(16) unsigned char smV[TILE];
     __shared__ int smOk[kPassKeys];
     // cache policy of the direct loads (the instruction's nt bit = 2): gathered rows are touched once per call
     // and should not displace what the neighbouring kernels keep in L2 (batch 64 x 32768: 158 -> 136 us); for
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
             ml[0] = -INFINITY;
             ml[1] = 0.f;
         }
-        if (WITH_V && n_chunks == 1) {
+        if (n_chunks == 1) {
             for (int e = threadIdx.x; e < G * D; e += kMB) {
                 bf16_t* o = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + e / D) * s.o_stride[2] + e % D;
                 *o = 0;
@@ -114,9 +116,9 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
     }
     const float c = s.scale_log2;
     float m_run = -INFINITY, l_run = 0.f;
-    f32x16_t acc_o[WITH_V ? DBLK : 1];
+    f32x16_t acc_o[DBLK];
 #pragma unroll
-    for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
+    for (int i = 0; i < DBLK; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
     const int key0 = w * kWaveKeys + perm_key(q);
@@ -143,8 +145,7 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
         for (int i = 0; i < PASSES; ++i) {
             const uint64_t off = (uint64_t)(rows[i] < 0 ? 0 : rows[i]) * row_bytes;
             __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + off + koff), (lds_ptr_t)(smK + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
-            if constexpr (WITH_V)
-                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
             if (pp == 0) smOk[i * RPP + r0] = rows[i] >= 0;
         }
         rows_of(j0 + kPassKeys, rows);   // past the end: all -1, no loads
@@ -189,12 +190,10 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
         if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {   // wave-uniform: rescale only when a maximum moved
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
             l_run *= alpha;
-            if constexpr (WITH_V) {
 #pragma unroll
-                for (int i = 0; i < DBLK; ++i)
+            for (int i = 0; i < DBLK; ++i)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
-            }
+                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
             m_run = m_new;
         }
         float rs = 0.f;
@@ -204,13 +203,12 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
             rs += s0[r];
         }
         l_run += half_swap_sum(rs);
-        if constexpr (WITH_V) {   // ---- O^T += V^T P^T
-            const bf16x8_t pf0 = pack_p(s0, 0), pf1 = pack_p(s0, 8);
+        // ---- O^T += V^T P^T
+        const bf16x8_t pf0 = pack_p(s0, 0), pf1 = pack_p(s0, 8);
 #pragma unroll
-            for (int i = 0; i < DBLK; ++i) {
-                acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys), pf0, acc_o[i], 0, 0, 0);
-                acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys + 16), pf1, acc_o[i], 0, 0, 0);
-            }
+        for (int i = 0; i < DBLK; ++i) {
+            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys), pf0, acc_o[i], 0, 0, 0);
+            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys + 16), pf1, acc_o[i], 0, 0, 0);
         }
         __syncthreads();   // the tiles are free for the next pass
     }
@@ -220,20 +218,18 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
     float* sm_l = sm_m + kMW * 32;                               // [kMW][32]
     float* sm_acc = reinterpret_cast<float*>(smK);               // [kMW][G][D], at most 4 * 32 * 128 floats = 64 KB > tile: G <= 16 here
     if (h == 0) { sm_m[w * 32 + q] = m_run; sm_l[w * 32 + q] = l_run; }
-    if constexpr (WITH_V) {
-        if (q < G) {
+    if (q < G) {
 #pragma unroll
-            for (int i = 0; i < DBLK; ++i)
+        for (int i = 0; i < DBLK; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int d = i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                    sm_acc[(w * G + q) * D + d] = acc_o[i][r];
-                }
-        }
+            for (int r = 0; r < 16; ++r) {
+                const int d = i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                sm_acc[(w * G + q) * D + d] = acc_o[i][r];
+            }
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < (WITH_V ? G * D : G); e += kMB) {
-        const int g = WITH_V ? e / D : e, col = WITH_V ? e % D : 0;
+    for (int e = threadIdx.x; e < G * D; e += kMB) {
+        const int g = e / D, col = e % D;
         float M = -INFINITY;
 #pragma unroll
         for (int t = 0; t < kMW; ++t) M = fmaxf(M, sm_m[t * 32 + g]);
@@ -243,23 +239,175 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
         for (int t = 0; t < kMW; ++t) {
             const float wgt = __builtin_amdgcn_exp2f(sm_m[t * 32 + g] - Ms);
             lsum = fmaf(wgt, sm_l[t * 32 + g], lsum);
-            if constexpr (WITH_V) val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
+            val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
         }
         const int hq = hk * G + g;
         const int64_t pidx = ((int64_t)(b * s.Hq + hq)) * n_chunks + chunk_id;
-        if constexpr (WITH_V) {
-            if (n_chunks == 1) {
-                const float o = lsum > 0.f ? val / lsum : 0.f;
-                bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
-                *op = (bf16_t)f32_to_bf16_bits(o);
-            } else {
-                a.part_acc[pidx * D + col] = val;
-            }
+        if (n_chunks == 1) {
+            const float o = lsum > 0.f ? val / lsum : 0.f;
+            bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
+            *op = (bf16_t)f32_to_bf16_bits(o);
+        } else {
+            a.part_acc[pidx * D + col] = val;
         }
         if (col == 0) {
             a.part_ml[pidx * 2 + 0] = M;
             a.part_ml[pidx * 2 + 1] = lsum;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The anchor's sweep over every key without P.V (Sec. 3.6 pass 1: logits and softmax statistics), staged
+// through registers.  The tile kernel above can keep no more bytes in flight than its LDS tiles hold
+// and couples its waves with two barriers per pass.  Here every wave streams on its own: it loads 32
+// key rows with coalesced 16-byte loads into registers (two register buffers, the next batch in flight
+// while the current one is used), copies them into a wave-private LDS tile in the swizzled operand
+// layout, reads the A fragments back and runs the same S^T = K Q^T product.  No workgroup barrier in
+// the loop, the vector ALU only sees 16 scores per lane and batch, and the matrix unit is idle most of
+// the time: the kernel is as memory-bound as the vector-ALU sweep with one head per key head.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+template <int D>
+__global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+    constexpr int KSTEPS = D / 16;
+    constexpr int LPR = D / 8;                 // lanes (16-byte pieces) per row
+    constexpr int RPI = kWave / LPR;           // rows per load instruction
+    constexpr int NI = kWaveKeys / RPI;        // load instructions per batch of 32 keys
+    __shared__ __align__(16) unsigned char smK[kMW][kWaveKeys * D * 2];
+    __shared__ float sm_m[kMW][32], sm_l[kMW][32];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane & 31, h = lane >> 5;
+    const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
+    const int n_chunks = plan.n_chunks, G = s.G;
+
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
+    if (chunk_id == 0 && a.hist11) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
+        uint32_t* hg = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
+        for (int i = threadIdx.x; i < 2048; i += kMB) hg[i] = 0u;
+    }
+    const int begin = chunk_id * plan.chunk;
+    const int end = (begin + plan.chunk < L) ? begin + plan.chunk : L;
+    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
+    if (begin >= end) {
+        if ((int)threadIdx.x < G) {
+            float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        return;
+    }
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const uint64_t row_bytes = (uint64_t)s.kv_stride[2] * 2u;
+    bf16x8_t qf[KSTEPS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + b * s.q_stride[0] + (int64_t)(hk * G + q) * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (q < G) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    const float c = s.scale_log2;
+    float m_run = -INFINITY, l_run = 0.f;
+    float* lg0 = a.logits + ((int64_t)b * s.Hq + hk * G) * a.logit_pitch;
+
+    unsigned char* tile = smK[w];
+    const int lr = lane / LPR, lc = lane % LPR;
+    const int frag_key = perm_key(q);
+
+    u32x4_t kA[NI], kB[NI];
+    // rows j0 .. j0 + 31 of the sequence into a register buffer; rows past the end re-read row `begin`
+    auto issue = [&](u32x4_t* buf, int j0) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int row = j0 + i * RPI + lr;
+            const uint64_t off = (uint64_t)(row < end ? row : begin) * row_bytes + (uint32_t)(lc * 16);
+            buf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(Kb + off));
+        }
+    };
+    auto attend = [&](const u32x4_t* buf, int j0) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            *reinterpret_cast<u32x4_t*>(tile + k_off<D>(i * RPI + lr, lc)) = buf[i];
+        f32x16_t s0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s0[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tile + k_off<D>(frag_key, kk * 2 + h)), qf[kk], s0, 0, 0, 0);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int j = j0 + (r >> 3) * 16 + h * 8 + (r & 7);
+            s0[r] = j < end ? s0[r] * c : -INFINITY;
+            mx = fmaxf(mx, s0[r]);
+        }
+        // logits out: a lane holds two runs of eight keys of its head; through the tile (its fragments have
+        // been read) they become one 128-byte line per head, written by eight lanes of one instruction
+        float* sc = reinterpret_cast<float*>(tile);
+        if (q < G) {
+#pragma unroll
+            for (int r8 = 0; r8 < 16; r8 += 8) {
+                float* dst = sc + q * kWaveKeys + (r8 >> 3) * 16 + h * 8;
+                *reinterpret_cast<float4*>(dst) = make_float4(s0[r8], s0[r8 + 1], s0[r8 + 2], s0[r8 + 3]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(s0[r8 + 4], s0[r8 + 5], s0[r8 + 6], s0[r8 + 7]);
+            }
+        }
+        for (int e = lane; e < G * (kWaveKeys / 4); e += kWave) {
+            const int g = e >> 3, piece = (e & 7) * 4;
+            const float4 val = *reinterpret_cast<const float4*>(sc + g * kWaveKeys + piece);
+            float* lgp = lg0 + (int64_t)g * a.logit_pitch + j0 + piece;
+            if (j0 + piece + 4 <= end) {
+                *reinterpret_cast<float4*>(lgp) = val;
+            } else {
+                if (j0 + piece < end) lgp[0] = val.x;
+                if (j0 + piece + 1 < end) lgp[1] = val.y;
+                if (j0 + piece + 2 < end) lgp[2] = val.z;
+            }
+        }
+        mx = half_swap_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        l_run *= __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
+        m_run = m_new;
+        float rs = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rs += __builtin_amdgcn_exp2f(s0[r] - m_safe);
+        l_run += half_swap_sum(rs);
+    };
+
+    // the workgroup walks its chunk 128 rows at a time, 32 per wave
+    constexpr int kStep = kMW * kWaveKeys;
+    int j0 = begin + w * kWaveKeys;
+    if (j0 < end) issue(kA, j0);
+    for (; j0 < end; j0 += 2 * kStep) {
+        const int j1 = j0 + kStep;
+        if (j1 < end) issue(kB, j1);
+        attend(kA, j0);
+        if (j1 + kStep < end) issue(kA, j1 + kStep);
+        if (j1 < end) attend(kB, j1);
+    }
+
+    // ---- merge the four waves' statistics, fixed order
+    if (h == 0) { sm_m[w][q] = m_run; sm_l[w][q] = l_run; }
+    __syncthreads();
+    if ((int)threadIdx.x < G) {
+        const int g = threadIdx.x;
+        float M = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kMW; ++t) M = fmaxf(M, sm_m[t][g]);
+        const float Ms = (M == -INFINITY) ? 0.f : M;
+        float lsum = 0.f;
+#pragma unroll
+        for (int t = 0; t < kMW; ++t) lsum = fmaf(__builtin_amdgcn_exp2f(sm_m[t][g] - Ms), sm_l[t][g], lsum);
+        float* ml = a.part_ml + (part_base + (int64_t)g * n_chunks) * 2;
+        ml[0] = M;
+        ml[1] = lsum;
     }
 }
 
@@ -269,8 +417,8 @@ __global__ __launch_bounds__(kMB, (WITH_V ? 2 : 4)) void decode_rows_mfma_kernel
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
     if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, true, true, false>), grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, true, true, false>), grid, block, 0, st, s, plan, a);
+    if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, true, false>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 
@@ -281,11 +429,11 @@ hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, con
     if ((a.logit_pitch & 3) || (reinterpret_cast<uintptr_t>(a.logits) & 15) || (plan.chunk & 7)) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
     if (s.D == 128) {
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, true, true>), grid, block, 0, st, s, plan, a);
-        else hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, false, true>), grid, block, 0, st, s, plan, a);
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, true>), grid, block, 0, st, s, plan, a);
+        else hipLaunchKernelGGL((decode_sweep_mfma_kernel<128>), grid, block, 0, st, s, plan, a);
     } else {
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, true, true>), grid, block, 0, st, s, plan, a);
-        else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, false, true>), grid, block, 0, st, s, plan, a);
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, true>), grid, block, 0, st, s, plan, a);
+        else hipLaunchKernelGGL((decode_sweep_mfma_kernel<64>), grid, block, 0, st, s, plan, a);
     }
     return hipGetLastError();
 }
