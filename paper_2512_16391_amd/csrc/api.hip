@@ -238,18 +238,18 @@ PrefillPreWs carve_prefill_presoftmax(const Shape& s, int64_t S, int T, void* ws
 
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
-// Which family runs the decode row passes.  The vector-ALU row kernels keep more bytes in flight (registers
-// instead of LDS tiles) and are equal or faster up to four heads per key head; their arithmetic grows with
-// the group, and from eight heads on the matrix-unit kernels, whose cost does not depend on the group, win
-// (batch 8 x 32768, eight heads: gather 34.5 -> 20.8 us, sweep with dense output 388 -> 219 us; 64-wide
-// heads: 20.4 -> 11.6, 215 -> 122 us).  The key sweep without P.V has a matrix-unit kernel that is staged
-// through registers as well; with 128-wide heads it is ahead from four heads on (batch 8 x 32768: 101 -> 96 us
-// at four heads, 161 -> 101 us at eight).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+// Which family runs the decode row passes.  The arithmetic of the vector-ALU row kernels grows with the number of
+// heads per key head, that of the matrix-unit kernels does not.  The matrix-unit kernels that stage rows through
+// LDS tiles keep fewer bytes in flight than the vector-ALU kernels keep in registers and only win from eight heads
+// on (batch 8 x 32768, eight heads, sweep with dense output 388 -> 219 us; 64-wide heads: gather 20.4 -> 11.6 us,
+// 215 -> 122 us).  With 128-wide heads the gather and the key sweep without P.V have matrix-unit kernels staged
+// through registers, ahead from four heads on (batch 8 x 32768, four heads: gather 19.5 -> 15.6 us, sweep
+// 101 -> 96 us; eight heads: 34.5 -> 18 us, 161 -> 101 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
 enum RowPass { kGatherPass, kSweepPass, kSweepWithVPass };
 bool use_matrix_unit(const Shape& s, RowPass pass) {
     if (s.dtype != 1 || s.G > 16) return false;
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
-    bool mfma = s.G >= 8 || (pass == kSweepPass && s.G >= 4 && s.D == 128);
+    bool mfma = s.G >= 8 || (pass != kSweepWithVPass && s.G >= 4 && s.D == 128);
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
     return mfma;
 }

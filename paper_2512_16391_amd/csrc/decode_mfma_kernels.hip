@@ -10,12 +10,14 @@
 //   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]       (8 x v_mfma_f32_32x32x16_bf16)
 //   O^T[d x 32 heads]      += V^T[d x 32 keys] P^T[32 keys x 32 heads] (8 more)
 // One workgroup = one chunk of a (sequence, key head) row list, as in the row kernels.
-//   decode_rows_mfma_kernel   attention with P.V (gather, or the sweep with dense output): per pass it
-//     brings 128 K rows and 128 V rows into LDS with direct global-to-LDS loads (swizzled on the source
-//     side, same tile layouts as the prefill kernels), and each of its four waves attends to 32 of those
-//     keys with its own online-softmax state; the four states merge through LDS at the end and leave
-//     either the output or this chunk's partial (max, sum, acc) triple for decode_merge_kernel.
-//   decode_sweep_mfma_kernel  the sweep without P.V (logits + statistics), staged through registers.
+//   decode_rows_mfma_kernel   attention with P.V through LDS tiles (the sweep with dense output; gather
+//     for 64-wide heads): per pass it brings 128 K rows and 128 V rows into LDS with direct global-to-LDS
+//     loads (swizzled on the source side, same tile layouts as the prefill kernels), and each of its four
+//     waves attends to 32 of those keys with its own online-softmax state; the four states merge through
+//     LDS at the end and leave either the output or this chunk's partial (max, sum, acc) triple for
+//     decode_merge_kernel.
+//   decode_sweep_mfma_kernel     the sweep without P.V (logits + statistics), staged through registers.
+//   decode_gather_mfma16_kernel  gather for 128-wide heads, staged through registers, 16-wide MFMA tiles.
 #include "device_utils.h"
 #include "kernels.h"
 #include "mfma_tiles.h"
@@ -411,13 +413,252 @@ __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, Deco
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Gather-mode attention staged through registers (reuse layers, anchor pass 4; 128-wide heads).
+// Same idea as the sweep above - every wave streams on its own, 32 K rows and 32 V rows per batch in
+// registers (two buffers for K, one for V), a wave-private LDS tile, no barrier in the loop - with P.V on
+// top.  To fit the buffers (96 registers) the products use the 16-wide tile, v_mfma_f32_16x16x32_bf16:
+// the heads of the group are padded to 16 columns instead of 32, so the output accumulators take 32
+// registers instead of 64 and the query fragments 16 instead of 32:
+//   S^T[16 keys x 16 heads] = K[16 keys x 32 d] Q^T[32 d x 16 heads]        (4 per tile, 2 tiles per batch)
+//   O^T[16 d x 16 heads]   += V^T[16 d x 32 keys] P^T[32 keys x 16 heads]   (one per 16 d)
+// Output layout of the 16x16 tile: lane (col = lane%16, rg = lane/16), register r holds row rg*4 + r.
+// Operands: lane (row or col = lane%16, kg = lane/16) holds the 8 consecutive k of group kg.  The key
+// slot behind row rho of S tile t is sigma(t, rho) = (rho/4)*8 + t*4 + rho%4, so that the eight scores a
+// lane holds (two tiles x four registers) are the key slots rg*8 .. rg*8+7: exactly its part of the
+// P^T operand.  The one LDS tile of a wave holds the K rows first and the V rows after the S tiles are
+// computed (LDS operations of a wave execute in order).
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// K rows in the tile: 16-byte chunks XOR-swizzled by the S-tile row of the slot, so that the 16 rows
+// one fragment read touches (same chunk) fall into 16 different chunk positions
+__device__ __forceinline__ int k16_off(int slot, int chunk) {
+    const int rho = ((slot >> 3) << 2) | (slot & 3);
+    return slot * 256 + ((chunk ^ rho) << 4);
+}
+// V rows in the tile: 32-byte pieces (16 d) XOR-swizzled so that the 16 rows one transposing read touches
+// (slots g*8 + m, g = 0..3, m = 0..3, same piece) spread over all eight piece positions
+__device__ __forceinline__ int v16_swz(int slot) { return (slot & 3) | (((slot >> 3) & 1) << 2); }
+__device__ __forceinline__ int v16_off(int slot, int d) {
+    return slot * 256 + ((((d >> 4) ^ v16_swz(slot))) << 5) + ((d & 15) << 1);
+}
+// V^T fragment: row = d index dt*16 + lane%16, keys (lane/16)*8 + 0..7 (see vt_frag in mfma_tiles.h)
+__device__ __forceinline__ bf16x8_t vt16_frag(const unsigned char* tile, int dt) {
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, cb = lane & 3, m = (lane >> 2) & 3;
+    typedef s16x4_t __attribute__((address_space(3))) * lds_v4;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + v16_off(g * 8 + m, dt * 16 + cb * 4)));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + v16_off(g * 8 + 4 + m, dt * 16 + cb * 4)));
+    struct { s16x4_t lo, hi; } both = {lo, hi};
+    return __builtin_bit_cast(bf16x8_t, both);
+}
+__device__ __forceinline__ float quad_rows_max(float x) {   // over the four lanes l, l+16, l+32, l+48
+    x = fmaxf(x, __shfl_xor(x, 16));
+    return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float quad_rows_sum(float x) {
+    x += __shfl_xor(x, 16);
+    return x + __shfl_xor(x, 32);
+}
+
+__global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+    constexpr int D = 128, KS = D / 32, DT = D / 16, NI = 8, RPI = 4;
+    __shared__ __align__(16) unsigned char smT[kMW][kWaveKeys * D * 2];
+    __shared__ float sm_m[kMW][16], sm_l[kMW][16];
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hd = lane & 15, rg = lane >> 4;
+    const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
+    const int n_chunks = plan.n_chunks, G = s.G;
+
+    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
+    int n_rows = a.k_per_seq[b];
+    n_rows = n_rows < a.k_max ? n_rows : a.k_max;
+    if (L <= 0 || n_rows < 0) n_rows = 0;
+    const int chunk = mfma_rows_per_chunk(n_rows, n_chunks);
+    const int begin = chunk_id * chunk;
+    const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
+    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
+    if (begin >= end) {   // an empty chunk: mark it for the merge (and define the output of an empty set)
+        if ((int)threadIdx.x < G) {
+            float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
+            ml[0] = -INFINITY;
+            ml[1] = 0.f;
+        }
+        if (n_chunks == 1) {
+            for (int e = threadIdx.x; e < G * D; e += kMB) {
+                bf16_t* o = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + e / D) * s.o_stride[2] + e % D;
+                *o = 0;
+            }
+        }
+        return;
+    }
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
+    const uint64_t row_bytes = (uint64_t)s.kv_stride[2] * 2u;
+    int src = a.head_map ? a.head_map[hk] : hk;
+    src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+    const int32_t* idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+
+    bf16x8_t qf[KS];
+    {
+        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + b * s.q_stride[0] + (int64_t)(hk * G + hd) * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (hd < G) raw = *reinterpret_cast<const uint4*>(qp + kk * 32 + rg * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    const float c = s.scale_log2;
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4_t acc[DT];
+#pragma unroll
+    for (int i = 0; i < DT; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    unsigned char* tile = smT[w];
+    const int lr = lane >> 4, lc = lane & 15;   // row within a load instruction, 16-byte piece of the row
+    const int v_piece = lc >> 1, v_half = (lc & 1) << 4;
+
+    // list entries j0 .. j0+31 of this wave's batch (lanes 32..63 repeat them); -1 = nothing to attend to
+    auto fetch_idx = [&](int j0) -> int {
+        const int j = j0 + (lane & 31);
+        const int row = j < end ? idx[j] : -1;
+        return (row >= 0 && row < L) ? row : -1;
+    };
+    // two register buffers for K rows, one for V rows: the V rows of the next batch are requested as soon as
+    // this batch's have moved into the tile
+    u32x4_t kA[NI], kB[NI], vb[NI];
+    auto issue = [&](u32x4_t* buf, const unsigned char* base, int rows) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int row = __shfl(rows, i * RPI + lr);
+            const uint64_t off = (uint64_t)(row < 0 ? 0 : row) * row_bytes + (uint32_t)(lc * 16);
+            buf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + off));
+        }
+    };
+    auto attend = [&](const u32x4_t* kb, int rows, int next_rows, bool have_next) {
+        const uint32_t ok = (uint32_t)__builtin_amdgcn_ballot_w64(rows >= 0);   // bit = key slot (lanes 0..31)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4_t*>(tile + k16_off(i * RPI + lr, lc)) = kb[i];
+        f32x4_t st[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            st[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            const int slot = ((hd >> 2) << 3) + t * 4 + (hd & 3);   // sigma(t, rho = hd)
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_frag(tile + k16_off(slot, kk * 4 + rg)), qf[kk], st[t], 0, 0, 0);
+        }
+        float p[8];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool valid = (ok >> (rg * 8 + e)) & 1u;
+            p[e] = valid ? st[e >> 2][e & 3] * c : -INFINITY;
+            mx = fmaxf(mx, p[e]);
+        }
+        mx = quad_rows_max(mx);
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {   // wave-uniform: rescale only when a maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < DT; ++i) acc[i] *= alpha;
+            m_run = m_new;
+        }
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            p[e] = __builtin_amdgcn_exp2f(p[e] - m_safe);
+            rs += p[e];
+        }
+        l_run += quad_rows_sum(rs);
+        bf16x8_t pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[e];
+        // the K fragments have been read: the tile takes the V rows
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int slot = i * RPI + lr;
+            *reinterpret_cast<u32x4_t*>(tile + slot * 256 + ((v_piece ^ v16_swz(slot)) << 5) + v_half) = vb[i];
+        }
+        if (have_next) issue(vb, Vb, next_rows);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt16_frag(tile, dt), pf, acc[dt], 0, 0, 0);
+    };
+
+    // the workgroup walks its chunk 128 list entries at a time, 32 per wave; index entries are fetched two
+    // batches ahead of their rows so that waiting for them never waits for rows in flight
+    constexpr int kStep = kMW * kWaveKeys;
+    int j0 = begin + w * kWaveKeys;
+    int r0 = fetch_idx(j0), r1 = fetch_idx(j0 + kStep);
+    if (j0 < end) {
+        issue(kA, Kb, r0);
+        issue(vb, Vb, r0);
+    }
+    for (; j0 < end; j0 += 2 * kStep) {
+        const int r2 = fetch_idx(j0 + 2 * kStep);
+        if (j0 + kStep < end) issue(kB, Kb, r1);
+        attend(kA, r0, r1, j0 + kStep < end);
+        const int r3 = fetch_idx(j0 + 3 * kStep);
+        if (j0 + 2 * kStep < end) issue(kA, Kb, r2);
+        if (j0 + kStep < end) attend(kB, r1, r2, j0 + 2 * kStep < end);
+        r0 = r2;
+        r1 = r3;
+    }
+
+    // ---- merge the four waves' states through LDS (the tiles are free after the barrier), fixed order
+    __syncthreads();
+    float* sm_acc = reinterpret_cast<float*>(&smT[0][0]);   // [kMW][G][D]: 4 * 16 * 128 floats = the four tiles
+    if (rg == 0) { sm_m[w][hd] = m_run; sm_l[w][hd] = l_run; }
+    if (hd < G) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sm_acc[(w * G + hd) * D + dt * 16 + rg * 4 + r] = acc[dt][r];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < G * D; e += kMB) {
+        const int g = e / D, col = e % D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < kMW; ++t) M = fmaxf(M, sm_m[t][g]);
+        const float Ms = (M == -INFINITY) ? 0.f : M;
+        float lsum = 0.f, val = 0.f;
+#pragma unroll
+        for (int t = 0; t < kMW; ++t) {
+            const float wgt = __builtin_amdgcn_exp2f(sm_m[t][g] - Ms);
+            lsum = fmaf(wgt, sm_l[t][g], lsum);
+            val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
+        }
+        const int hq = hk * G + g;
+        const int64_t pidx = ((int64_t)(b * s.Hq + hq)) * n_chunks + chunk_id;
+        if (n_chunks == 1) {
+            const float o = lsum > 0.f ? val / lsum : 0.f;
+            bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
+            *op = (bf16_t)f32_to_bf16_bits(o);
+        } else {
+            a.part_acc[pidx * D + col] = val;
+        }
+        if (col == 0) {
+            a.part_ml[pidx * 2 + 0] = M;
+            a.part_ml[pidx * 2 + 1] = lsum;
+        }
+    }
+}
+
 }  // namespace
 
 // Gather-mode attention for bf16, groups of up to 16 heads.
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
     if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, true, false>), grid, block, 0, st, s, plan, a);
+    if (s.D == 128) hipLaunchKernelGGL(decode_gather_mfma16_kernel, grid, block, 0, st, s, plan, a);
     else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
