@@ -239,28 +239,27 @@ PrefillPreWs carve_prefill_presoftmax(const Shape& s, int64_t S, int T, void* ws
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
 // Which family runs the decode row passes.  The arithmetic of the vector-ALU row kernels grows with the number of
-// heads per key head, that of the matrix-unit kernels does not.  The matrix-unit kernels that stage rows through
-// LDS tiles keep fewer bytes in flight than the vector-ALU kernels keep in registers and only win from eight heads
-// on (batch 8 x 32768, eight heads, sweep with dense output 388 -> 219 us; 64-wide heads: gather 20.4 -> 11.6 us,
-// 215 -> 122 us).  With 128-wide heads the gather and the key sweep without P.V have matrix-unit kernels staged
-// through registers, ahead from four heads on (batch 8 x 32768, four heads: gather 19.5 -> 15.6 us, sweep
-// 101 -> 96 us; eight heads: 34.5 -> 18 us, 161 -> 101 us).  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
-enum RowPass { kGatherPass, kSweepPass, kSweepWithVPass };
-bool use_matrix_unit(const Shape& s, RowPass pass) {
+// heads per key head, that of the matrix-unit kernels does not.  For 128-wide heads the matrix-unit kernels stage
+// rows through registers like the vector-ALU kernels do and are ahead from four heads on (batch 8 x 32768, four
+// heads: gather 19.5 -> 15.6 us, key sweep 101 -> 96 us, sweep with dense output 191 -> 184 us; eight heads:
+// 34.5 -> 18 us, 161 -> 101 us, 385 -> 194 us).  For 64-wide heads the passes with P.V stage through LDS tiles,
+// which keep fewer bytes in flight, and win from eight heads on (gather 20.4 -> 11.6 us, 215 -> 122 us).
+// KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+bool use_matrix_unit(const Shape& s) {
     if (s.dtype != 1 || s.G > 16) return false;
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
-    bool mfma = s.G >= 8 || (pass != kSweepWithVPass && s.G >= 4 && s.D == 128);
+    bool mfma = s.G >= 8 || (s.G >= 4 && s.D == 128);
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
     return mfma;
 }
 // Attention over a gathered index list.
 hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
-    if (use_matrix_unit(s, kGatherPass)) return launch_decode_gather_mfma(s, plan, a, st);
+    if (use_matrix_unit(s)) return launch_decode_gather_mfma(s, plan, a, st);
     return launch_decode_rows(s, plan, a, true, true, false, st);
 }
 // The anchor's sweep over every key (logits stored), with the same choice of kernel.
 hipError_t launch_stream(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st) {
-    if (use_matrix_unit(s, with_v ? kSweepWithVPass : kSweepPass)) return launch_decode_stream_mfma(s, plan, a, with_v, st);
+    if (use_matrix_unit(s)) return launch_decode_stream_mfma(s, plan, a, with_v, st);
     return launch_decode_rows(s, plan, a, false, with_v, true, st);
 }
 

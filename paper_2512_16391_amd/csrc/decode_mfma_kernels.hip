@@ -10,14 +10,15 @@
 //   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]       (8 x v_mfma_f32_32x32x16_bf16)
 //   O^T[d x 32 heads]      += V^T[d x 32 keys] P^T[32 keys x 32 heads] (8 more)
 // One workgroup = one chunk of a (sequence, key head) row list, as in the row kernels.
-//   decode_rows_mfma_kernel   attention with P.V through LDS tiles (the sweep with dense output; gather
-//     for 64-wide heads): per pass it brings 128 K rows and 128 V rows into LDS with direct global-to-LDS
+//   decode_rows_mfma_kernel   attention with P.V through LDS tiles (64-wide heads: gather and the sweep
+//     with dense output): per pass it brings 128 K rows and 128 V rows into LDS with direct global-to-LDS
 //     loads (swizzled on the source side, same tile layouts as the prefill kernels), and each of its four
 //     waves attends to 32 of those keys with its own online-softmax state; the four states merge through
 //     LDS at the end and leave either the output or this chunk's partial (max, sum, acc) triple for
 //     decode_merge_kernel.
 //   decode_sweep_mfma_kernel     the sweep without P.V (logits + statistics), staged through registers.
-//   decode_gather_mfma16_kernel  gather for 128-wide heads, staged through registers, 16-wide MFMA tiles.
+//   decode_rows_mfma16_kernel    attention with P.V for 128-wide heads (gather and the sweep with dense
+//     output), staged through registers, 16-wide MFMA tiles.
 #include "device_utils.h"
 #include "kernels.h"
 #include "mfma_tiles.h"
@@ -414,7 +415,8 @@ __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, Deco
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Gather-mode attention staged through registers (reuse layers, anchor pass 4; 128-wide heads).
+// Attention with P.V staged through registers, 128-wide heads: gather mode (reuse layers, anchor pass 4)
+// and the sweep over every key with dense output.
 // Same idea as the sweep above - every wave streams on its own, 32 K rows and 32 V rows per batch in
 // registers (two buffers for K, one for V), a wave-private LDS tile, no barrier in the loop - with P.V on
 // top.  To fit the buffers (96 registers) the products use the 16-wide tile, v_mfma_f32_16x16x32_bf16:
@@ -461,7 +463,10 @@ __device__ __forceinline__ float quad_rows_sum(float x) {
     return x + __shfl_xor(x, 32);
 }
 
-__global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
+// GATHER: rows from the index list; otherwise rows begin .. end of a fixed-length chunk, logits stored (the sweep
+// with dense output).
+template <bool GATHER>
+__global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int D = 128, KS = D / 32, DT = D / 16, NI = 8, RPI = 4;
     __shared__ __align__(16) unsigned char smT[kMW][kWaveKeys * D * 2];
     __shared__ float sm_m[kMW][16], sm_l[kMW][16];
@@ -473,10 +478,18 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
     const int n_chunks = plan.n_chunks, G = s.G;
 
     const int L = bounded_len(a.seqlens[b], a.max_seqlen);
-    int n_rows = a.k_per_seq[b];
-    n_rows = n_rows < a.k_max ? n_rows : a.k_max;
-    if (L <= 0 || n_rows < 0) n_rows = 0;
-    const int chunk = mfma_rows_per_chunk(n_rows, n_chunks);
+    int n_rows = L;
+    if constexpr (GATHER) {
+        n_rows = a.k_per_seq[b];
+        n_rows = n_rows < a.k_max ? n_rows : a.k_max;
+        if (L <= 0 || n_rows < 0) n_rows = 0;
+    } else {
+        if (chunk_id == 0 && a.hist11) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
+            uint32_t* hg = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
+            for (int i = threadIdx.x; i < 2048; i += kMB) hg[i] = 0u;
+        }
+    }
+    const int chunk = GATHER ? mfma_rows_per_chunk(n_rows, n_chunks) : plan.chunk;
     const int begin = chunk_id * chunk;
     const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
     const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
@@ -498,9 +511,13 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
     const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
     const uint64_t row_bytes = (uint64_t)s.kv_stride[2] * 2u;
-    int src = a.head_map ? a.head_map[hk] : hk;
-    src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
-    const int32_t* idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+    const int32_t* idx = nullptr;
+    if constexpr (GATHER) {
+        int src = a.head_map ? a.head_map[hk] : hk;
+        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
+        idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
+    }
+    float* lg = GATHER ? nullptr : a.logits + ((int64_t)b * s.Hq + hk * G + (hd < G ? hd : 0)) * a.logit_pitch;
 
     bf16x8_t qf[KS];
     {
@@ -525,8 +542,12 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
     // list entries j0 .. j0+31 of this wave's batch (lanes 32..63 repeat them); -1 = nothing to attend to
     auto fetch_idx = [&](int j0) -> int {
         const int j = j0 + (lane & 31);
-        const int row = j < end ? idx[j] : -1;
-        return (row >= 0 && row < L) ? row : -1;
+        if constexpr (GATHER) {
+            const int row = j < end ? idx[j] : -1;
+            return (row >= 0 && row < L) ? row : -1;
+        } else {
+            return j < end ? j : -1;
+        }
     };
     // two register buffers for K rows, one for V rows: the V rows of the next batch are requested as soon as
     // this batch's have moved into the tile
@@ -539,7 +560,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
             buf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + off));
         }
     };
-    auto attend = [&](const u32x4_t* kb, int rows, int next_rows, bool have_next) {
+    auto attend = [&](const u32x4_t* kb, int rows, int next_rows, bool have_next, int j0) {
         const uint32_t ok = (uint32_t)__builtin_amdgcn_ballot_w64(rows >= 0);   // bit = key slot (lanes 0..31)
 #pragma unroll
         for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4_t*>(tile + k16_off(i * RPI + lr, lc)) = kb[i];
@@ -559,6 +580,19 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
             const bool valid = (ok >> (rg * 8 + e)) & 1u;
             p[e] = valid ? st[e >> 2][e & 3] * c : -INFINITY;
             mx = fmaxf(mx, p[e]);
+        }
+        if constexpr (!GATHER) {   // a lane holds eight consecutive keys of its head
+            if (hd < G) {
+                const int j = j0 + rg * 8;
+                if (j + 8 <= end) {
+                    *reinterpret_cast<float4*>(lg + j) = make_float4(p[0], p[1], p[2], p[3]);
+                    *reinterpret_cast<float4*>(lg + j + 4) = make_float4(p[4], p[5], p[6], p[7]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (j + e < end) lg[j + e] = p[e];
+                }
+            }
         }
         mx = quad_rows_max(mx);
         const float m_new = fmaxf(m_run, mx);
@@ -604,10 +638,10 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
     for (; j0 < end; j0 += 2 * kStep) {
         const int r2 = fetch_idx(j0 + 2 * kStep);
         if (j0 + kStep < end) issue(kB, Kb, r1);
-        attend(kA, r0, r1, j0 + kStep < end);
+        attend(kA, r0, r1, j0 + kStep < end, j0);
         const int r3 = fetch_idx(j0 + 3 * kStep);
         if (j0 + 2 * kStep < end) issue(kA, Kb, r2);
-        if (j0 + kStep < end) attend(kB, r1, r2, j0 + 2 * kStep < end);
+        if (j0 + kStep < end) attend(kB, r1, r2, j0 + 2 * kStep < end, j0 + kStep);
         r0 = r2;
         r1 = r3;
     }
@@ -658,7 +692,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_gather_mfma16_kernel(Shape s, D
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
     if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (s.D == 128) hipLaunchKernelGGL(decode_gather_mfma16_kernel, grid, block, 0, st, s, plan, a);
+    if (s.D == 128) hipLaunchKernelGGL(decode_rows_mfma16_kernel<true>, grid, block, 0, st, s, plan, a);
     else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
@@ -670,7 +704,7 @@ hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, con
     if ((a.logit_pitch & 3) || (reinterpret_cast<uintptr_t>(a.logits) & 15) || (plan.chunk & 7)) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
     if (s.D == 128) {
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<128, false, true>), grid, block, 0, st, s, plan, a);
+        if (with_v) hipLaunchKernelGGL(decode_rows_mfma16_kernel<false>, grid, block, 0, st, s, plan, a);
         else hipLaunchKernelGGL((decode_sweep_mfma_kernel<128>), grid, block, 0, st, s, plan, a);
     } else {
         if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, true>), grid, block, 0, st, s, plan, a);
