@@ -652,3 +652,32 @@ def test_decode_anchor_holds_lengths_to_max_seqlen(dtype, d, G, variant):
             res.append((idx.clone(), out.clone()))
         assert torch.equal(res[0][0], res[1][0]) and torch.equal(res[0][1], res[1][1])
         assert int(res[0][0].max()) < max_seqlen
+
+
+@pytest.mark.parametrize("dtype,d,G", [(torch.bfloat16, 128, 4), (torch.bfloat16, 128, 8), (torch.bfloat16, 64, 2),
+                                       (torch.float32, 64, 4)])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_decode_anchor_token_major_cache(dtype, d, G, out_mode):
+    """Anchor layer over a cache laid out [B, L, Hkv, d] (rows of a key head Hkv*d elements apart) with a
+    custom softmax scale: the same bits as over the head-major copy of the cache."""
+    print(f"case anchor token-major cache dtype={dtype} d={d} G={G} out_mode={out_mode}", flush=True)
+    Hkv, lens, ks = 2, [1300, 257, 40], [130, 26, 40]
+    q, k, v = random_case(55, 3, G * Hkv, Hkv, d, dtype, lens)
+    a = (i32(lens), i32(ks), max(lens), max(ks))
+    idx0, out0 = binding.kascade_decode_anchor(q.to(DEV), k.to(DEV), v.to(DEV), *a, recent_window=2, out_mode=out_mode,
+                                               softmax_scale=0.11)
+    k_t, v_t = k.permute(0, 2, 1, 3).contiguous(), v.permute(0, 2, 1, 3).contiguous()
+    idx1, out1 = binding.kascade_decode_anchor(q.to(DEV), k_t.to(DEV), v_t.to(DEV), *a, recent_window=2, out_mode=out_mode,
+                                               softmax_scale=0.11, kv_layout="BLHD")
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1) and torch.equal(out0, out1)
+    # and the head-major result against the oracle
+    idx_h, o = idx0.cpu().numpy(), f64(out0)
+    for b, (L, kb) in enumerate(zip(lens, ks)):
+        qb, kb_, vb = f64(q[b]), f64(k[b, :, :L]), f64(v[b, :, :L])
+        ref_idx, aa = ko.decode_anchor_indices(qb, kb_, 0.11, kb, 2)
+        for h in range(Hkv):
+            check_index_set(idx_h[b, h, :kb], ref_idx[h], aa[h], n_forced=2, where=f"b{b} h{h}")
+        want = ko.dense_decode(qb, kb_, vb, 0.11) if out_mode == binding.KASCADE_OUT_DENSE else \
+            ko.sparse_decode(qb, kb_, vb, [idx_h[b, h, :kb] for h in range(Hkv)], 0.11)
+        assert max_abs(o[b], want) <= TOL_OUT[dtype]
