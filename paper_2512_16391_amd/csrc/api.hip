@@ -239,16 +239,15 @@ PrefillPreWs carve_prefill_presoftmax(const Shape& s, int64_t S, int T, void* ws
 int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP_ERROR; }
 
 // Which family runs the decode row passes.  The arithmetic of the vector-ALU row kernels grows with the number of
-// heads per key head, that of the matrix-unit kernels does not.  For 128-wide heads the matrix-unit kernels stage
-// rows through registers like the vector-ALU kernels do and are ahead from four heads on (batch 8 x 32768, four
-// heads: gather 19.5 -> 15.6 us, key sweep 101 -> 96 us, sweep with dense output 191 -> 184 us; eight heads:
-// 34.5 -> 18 us, 161 -> 101 us, 385 -> 194 us).  For 64-wide heads the passes with P.V stage through LDS tiles,
-// which keep fewer bytes in flight, and win from eight heads on (gather 20.4 -> 11.6 us, 215 -> 122 us).
-// KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+// heads per key head, that of the matrix-unit kernels does not; both stage rows through registers in the same
+// way.  The matrix-unit kernels are ahead from four heads on (batch 8 x 32768, 128-wide heads, four heads: gather
+// 19.5 -> 15.6 us, key sweep 101 -> 96 us, sweep with dense output 191 -> 184 us; eight heads: 34.5 -> 18 us,
+// 161 -> 101 us, 385 -> 194 us; 64-wide heads, four heads: gather 10.9 -> 8.2 us) and equal or a little behind
+// below that.  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
 bool use_matrix_unit(const Shape& s) {
     if (s.dtype != 1 || s.G > 16) return false;
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
-    bool mfma = s.G >= 8 || (s.G >= 4 && s.D == 128);
+    bool mfma = s.G >= 4;
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
     return mfma;
 }

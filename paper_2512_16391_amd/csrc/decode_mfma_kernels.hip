@@ -5,20 +5,16 @@
 //
 // The vector-ALU row kernels spend arithmetic in proportion to the number of query heads per key
 // head; from four heads up that arithmetic, not HBM, sets their speed.  Here the G query heads of
-// a key head are the columns of one 32-wide MFMA operand (zero padded), so q.k and P.V cost the
-// same for any G <= 32:
-//   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]       (8 x v_mfma_f32_32x32x16_bf16)
-//   O^T[d x 32 heads]      += V^T[d x 32 keys] P^T[32 keys x 32 heads] (8 more)
-// One workgroup = one chunk of a (sequence, key head) row list, as in the row kernels.
-//   decode_rows_mfma_kernel   attention with P.V through LDS tiles (64-wide heads: gather and the sweep
-//     with dense output): per pass it brings 128 K rows and 128 V rows into LDS with direct global-to-LDS
-//     loads (swizzled on the source side, same tile layouts as the prefill kernels), and each of its four
-//     waves attends to 32 of those keys with its own online-softmax state; the four states merge through
-//     LDS at the end and leave either the output or this chunk's partial (max, sum, acc) triple for
-//     decode_merge_kernel.
-//   decode_sweep_mfma_kernel     the sweep without P.V (logits + statistics), staged through registers.
-//   decode_rows_mfma16_kernel    attention with P.V for 128-wide heads (gather and the sweep with dense
-//     output), staged through registers, 16-wide MFMA tiles.
+// a key head are the columns of one MFMA operand (zero padded), so q.k and P.V cost the same for any
+// G up to 16, and rows are staged the way the vector-ALU kernels stage them: every wave streams on its
+// own, with coalesced 16-byte loads into register buffers (the next batch in flight while the current
+// one is used), and a wave-private LDS tile turns a batch of 32 rows into MFMA fragments.  No
+// workgroup barrier in the loops.  One workgroup = one chunk of a (sequence, key head) row list, as
+// in the row kernels; its four waves take 32-row batches in turn and merge their online-softmax
+// states through LDS at the end, leaving either the output or this chunk's partial (max, sum, acc)
+// triple for decode_merge_kernel.
+//   decode_sweep_mfma_kernel     the sweep without P.V (logits + statistics), 32-wide MFMA tiles
+//   decode_rows_mfma16_kernel    attention with P.V (gather, and the sweep with dense output), 16-wide tiles
 #include "device_utils.h"
 #include "kernels.h"
 #include "mfma_tiles.h"
@@ -32,243 +28,21 @@ using namespace mfma;
 constexpr int kMB = 256;              // threads per workgroup
 constexpr int kMW = kMB / kWave;      // waves
 constexpr int kWaveKeys = 32;         // keys per wave and pass
-constexpr int kPassKeys = kMW * kWaveKeys;
 
 __device__ __forceinline__ int mfma_rows_per_chunk(int n_rows, int n_chunks) {
     const int c = (n_rows + n_chunks - 1) / n_chunks;
     return (c + 63) & ~63;
 }
 
-// Attention with P.V.  GATHER: rows from the index list, split evenly over the chunks; otherwise rows
-// begin .. end of a fixed-length chunk.  STORE: the base-2 scaled logits go to a.logits (stream mode).
-template <int D, bool GATHER, bool STORE>
-__global__ __launch_bounds__(kMB, 2) void decode_rows_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
-    constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = kPassKeys * D * 2;
-    constexpr int PPR = D / 8, RPP = kMB / PPR, PASSES = kPassKeys / RPP;
-    __shared__ __align__(16) unsigned char smK[TILE];
-    __shared__ __align__(16) unsigned char smV[TILE];
-    __shared__ int smOk[kPassKeys];
-    // cache policy of the direct loads (the instruction's nt bit = 2): gathered rows are touched once per call
-    // and should not displace what the neighbouring kernels keep in L2 (batch 64 x 32768: 158 -> 136 us); for
-    // the sweep over every key it makes no difference to the sweep and slows the pooling pass that follows
-    constexpr int kPolicy = GATHER ? 2 : 0;
-
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int q = lane & 31, h = lane >> 5;
-    const int b = blockIdx.z, hk = blockIdx.y, chunk_id = blockIdx.x;
-    const int n_chunks = plan.n_chunks, G = s.G;
-
-    const int L = bounded_len(a.seqlens[b], a.max_seqlen);
-    int n_rows = L;
-    if constexpr (GATHER) {
-        n_rows = a.k_per_seq[b];
-        n_rows = n_rows < a.k_max ? n_rows : a.k_max;
-        if (L <= 0 || n_rows < 0) n_rows = 0;
-    } else {
-        if (chunk_id == 0 && a.hist11) {   // pass 2 accumulates the Top-k histogram of this (b, hk): clear it here
-            uint32_t* hg = a.hist11 + ((int64_t)b * s.Hkv + hk) * 2048;
-            for (int i = threadIdx.x; i < 2048; i += kMB) hg[i] = 0u;
-        }
-    }
-    const int chunk = GATHER ? mfma_rows_per_chunk(n_rows, n_chunks) : plan.chunk;
-    const int begin = chunk_id * chunk;
-    const int end = (begin + chunk < n_rows) ? begin + chunk : n_rows;
-    const int64_t part_base = ((int64_t)(b * s.Hq + hk * G)) * n_chunks + chunk_id;
-    if (begin >= end) {   // an empty chunk: mark it for the merge (and define the output of an empty set)
-        if ((int)threadIdx.x < G) {
-            float* ml = a.part_ml + (part_base + (int64_t)threadIdx.x * n_chunks) * 2;
-            ml[0] = -INFINITY;
-            ml[1] = 0.f;
-        }
-        if (n_chunks == 1) {
-            for (int e = threadIdx.x; e < G * D; e += kMB) {
-                bf16_t* o = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)(hk * G + e / D) * s.o_stride[2] + e % D;
-                *o = 0;
-            }
-        }
-        return;
-    }
-
-    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
-    const unsigned char* Vb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.v) + b * s.kv_stride[0] + hk * s.kv_stride[1]);
-    const uint64_t row_bytes = (uint64_t)s.kv_stride[2] * 2u;
-    const int32_t* idx = nullptr;
-    if constexpr (GATHER) {
-        int src = a.head_map ? a.head_map[hk] : hk;
-        src = src < 0 ? 0 : (src >= a.n_src_heads ? a.n_src_heads - 1 : src);
-        idx = a.idx + ((int64_t)b * a.n_src_heads + src) * a.k_max;
-    }
-
-    // staging role of this thread: 16-byte piece pp of the rows r0, r0 + RPP, ... of a pass; the piece it
-    // fetches is the one the swizzled tile layout wants at that position
-    const int r0 = threadIdx.x / PPR, pp = threadIdx.x % PPR;
-    const uint32_t koff = (uint32_t)((pp ^ ((D == 128) ? (r0 & 15) : ((r0 >> 1) & 7))) << 4);
-    const uint32_t voff = (uint32_t)((pp ^ ((D == 128) ? ((r0 & 3) << 2) : (((r0 >> 1) & 1) << 2))) << 4);
-
-    // query fragments (B operand of S^T = K Q^T): column = head q of the group (zero beyond G)
-    bf16x8_t qf[KSTEPS];
-    {
-        const bf16_t* qp = reinterpret_cast<const bf16_t*>(a.q) + b * s.q_stride[0] + (int64_t)(hk * G + q) * s.q_stride[2];
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (q < G) raw = *reinterpret_cast<const uint4*>(qp + kk * 16 + h * 8);
-            qf[kk] = __builtin_bit_cast(bf16x8_t, raw);
-        }
-    }
-    const float c = s.scale_log2;
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x16_t acc_o[DBLK];
-#pragma unroll
-    for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
-    const int key0 = w * kWaveKeys + perm_key(q);
-
-    // the rows of a pass: positions begin .. end of the chunk, or (gather) the entries of the index list at
-    // those positions, fetched one pass ahead so that a pass waits for its rows only, not for its indices first
-    auto rows_of = [&](int j0, int* rows) {
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const int j = j0 + i * RPP + r0;
-            if constexpr (GATHER) {
-                const int row = j < end ? idx[j] : -1;
-                rows[i] = (row >= 0 && row < L) ? row : -1;
-            } else {
-                rows[i] = j < end ? j : -1;
-            }
-        }
-    };
-    int rows[PASSES];
-    rows_of(begin, rows);
-    for (int j0 = begin; j0 < end; j0 += kPassKeys) {
-        // ---- bring this pass's rows into the tiles
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const uint64_t off = (uint64_t)(rows[i] < 0 ? 0 : rows[i]) * row_bytes;
-            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + off + koff), (lds_ptr_t)(smK + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
-            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + off + voff), (lds_ptr_t)(smV + (i * kMB + w * kWave) * 16), 16, 0, kPolicy);
-            if (pp == 0) smOk[i * RPP + r0] = rows[i] >= 0;
-        }
-        rows_of(j0 + kPassKeys, rows);   // past the end: all -1, no loads
-        wait_vmem();
-        __syncthreads();
-
-        // ---- S^T for this wave's 32 keys, masks for slots without a key
-        f32x16_t s0;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s0[r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk)
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(smK + k_off<D>(key0, kk * 2 + h)), qf[kk], s0, 0, 0, 0);
-        float mx = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int slot = w * kWaveKeys + (r >> 3) * 16 + h * 8 + (r & 7);
-            s0[r] = smOk[slot] ? s0[r] * c : -INFINITY;
-            mx = fmaxf(mx, s0[r]);
-        }
-        if constexpr (STORE) {   // a lane holds two runs of eight consecutive keys of its head
-            if (q < G) {
-                float* lg = a.logits + ((int64_t)b * s.Hq + hk * G + q) * a.logit_pitch;
-#pragma unroll
-                for (int r8 = 0; r8 < 16; r8 += 8) {
-                    const int j = j0 + w * kWaveKeys + (r8 >> 3) * 16 + h * 8;
-                    if (j + 8 <= end) {
-                        *reinterpret_cast<float4*>(lg + j) = make_float4(s0[r8], s0[r8 + 1], s0[r8 + 2], s0[r8 + 3]);
-                        *reinterpret_cast<float4*>(lg + j + 4) = make_float4(s0[r8 + 4], s0[r8 + 5], s0[r8 + 6], s0[r8 + 7]);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (j + e < end) lg[j + e] = s0[r8 + e];
-                    }
-                }
-            }
-        }
-        mx = half_swap_max(mx);
-        // ---- online softmax, base 2; this lane owns head q (the other half-wave holds the other keys)
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {   // wave-uniform: rescale only when a maximum moved
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);   // 0 while m_run is -inf
-            l_run *= alpha;
-#pragma unroll
-            for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
-            m_run = m_new;
-        }
-        float rs = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            s0[r] = __builtin_amdgcn_exp2f(s0[r] - m_safe);
-            rs += s0[r];
-        }
-        l_run += half_swap_sum(rs);
-        // ---- O^T += V^T P^T
-        const bf16x8_t pf0 = pack_p(s0, 0), pf1 = pack_p(s0, 8);
-#pragma unroll
-        for (int i = 0; i < DBLK; ++i) {
-            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys), pf0, acc_o[i], 0, 0, 0);
-            acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt_frag<D>(smV, i, w * kWaveKeys + 16), pf1, acc_o[i], 0, 0, 0);
-        }
-        __syncthreads();   // the tiles are free for the next pass
-    }
-
-    // ---- merge the four waves' states through LDS (the tiles are free), fixed order
-    float* sm_m = reinterpret_cast<float*>(smV);                 // [kMW][32]
-    float* sm_l = sm_m + kMW * 32;                               // [kMW][32]
-    float* sm_acc = reinterpret_cast<float*>(smK);               // [kMW][G][D], at most 4 * 32 * 128 floats = 64 KB > tile: G <= 16 here
-    if (h == 0) { sm_m[w * 32 + q] = m_run; sm_l[w * 32 + q] = l_run; }
-    if (q < G) {
-#pragma unroll
-        for (int i = 0; i < DBLK; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int d = i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                sm_acc[(w * G + q) * D + d] = acc_o[i][r];
-            }
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < G * D; e += kMB) {
-        const int g = e / D, col = e % D;
-        float M = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < kMW; ++t) M = fmaxf(M, sm_m[t * 32 + g]);
-        const float Ms = (M == -INFINITY) ? 0.f : M;
-        float lsum = 0.f, val = 0.f;
-#pragma unroll
-        for (int t = 0; t < kMW; ++t) {
-            const float wgt = __builtin_amdgcn_exp2f(sm_m[t * 32 + g] - Ms);
-            lsum = fmaf(wgt, sm_l[t * 32 + g], lsum);
-            val = fmaf(wgt, sm_acc[(t * G + g) * D + col], val);
-        }
-        const int hq = hk * G + g;
-        const int64_t pidx = ((int64_t)(b * s.Hq + hq)) * n_chunks + chunk_id;
-        if (n_chunks == 1) {
-            const float o = lsum > 0.f ? val / lsum : 0.f;
-            bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
-            *op = (bf16_t)f32_to_bf16_bits(o);
-        } else {
-            a.part_acc[pidx * D + col] = val;
-        }
-        if (col == 0) {
-            a.part_ml[pidx * 2 + 0] = M;
-            a.part_ml[pidx * 2 + 1] = lsum;
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------------------------------
-// The anchor's sweep over every key without P.V (Sec. 3.6 pass 1: logits and softmax statistics), staged
-// through registers.  The tile kernel above can keep no more bytes in flight than its LDS tiles hold
-// and couples its waves with two barriers per pass.  Here every wave streams on its own: it loads 32
-// key rows with coalesced 16-byte loads into registers (two register buffers, the next batch in flight
-// while the current one is used), copies them into a wave-private LDS tile in the swizzled operand
-// layout, reads the A fragments back and runs the same S^T = K Q^T product.  No workgroup barrier in
-// the loop, the vector ALU only sees 16 scores per lane and batch, and the matrix unit is idle most of
-// the time: the kernel is as memory-bound as the vector-ALU sweep with one head per key head.
+// The anchor's sweep over every key without P.V (Sec. 3.6 pass 1: logits and softmax statistics).
+//   S^T[32 keys x 32 heads] = K[32 keys x d] Q^T[d x 32 heads]   (d/16 x v_mfma_f32_32x32x16_bf16 per batch)
+// A wave loads 32 key rows into one of two register buffers, copies them into its LDS tile in the swizzled
+// operand layout of the prefill kernels, reads the A fragments back and multiplies.  The vector ALU only
+// sees 16 scores per lane and batch and the matrix unit is idle most of the time: the kernel is as
+// memory-bound as the vector-ALU sweep with one head per key head.  (Staging through LDS tiles filled by
+// direct global-to-LDS loads, as the prefill kernels do, was 10 % slower here: a compute unit's LDS holds
+// fewer bytes in flight than its registers, and the waves of a workgroup wait for each other.)
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 template <int D>
@@ -415,11 +189,9 @@ __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, Deco
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Attention with P.V staged through registers, 128-wide heads: gather mode (reuse layers, anchor pass 4)
-// and the sweep over every key with dense output.
-// Same idea as the sweep above - every wave streams on its own, 32 K rows and 32 V rows per batch in
-// registers (two buffers for K, one for V), a wave-private LDS tile, no barrier in the loop - with P.V on
-// top.  To fit the buffers (96 registers) the products use the 16-wide tile, v_mfma_f32_16x16x32_bf16:
+// Attention with P.V: gather mode (reuse layers, anchor pass 4) and the sweep over every key with dense
+// output.  32 K rows and 32 V rows per batch in registers (two buffers for K, one for V).  To fit the
+// buffers (96 registers for 128-wide heads) the products use the 16-wide tile, v_mfma_f32_16x16x32_bf16:
 // the heads of the group are padded to 16 columns instead of 32, so the output accumulators take 32
 // registers instead of 64 and the query fragments 16 instead of 32:
 //   S^T[16 keys x 16 heads] = K[16 keys x 32 d] Q^T[32 d x 16 heads]        (4 per tile, 2 tiles per batch)
@@ -432,25 +204,34 @@ __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, Deco
 // computed (LDS operations of a wave execute in order).
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-// K rows in the tile: 16-byte chunks XOR-swizzled by the S-tile row of the slot, so that the 16 rows
-// one fragment read touches (same chunk) fall into 16 different chunk positions
+// K rows in the tile: 16-byte chunks XOR-swizzled by the S-tile row rho of the slot, so that the 16 rows one
+// fragment read touches (same chunk) fall into different banks: 16 chunk positions for 256-byte rows; for
+// 128-byte rows rho/2 picks one of 8 positions and the rows rho, rho+1 lie in different halves of a 256-byte window
+template <int D>
 __device__ __forceinline__ int k16_off(int slot, int chunk) {
     const int rho = ((slot >> 3) << 2) | (slot & 3);
-    return slot * 256 + ((chunk ^ rho) << 4);
+    const int f = (D == 128) ? rho : (rho >> 1);
+    return slot * (D * 2) + ((chunk ^ f) << 4);
 }
 // V rows in the tile: 32-byte pieces (16 d) XOR-swizzled so that the 16 rows one transposing read touches
-// (slots g*8 + m, g = 0..3, m = 0..3, same piece) spread over all eight piece positions
-__device__ __forceinline__ int v16_swz(int slot) { return (slot & 3) | (((slot >> 3) & 1) << 2); }
+// (slots g*8 + m, g = 0..3, m = 0..3, same piece) spread evenly over the eight piece positions of a
+// 256-byte window
+template <int D>
+__device__ __forceinline__ int v16_swz(int slot) {
+    return (D == 128) ? ((slot & 3) | (((slot >> 3) & 1) << 2)) : ((slot ^ (slot >> 3)) & 3);
+}
+template <int D>
 __device__ __forceinline__ int v16_off(int slot, int d) {
-    return slot * 256 + ((((d >> 4) ^ v16_swz(slot))) << 5) + ((d & 15) << 1);
+    return slot * (D * 2) + ((((d >> 4) ^ v16_swz<D>(slot))) << 5) + ((d & 15) << 1);
 }
 // V^T fragment: row = d index dt*16 + lane%16, keys (lane/16)*8 + 0..7 (see vt_frag in mfma_tiles.h)
+template <int D>
 __device__ __forceinline__ bf16x8_t vt16_frag(const unsigned char* tile, int dt) {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, cb = lane & 3, m = (lane >> 2) & 3;
     typedef s16x4_t __attribute__((address_space(3))) * lds_v4;
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + v16_off(g * 8 + m, dt * 16 + cb * 4)));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + v16_off(g * 8 + 4 + m, dt * 16 + cb * 4)));
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + v16_off<D>(g * 8 + m, dt * 16 + cb * 4)));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + v16_off<D>(g * 8 + 4 + m, dt * 16 + cb * 4)));
     struct { s16x4_t lo, hi; } both = {lo, hi};
     return __builtin_bit_cast(bf16x8_t, both);
 }
@@ -465,9 +246,12 @@ __device__ __forceinline__ float quad_rows_sum(float x) {
 
 // GATHER: rows from the index list; otherwise rows begin .. end of a fixed-length chunk, logits stored (the sweep
 // with dense output).
-template <bool GATHER>
+template <int D, bool GATHER>
 __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
-    constexpr int D = 128, KS = D / 32, DT = D / 16, NI = 8, RPI = 4;
+    constexpr int KS = D / 32, DT = D / 16;
+    constexpr int LPR = D / 8;                 // lanes (16-byte pieces) per row
+    constexpr int RPI = kWave / LPR;           // rows per load instruction
+    constexpr int NI = kWaveKeys / RPI;        // load instructions per batch of 32 keys
     __shared__ __align__(16) unsigned char smT[kMW][kWaveKeys * D * 2];
     __shared__ float sm_m[kMW][16], sm_l[kMW][16];
 
@@ -536,7 +320,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
     for (int i = 0; i < DT; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     unsigned char* tile = smT[w];
-    const int lr = lane >> 4, lc = lane & 15;   // row within a load instruction, 16-byte piece of the row
+    const int lr = lane / LPR, lc = lane % LPR;   // row within a load instruction, 16-byte piece of the row
     const int v_piece = lc >> 1, v_half = (lc & 1) << 4;
 
     // list entries j0 .. j0+31 of this wave's batch (lanes 32..63 repeat them); -1 = nothing to attend to
@@ -563,7 +347,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
     auto attend = [&](const u32x4_t* kb, int rows, int next_rows, bool have_next, int j0) {
         const uint32_t ok = (uint32_t)__builtin_amdgcn_ballot_w64(rows >= 0);   // bit = key slot (lanes 0..31)
 #pragma unroll
-        for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4_t*>(tile + k16_off(i * RPI + lr, lc)) = kb[i];
+        for (int i = 0; i < NI; ++i) *reinterpret_cast<u32x4_t*>(tile + k16_off<D>(i * RPI + lr, lc)) = kb[i];
         f32x4_t st[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -571,7 +355,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
             const int slot = ((hd >> 2) << 3) + t * 4 + (hd & 3);   // sigma(t, rho = hd)
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk)
-                st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_frag(tile + k16_off(slot, kk * 4 + rg)), qf[kk], st[t], 0, 0, 0);
+                st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_frag(tile + k16_off<D>(slot, kk * 4 + rg)), qf[kk], st[t], 0, 0, 0);
         }
         float p[8];
         float mx = -INFINITY;
@@ -618,12 +402,12 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int slot = i * RPI + lr;
-            *reinterpret_cast<u32x4_t*>(tile + slot * 256 + ((v_piece ^ v16_swz(slot)) << 5) + v_half) = vb[i];
+            *reinterpret_cast<u32x4_t*>(tile + slot * (D * 2) + ((v_piece ^ v16_swz<D>(slot)) << 5) + v_half) = vb[i];
         }
         if (have_next) issue(vb, Vb, next_rows);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt16_frag(tile, dt), pf, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt16_frag<D>(tile, dt), pf, acc[dt], 0, 0, 0);
     };
 
     // the workgroup walks its chunk 128 list entries at a time, 32 per wave; index entries are fetched two
@@ -692,8 +476,8 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
     if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (s.D == 128) hipLaunchKernelGGL(decode_rows_mfma16_kernel<true>, grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_mfma_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
+    if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, true>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, true>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 
@@ -704,10 +488,10 @@ hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, con
     if ((a.logit_pitch & 3) || (reinterpret_cast<uintptr_t>(a.logits) & 15) || (plan.chunk & 7)) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
     if (s.D == 128) {
-        if (with_v) hipLaunchKernelGGL(decode_rows_mfma16_kernel<false>, grid, block, 0, st, s, plan, a);
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, false>), grid, block, 0, st, s, plan, a);
         else hipLaunchKernelGGL((decode_sweep_mfma_kernel<128>), grid, block, 0, st, s, plan, a);
     } else {
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma_kernel<64, false, true>), grid, block, 0, st, s, plan, a);
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, false>), grid, block, 0, st, s, plan, a);
         else hipLaunchKernelGGL((decode_sweep_mfma_kernel<64>), grid, block, 0, st, s, plan, a);
     }
     return hipGetLastError();
