@@ -9,7 +9,7 @@
 //  decode_merge_kernel  combines per-chunk (max, sum, acc) triples into the output.
 //  decode_pool_kernel   anchor pass 2: softmax from logits + statistics, mean over the GQA
 //                       group (Sec. 3.4).
-//  (bf16 groups of eight heads and more run both modes on the matrix unit instead:
+//  (bf16 groups of four heads and more run both modes on the matrix unit instead:
 //  decode_mfma_kernels.hip.)
 //
 // Data movement: a K or V row is 128..512 bytes.  LPR = row_bytes/16 adjacent lanes read one

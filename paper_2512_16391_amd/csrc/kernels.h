@@ -49,7 +49,7 @@ struct DecodeRowsArgs {
 hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a,
                               bool gather, bool with_v, bool store_logits, hipStream_t st);
 
-// Gather mode on the matrix unit (bf16, head dimension 128, up to 16 heads per key head): same plan,
+// Gather mode on the matrix unit (bf16, head dimension 64 or 128, up to 16 heads per key head): same plan,
 // arguments and partial-result format as launch_decode_rows(gather = true).
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st);
 // Stream mode with stored logits on the matrix unit, same restrictions; same plan, arguments and results as
