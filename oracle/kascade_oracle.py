@@ -416,7 +416,7 @@ def pool_query_vectors(rows, storage):
     query vectors [n, d].  The average is itself a query the attention kernels
     consume, so it exists in the tensors' storage type: accumulated in float32
     in the order given, divided by n in float32, then rounded to `storage`
-    ("fp32": as is, "bf16": nearest even).  The rounding decides index sets, so
+    ("fp32": as is, "bf16" / "fp16": nearest even).  The rounding decides index sets, so
     it is taken here exactly as on the device.  Returns float64 [d]."""
     rows = np.asarray(rows, dtype=np.float32)
     acc = np.zeros(rows.shape[1], dtype=np.float32)
@@ -425,8 +425,10 @@ def pool_query_vectors(rows, storage):
     mean = acc / np.float32(rows.shape[0])
     if storage == "bf16":
         mean = round_to_bf16(mean)
+    elif storage == "fp16":
+        mean = mean.astype(np.float16).astype(np.float32)   # IEEE binary16, ties to even
     elif storage != "fp32":
-        raise ValueError("storage is 'fp32' or 'bf16'")
+        raise ValueError("storage is 'fp32', 'bf16' or 'fp16'")
     return mean.astype(np.float64)
 
 

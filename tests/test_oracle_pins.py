@@ -520,6 +520,31 @@ def test_pooled_query_is_the_rounded_mean():
     np.testing.assert_array_equal(ko.pool_query_vectors(v[None], "fp32"), v)
 
 
+def test_pooled_query_in_fp16_storage():
+    """binary16: 10 fraction bits, ties to even, largest finite value 65504; expectations written out from
+    the format's definition, not taken from a conversion routine."""
+    one = np.zeros((1, 6))
+    one[0] = [1.0 + 2.0 ** -11,            # exact tie above 1: the even neighbour is 1
+              1.0 + 3.0 * 2.0 ** -11,      # tie between 1 + 2^-10 (odd) and 1 + 2^-9 (even)
+              1.0 + 2.0 ** -11 + 2.0 ** -20,   # just above the tie
+              -0.3333333432674408,         # float32(-1/3): below 0.5 the step is 2^-12 ... here 2^-12
+              2.0 ** -25,                  # half the smallest subnormal: tie, the even neighbour is 0
+              1000.4]                      # step 0.5 between 512 and 1024
+    got = ko.pool_query_vectors(one, "fp16")[...]
+    want = [1.0, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10, -(1365.0 / 4096.0), 0.0, 1000.5]
+    np.testing.assert_array_equal(got, np.array(want))
+    # the mean of rows, then one rounding: within half a step of the exact mean, and representable
+    r = rng(73)
+    rows = r.standard_normal((12, 16)).astype(np.float32).astype(np.float64)
+    exact = rows.mean(axis=0)
+    pf = ko.pool_query_vectors(rows, "fp16")
+    assert np.all(np.abs(pf - exact) <= np.abs(exact) * 2.0 ** -11 + 1e-6)
+    m, e = np.frexp(pf)
+    assert np.all((m * 2048.0) == np.round(m * 2048.0))        # 11 significant bits
+    with pytest.raises(ValueError):
+        ko.pool_query_vectors(rows, "fp8")
+
+
 def test_presoftmax_decode_is_softmax_of_the_mean_logits():
     r = rng(72)
     Hq, Hkv, d, L, k = 8, 2, 16, 70, 9
