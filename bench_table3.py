@@ -9,7 +9,8 @@ layer-0 anchor plus its merge; prefill: the causal flash sweep of the layer-0 an
 slightly MORE than a plain dense kernel - they also store logits / row statistics - so the
 speed-ups printed here are upper-bounded by that).  Shapes follow the paper: Llama-3.1-8B
 attention (32 query heads, 8 key heads, head dimension 128), decode batch 64 (32 at 524288),
-prefill batch 1, Top-k 10 % (plus 20 % and 30 % at one length); bf16, seeded synthetic inputs.
+prefill batch 1, Top-k 10 % (plus 20 % and 30 % at one length); bf16 (or fp16 with --dtype fp16, the
+precision of the paper's own timings), seeded synthetic inputs.
 
 Prints one JSON line per row and a text table at the end.  Not part of bench.py's contract.
 """
@@ -52,9 +53,9 @@ def kernel_ms(binding, torch, fn, names, reps):
     return sum(prof[n][0] for n in names if n in prof) / reps
 
 
-def decode_row(torch, binding, workloads, dev, L, B, permille, reps):
+def decode_row(torch, binding, workloads, dev, L, B, permille, reps, dtype):
     k = workloads.budget(L, permille)
-    wl = workloads.make_decode_workload(f"table3-decode-L{L}-B{B}", 7, 1, B, 32, 8, 128, torch.bfloat16, [L] * B,
+    wl = workloads.make_decode_workload(f"table3-decode-L{L}-B{B}", 7, 1, B, 32, 8, 128, dtype, [L] * B,
                                         [k] * B, 1024, 0.85, device=dev, keep_hitters=False)
     a = wl.layers[0]
     seqlens = torch.full((B,), L, dtype=torch.int32, device=dev)
@@ -75,8 +76,8 @@ def decode_row(torch, binding, workloads, dev, L, B, permille, reps):
             "reuse_GBps": kv_bytes * k / L / (t_r * 1e-3) / 1e9}
 
 
-def prefill_row(torch, binding, workloads, dev, S, permille, reps, T=32):
-    wl = workloads.make_prefill_workload(f"table3-prefill-S{S}", 8, 1, S, 32, 8, 128, torch.bfloat16, T, permille, 256,
+def prefill_row(torch, binding, workloads, dev, S, permille, reps, dtype, T=32):
+    wl = workloads.make_prefill_workload(f"table3-prefill-S{S}", 8, 1, S, 32, 8, 128, dtype, T, permille, 256,
                                          64, 0.80, device=dev)
     a = wl.layers[0]
     off = wl.idx_offsets
@@ -114,6 +115,7 @@ def main():
     ap.add_argument("--max-decode-context", type=int, default=524288)
     ap.add_argument("--max-prefill-context", type=int, default=131072)
     ap.add_argument("--quick", action="store_true", help="10 %% rows only")
+    ap.add_argument("--dtype", choices=["bf16", "fp16"], default="bf16", help="storage type (the paper's own timings are fp16)")
     args = ap.parse_args()
     import torch
     from paper_2512_16391_amd import binding, workloads
@@ -122,6 +124,7 @@ def main():
         sys.exit(2)
     binding.load_library()
     dev = torch.device("cuda:0")
+    dtype = torch.float16 if args.dtype == "fp16" else torch.bfloat16
     rows = []
     decode_cases = [(L, 64 if L < 524288 else 32, 100) for L in (8192, 16384, 32768, 65536, 131072, 262144, 524288)
                     if L <= args.max_decode_context]
@@ -129,7 +132,7 @@ def main():
         decode_cases += [(131072, 64, 200), (131072, 64, 300)]
     for L, B, pm in decode_cases:
         reps = 10 if L * B <= 1 << 22 else 4
-        row = finish(decode_row(torch, binding, workloads, dev, L, B, pm, reps), PAPER_DECODE)
+        row = finish(decode_row(torch, binding, workloads, dev, L, B, pm, reps, dtype), PAPER_DECODE)
         rows.append(row)
         print(json.dumps(row), flush=True)
         torch.cuda.empty_cache()
@@ -142,7 +145,7 @@ def main():
         S, pm = case[0], case[1]
         T = case[2] if len(case) > 2 else 32
         reps = 5 if S <= 32768 else (2 if S <= 131072 else 1)
-        row = finish(prefill_row(torch, binding, workloads, dev, S, pm, reps, T), PAPER_PREFILL if T == 32 else {})
+        row = finish(prefill_row(torch, binding, workloads, dev, S, pm, reps, dtype, T), PAPER_PREFILL if T == 32 else {})
         rows.append(row)
         print(json.dumps(row), flush=True)
         torch.cuda.empty_cache()

@@ -45,7 +45,7 @@ enum {
     KASCADE_HIP_ERROR = -5            /* a launch failed; hipGetLastError() has the detail    */
 };
 
-enum { KASCADE_F32 = 0, KASCADE_BF16 = 1 };
+enum { KASCADE_F32 = 0, KASCADE_BF16 = 1, KASCADE_F16 = 2 };
 
 /* out_mode of the anchor calls (Sec. 3.6): layer 0 returns dense attention
  * (Sec. 3.1), every other anchor returns Top-k attention over its own fresh set. */
@@ -63,10 +63,10 @@ enum {
 typedef struct {
     int32_t batch;          /* sequences (decode), at most 65535; must be 1 for prefill  */
     int32_t n_q_heads;      /* Hq                                                        */
-    int32_t n_kv_heads;     /* Hkv, divides Hq; G = Hq/Hkv in {1,2,4,8}; bf16 decode:    *
+    int32_t n_kv_heads;     /* Hkv, divides Hq; G = Hq/Hkv in {1,2,4,8}; 16-bit decode:  *
                              * any G <= 16                                                */
     int32_t head_dim;       /* d in {64, 128}                                            */
-    int32_t dtype;          /* KASCADE_F32 or KASCADE_BF16; Q, K, V, O share it          */
+    int32_t dtype;          /* KASCADE_F32, KASCADE_BF16 or KASCADE_F16; Q, K, V, O share it */
     float   softmax_scale;  /* 0 -> 1/sqrt(head_dim) (Eq. 1)                             */
     int64_t q_stride[3];    /* batch, token, head   (decode ignores the token stride)    */
     int64_t kv_stride[3];   /* batch, head, token   (covers [B,Hkv,L,d] and [B,L,Hkv,d]) */
@@ -117,7 +117,7 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
  * post-softmax weight (row normalisers include the diagonal keys).  k_per_tile[t]
  * <= t*T keys are selected per key head; the diagonal block t*T..i is always
  * attended on top, causally.
- *   q [S,Hq,d] per q_stride;  k, v [Hkv,S,d] per kv_stride; bf16 only, T*G a multiple of 128 (the
+ *   q [S,Hq,d] per q_stride;  k, v [Hkv,S,d] per kv_stride; bf16 or fp16, T*G a multiple of 128 (the
  *   paper's tile is T*G = 128 rows), and the rows of one key head must span less than 4 GiB
  *   (S * kv_stride[2] * 2 bytes), else KASCADE_UNSUPPORTED
  *   k_per_tile  [n_tiles] int32 (device), idx_offsets [n_tiles+1] int64 (device),
@@ -270,7 +270,7 @@ int kascade_head_map(int32_t n_samples, int32_t n_kv_heads, int32_t n_heads_a, c
  * Layer importance (Sec. 3.3): w_out[r] = 1 - cosine similarity of row r of x (input of a
  * layer's attention block) and row r of y (its output); fp32 accumulation.  Averaging the rows
  * of a layer gives the weight passed to kascade_select_anchor_layers.
- *   x, y [n_rows,n_cols] of `dtype` (KASCADE_F32 / KASCADE_BF16), row strides in elements;
+ *   x, y [n_rows,n_cols] of `dtype` (KASCADE_F32 / KASCADE_BF16 / KASCADE_F16), row strides in elements;
  *   w_out [n_rows] fp32.  All device memory.  A zero row gives NaN.
  */
 int kascade_layer_importance(const void* x, const void* y, int64_t n_rows, int32_t n_cols,

@@ -17,7 +17,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libkascade.so")
 
 KASCADE_OK = 0
-KASCADE_F32, KASCADE_BF16 = 0, 1
+KASCADE_F32, KASCADE_BF16, KASCADE_F16 = 0, 1, 2
 KASCADE_OUT_DENSE, KASCADE_OUT_SPARSE = 0, 1
 OP_DECODE_ANCHOR, OP_DECODE_REUSE, OP_PREFILL_ANCHOR, OP_PREFILL_REUSE, OP_DECODE_POOLED = 0, 1, 2, 3, 4
 OP_PREFILL_ANCHOR_PRESOFTMAX = 5
@@ -151,6 +151,8 @@ def _dtype_code(t: torch.Tensor) -> int:
         return KASCADE_F32
     if t.dtype == torch.bfloat16:
         return KASCADE_BF16
+    if t.dtype == torch.float16:
+        return KASCADE_F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -395,7 +397,7 @@ def kascade_head_map(sim):
 
 
 def kascade_layer_importance(x, y):
-    """x, y [n_rows,n_cols] (fp32 or bf16, device, unit column stride).  Returns w [n_rows] fp32."""
+    """x, y [n_rows,n_cols] (fp32, bf16 or fp16, device, unit column stride).  Returns w [n_rows] fp32."""
     _need_gpu(x, y)
     if x.shape != y.shape or x.dim() != 2 or x.dtype != y.dtype or x.stride(1) != 1 or y.stride(1) != 1:
         raise ValueError("x and y must be 2-D tensors of one shape and dtype with contiguous rows")

@@ -39,12 +39,12 @@ int check_desc(const kascade_desc* d, bool prefill) {
     // sequences and key heads are grid dimensions y / z of the decode kernels
     if (d->batch > 65535 || d->n_kv_heads > 65535) return KASCADE_UNSUPPORTED;
     if (d->head_dim != 64 && d->head_dim != 128) return KASCADE_UNSUPPORTED;
-    if (d->dtype != KASCADE_F32 && d->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    if (d->dtype != KASCADE_F32 && d->dtype != KASCADE_BF16 && d->dtype != KASCADE_F16) return KASCADE_UNSUPPORTED;
     // heads per key head: the vector-ALU kernels are built for 1, 2, 4 and 8; the matrix-unit decode kernels
     // (bf16) take any group up to 16; prefill workgroups hold 128 / G whole tokens
     const int G = d->n_q_heads / d->n_kv_heads;
     const bool pow2 = G == 1 || G == 2 || G == 4 || G == 8;
-    const bool any_group = !prefill && d->dtype == KASCADE_BF16 && G <= 16;
+    const bool any_group = !prefill && d->dtype != KASCADE_F32 && G <= 16;
     if (!pow2 && !any_group) return KASCADE_UNSUPPORTED;
     if (!(d->softmax_scale >= 0.f) || isinf(d->softmax_scale)) return KASCADE_INVALID_ARG;
     const int64_t es = d->dtype == KASCADE_F32 ? 4 : 2;
@@ -97,7 +97,7 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
 // serves groups of eight heads is fastest with the same split.  Other shapes keep that older rule.
 DecodePlan plan_gather(const Shape& s, int64_t k_max) {
     const int pairs = s.B * s.Hkv;
-    if (s.dtype == 1 && s.D == 128 && !getenv("KASCADE_GATHER_CHUNK")) {
+    if (s.dtype != 0 && s.D == 128 && !getenv("KASCADE_GATHER_CHUNK")) {
         int64_t n = 512 / pairs;
         n = n < 1 ? 1 : (n > 64 ? 64 : n);
         DecodePlan p;
@@ -245,7 +245,8 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // 161 -> 101 us, 385 -> 194 us; 64-wide heads, four heads: gather 10.9 -> 8.2 us) and equal or a little behind
 // below that.  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
 bool use_matrix_unit(const Shape& s) {
-    if (s.dtype != 1 || s.G > 16) return false;
+    if (s.dtype == 0 || s.G > 16) return false;
+    if (s.dtype == 2) return true;   // fp16 exists on the matrix unit only
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
     bool mfma = s.G >= 4;
     if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
@@ -555,7 +556,7 @@ int check_prefill(const kascade_desc* desc, const void* q, const void* k, const 
     if (!q || !k || !v || !k_per_tile || !idx_offsets || !out) return KASCADE_INVALID_ARG;
     if (seqlen <= 0 || T <= 0 || idx_total < 0) return KASCADE_INVALID_ARG;
     if (idx_total > 0 && !idx) return KASCADE_INVALID_ARG;
-    if (desc->dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    if (desc->dtype != KASCADE_BF16 && desc->dtype != KASCADE_F16) return KASCADE_UNSUPPORTED;
     // a query tile is T tokens times the G heads of a key head; a workgroup owns 128 of those
     // (token, head) rows, so a tile is one or several whole workgroups
     if (((int64_t)T * (desc->n_q_heads / desc->n_kv_heads)) % 128 != 0) return KASCADE_UNSUPPORTED;
@@ -782,7 +783,7 @@ int kascade_layer_importance(const void* x, const void* y, int64_t n_rows, int32
     if (!x || !y || !w_out || n_rows <= 0 || n_cols <= 0) return KASCADE_INVALID_ARG;
     if (n_rows > (int64_t)0x7fffffff * 4) return KASCADE_INVALID_ARG;
     if (x_row_stride < n_cols || y_row_stride < n_cols) return KASCADE_INVALID_ARG;
-    if (dtype != KASCADE_F32 && dtype != KASCADE_BF16) return KASCADE_UNSUPPORTED;
+    if (dtype != KASCADE_F32 && dtype != KASCADE_BF16 && dtype != KASCADE_F16) return KASCADE_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return timed(K_IMPORTANCE, stream, [&] {
         return launch_importance(dtype, x, y, n_rows, n_cols, x_row_stride, y_row_stride, w_out, stream);

@@ -73,8 +73,6 @@ __global__ __launch_bounds__(kWave) void head_map_kernel(int B, int Hkv, int Ha,
     if (lane == 0) head_map_out[hk] = arg;
 }
 
-__device__ __forceinline__ float widen1(float v) { return v; }
-__device__ __forceinline__ float widen1(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
 // One wave per row: 1 - <x, y> / (|x| |y|), fp32 accumulation.
 template <typename T>
@@ -144,7 +142,7 @@ __global__ void pool_queries_kernel(const T* q, int64_t unit_stride, int64_t tok
     }
     const float mean = acc / (float)((hi - lo) * G);
     T* dst = qbar + ((int64_t)unit * Hkv + hk) * D + c;
-    if constexpr (sizeof(T) == 4) *dst = mean; else *dst = (T)f32_to_bf16_bits(mean);
+    *dst = narrow<T>(mean);
 }
 
 }  // namespace
@@ -156,9 +154,12 @@ hipError_t launch_pool_queries(int dtype, const void* q, int64_t unit_stride, in
     if (dtype == 0)
         hipLaunchKernelGGL(pool_queries_kernel<float>, grid, block, 0, st, (const float*)q, unit_stride, token_stride,
                            head_stride, G, tokens_per_unit, n_tokens, (float*)qbar, Hkv, D, tile_lens);
-    else
+    else if (dtype == 1)
         hipLaunchKernelGGL(pool_queries_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)q, unit_stride, token_stride,
                            head_stride, G, tokens_per_unit, n_tokens, (bf16_t*)qbar, Hkv, D, tile_lens);
+    else
+        hipLaunchKernelGGL(pool_queries_kernel<f16_t>, grid, block, 0, st, (const f16_t*)q, unit_stride, token_stride,
+                           head_stride, G, tokens_per_unit, n_tokens, (f16_t*)qbar, Hkv, D, tile_lens);
     return hipGetLastError();
 }
 
@@ -187,8 +188,11 @@ hipError_t launch_importance(int dtype, const void* x, const void* y, int64_t n_
     if (dtype == 0)
         hipLaunchKernelGGL(importance_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)y, n_rows, n_cols,
                            x_stride, y_stride, w_out);
-    else
+    else if (dtype == 1)
         hipLaunchKernelGGL(importance_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)y, n_rows,
+                           n_cols, x_stride, y_stride, w_out);
+    else
+        hipLaunchKernelGGL(importance_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)y, n_rows,
                            n_cols, x_stride, y_stride, w_out);
     return hipGetLastError();
 }

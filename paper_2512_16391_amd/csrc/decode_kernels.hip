@@ -75,7 +75,7 @@ __device__ __forceinline__ void merge_streams(const Shape& s, const DecodeRowsAr
             if (WITH_V && n_chunks == 1) {
                 const float o = lsum > 0.f ? val / lsum : 0.f;
                 T* op = reinterpret_cast<T*>(a.out) + b * s.o_stride[0] + (int64_t)h * s.o_stride[2] + col;
-                if constexpr (sizeof(T) == 4) *op = o; else *op = (T)f32_to_bf16_bits(o);
+                *op = narrow<T>(o);
             } else if constexpr (WITH_V) {
                 a.part_acc[pidx * D + col] = val;
             }
@@ -590,7 +590,7 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(Shape s, int n_chun
 #pragma unroll
     for (int e = 0; e < CPL; ++e) {
         const float o = lsum > 0.f ? val[e] / lsum : 0.f;
-        if constexpr (sizeof(T) == 4) op[e * kWave + lane] = o; else op[e * kWave + lane] = (T)f32_to_bf16_bits(o);
+        op[e * kWave + lane] = narrow<T>(o);
     }
 }
 
@@ -747,6 +747,8 @@ hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_m
     else if (s.dtype == 0 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
     else if (s.dtype == 1 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
     else if (s.dtype == 1 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 2 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<f16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 2 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<f16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

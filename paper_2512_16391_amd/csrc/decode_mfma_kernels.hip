@@ -1,4 +1,4 @@
-// The decode row passes on the matrix unit, for bf16 caches (head dimension 64 or 128): attention over the
+// The decode row passes on the matrix unit, for bf16 and fp16 caches (head dimension 64 or 128): attention over the
 // K/V rows named by a Top-k index list (paper Sec. 3.6, reuse layers and anchor pass 4) and the
 // anchor's sweep over every key (Sec. 3.6 pass 1: logits and softmax statistics, with P.V when the
 // layer's output is dense).
@@ -45,7 +45,7 @@ __device__ __forceinline__ int mfma_rows_per_chunk(int n_rows, int n_chunks) {
 // fewer bytes in flight than its registers, and the waves of a workgroup wait for each other.)
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-template <int D>
+template <int D, bool F16>
 __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int KSTEPS = D / 16;
     constexpr int LPR = D / 8;                 // lanes (16-byte pieces) per row
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, Deco
         for (int r = 0; r < 16; ++r) s0[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk)
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(tile + k_off<D>(frag_key, kk * 2 + h)), qf[kk], s0, 0, 0, 0);
+            s0 = Mma<F16>::mma32(lds_frag(tile + k_off<D>(frag_key, kk * 2 + h)), qf[kk], s0);
         float mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -202,7 +202,6 @@ __global__ __launch_bounds__(kMB, 3) void decode_sweep_mfma_kernel(Shape s, Deco
 // lane holds (two tiles x four registers) are the key slots rg*8 .. rg*8+7: exactly its part of the
 // P^T operand.  The one LDS tile of a wave holds the K rows first and the V rows after the S tiles are
 // computed (LDS operations of a wave execute in order).
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // K rows in the tile: 16-byte chunks XOR-swizzled by the S-tile row rho of the slot, so that the 16 rows one
 // fragment read touches (same chunk) fall into different banks: 16 chunk positions for 256-byte rows; for
@@ -246,7 +245,7 @@ __device__ __forceinline__ float quad_rows_sum(float x) {
 
 // GATHER: rows from the index list; otherwise rows begin .. end of a fixed-length chunk, logits stored (the sweep
 // with dense output).
-template <int D, bool GATHER>
+template <int D, bool GATHER, bool F16>
 __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, DecodePlan plan, DecodeRowsArgs a) {
     constexpr int KS = D / 32, DT = D / 16;
     constexpr int LPR = D / 8;                 // lanes (16-byte pieces) per row
@@ -355,7 +354,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
             const int slot = ((hd >> 2) << 3) + t * 4 + (hd & 3);   // sigma(t, rho = hd)
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk)
-                st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lds_frag(tile + k16_off<D>(slot, kk * 4 + rg)), qf[kk], st[t], 0, 0, 0);
+                st[t] = Mma<F16>::mma16(lds_frag(tile + k16_off<D>(slot, kk * 4 + rg)), qf[kk], st[t]);
         }
         float p[8];
         float mx = -INFINITY;
@@ -395,9 +394,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
             rs += p[e];
         }
         l_run += quad_rows_sum(rs);
-        bf16x8_t pf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (__bf16)p[e];
+        const bf16x8_t pf = Mma<F16>::pack8(p);
         // the K fragments have been read: the tile takes the V rows
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -407,7 +404,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
         if (have_next) issue(vb, Vb, next_rows);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt16_frag<D>(tile, dt), pf, acc[dt], 0, 0, 0);
+            acc[dt] = Mma<F16>::mma16(vt16_frag<D>(tile, dt), pf, acc[dt]);
     };
 
     // the workgroup walks its chunk 128 list entries at a time, 32 per wave; index entries are fetched two
@@ -459,7 +456,7 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
         if (n_chunks == 1) {
             const float o = lsum > 0.f ? val / lsum : 0.f;
             bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + b * s.o_stride[0] + (int64_t)hq * s.o_stride[2] + col;
-            *op = (bf16_t)f32_to_bf16_bits(o);
+            *op = (bf16_t)Mma<F16>::bits(o);
         } else {
             a.part_acc[pidx * D + col] = val;
         }
@@ -472,28 +469,35 @@ __global__ __launch_bounds__(kMB, 2) void decode_rows_mfma16_kernel(Shape s, Dec
 
 }  // namespace
 
-// Gather-mode attention for bf16, groups of up to 16 heads.
+// Gather-mode attention for 16-bit caches (dtype 1 = bf16, 2 = fp16), groups of up to 16 heads.
 hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
-    if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
+    if ((s.dtype != 1 && s.dtype != 2) || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, true>), grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, true>), grid, block, 0, st, s, plan, a);
+    const bool f16 = s.dtype == 2;
+    if (s.D == 128 && !f16) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, true, false>), grid, block, 0, st, s, plan, a);
+    else if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, true, true>), grid, block, 0, st, s, plan, a);
+    else if (!f16) hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
+    else hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, true, true>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 
 // Stream mode (every row of a sequence, logits stored), same restrictions; the logit rows must be
 // 16-byte aligned (pitch a multiple of 4 floats) and the chunk length a multiple of 8.
 hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, bool with_v, hipStream_t st) {
-    if (s.dtype != 1 || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
+    if ((s.dtype != 1 && s.dtype != 2) || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     if ((a.logit_pitch & 3) || (reinterpret_cast<uintptr_t>(a.logits) & 15) || (plan.chunk & 7)) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
-    if (s.D == 128) {
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, false>), grid, block, 0, st, s, plan, a);
-        else hipLaunchKernelGGL((decode_sweep_mfma_kernel<128>), grid, block, 0, st, s, plan, a);
-    } else {
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, false>), grid, block, 0, st, s, plan, a);
-        else hipLaunchKernelGGL((decode_sweep_mfma_kernel<64>), grid, block, 0, st, s, plan, a);
+    const bool f16 = s.dtype == 2;
+#define KASCADE_LAUNCH_SWEEP(D_, F_)                                                                                   \
+    {                                                                                                                  \
+        if (with_v) hipLaunchKernelGGL((decode_rows_mfma16_kernel<D_, false, F_>), grid, block, 0, st, s, plan, a);     \
+        else hipLaunchKernelGGL((decode_sweep_mfma_kernel<D_, F_>), grid, block, 0, st, s, plan, a);                   \
     }
+    if (s.D == 128 && !f16) KASCADE_LAUNCH_SWEEP(128, false)
+    else if (s.D == 128) KASCADE_LAUNCH_SWEEP(128, true)
+    else if (!f16) KASCADE_LAUNCH_SWEEP(64, false)
+    else KASCADE_LAUNCH_SWEEP(64, true)
+#undef KASCADE_LAUNCH_SWEEP
     return hipGetLastError();
 }
 

@@ -8,6 +8,7 @@ namespace kascade {
 constexpr int kWave = 64;
 
 typedef uint16_t bf16_t;   // storage only; arithmetic is fp32
+typedef _Float16 f16_t;    // the other 16-bit storage type (matrix-unit kernels only)
 
 // A sequence length read from device memory, held to the host-side bound that sized the grid and the
 // buffers (bound <= 0: none): a length beyond it must not become a write beyond them.
@@ -41,6 +42,15 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);
     return u >> 16;
 }
+// fp32 -> storage type T (float, bf16_t, f16_t), round to nearest even; and back
+template <typename T> __device__ __forceinline__ T narrow(float f);
+template <> __device__ __forceinline__ float narrow<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t narrow<bf16_t>(float f) { return (bf16_t)f32_to_bf16_bits(f); }
+template <> __device__ __forceinline__ f16_t narrow<f16_t>(float f) { return (f16_t)f; }
+__device__ __forceinline__ float widen1(float v) { return v; }
+__device__ __forceinline__ float widen1(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+__device__ __forceinline__ float widen1(f16_t v) { return (float)v; }
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }

@@ -9,7 +9,7 @@ namespace kascade {
 
 struct Shape {
     int B, Hq, Hkv, D, G;
-    int dtype;              // 0 fp32, 1 bf16
+    int dtype;              // 0 fp32, 1 bf16, 2 fp16 (matrix-unit kernels only)
     float scale_log2;       // softmax scale * log2(e): all softmax arithmetic is base 2
     int64_t q_stride[3];
     int64_t kv_stride[3];

@@ -79,5 +79,50 @@ __device__ __forceinline__ bf16x8_t pack_p(const f32x16_t& s, int base) {
 
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only
 
+// The two 16-bit storage types share every operand layout; what differs is the MFMA opcode and the
+// rounding of fp32 values to the storage type.  Fragments travel as bf16x8_t (8 x 16 raw bits) either way.
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+template <bool F16> struct Mma {
+    static __device__ __forceinline__ f32x16_t mma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+        if constexpr (F16)
+            return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+        else
+            return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4_t mma16(bf16x8_t a, bf16x8_t b, f32x4_t c) {
+        if constexpr (F16)
+            return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+        else
+            return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    // eight fp32 values rounded to nearest even in the storage type
+    static __device__ __forceinline__ bf16x8_t pack8(const float* p) {
+        if constexpr (F16) {   // as one vector conversion: four v_cvt_pk_f16_f32
+            typedef __attribute__((ext_vector_type(8))) float f32x8_t;
+            f32x8_t v;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = p[e];
+            return __builtin_bit_cast(bf16x8_t, __builtin_convertvector(v, f16x8_t));
+        } else {
+            bf16x8_t r;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[e] = (__bf16)p[e];
+            return r;
+        }
+    }
+    // registers base .. base+7 of a 32x32 accumulator tile as one operand fragment
+    static __device__ __forceinline__ bf16x8_t pack_tile(const f32x16_t& t, int base) {
+        float p[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[e] = t[base + e];
+        return pack8(p);
+    }
+    static __device__ __forceinline__ uint32_t bits(float x) {
+        if constexpr (F16) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)x);
+        else return f32_to_bf16_bits(x);
+    }
+};
+
 }  // namespace mfma
 }  // namespace kascade

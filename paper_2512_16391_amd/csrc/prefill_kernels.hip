@@ -98,7 +98,7 @@ __device__ __forceinline__ void dma_rows_seq(unsigned char* tile, const unsigned
 // buffered in LDS and filled by direct loads: block kb+1 streams in while block kb is multiplied,
 // one barrier per block.  BUF is the LDS buffer of this block; it is a template constant so that all
 // LDS addresses of a block differ from the other buffer's only by an immediate offset.
-template <int D, bool SPARSE, bool WITH_V>
+template <int D, bool SPARSE, bool WITH_V, bool F16>
 __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = BK * D * 2;
     constexpr int PASSES = Dma<D>::PASSES, RPP = Dma<D>::RPP, PPR = Dma<D>::PPR;
@@ -116,6 +116,9 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     const RowMap rm = map_row(w * 32 + q, u, Ts, hk, s.G, S);
     const int q_token = rm.ok ? rm.token : INT_MAX - 1;
     const float c = s.scale_log2;
+    // a block's weights are rescaled once a lane's block sum exceeds this: far below the largest value of the
+    // type the weights are rounded to for the second product (bf16: 2^127, fp16: 65504)
+    constexpr float kRescaleAbove = F16 ? 32768.f : 1073741824.f;
 
     // sparse: the tile these rows belong to owns the index list and the candidates end where it starts;
     // dense: plain causal attention, everything before the rows' own first token is unmasked
@@ -249,8 +252,8 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             fb_[kk] = lds_frag(tK_ + k_off<D>(key1, kk * 2 + h));                                            \
         }                                                                                                    \
         _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                                               \
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[kk], qf[kk], s0, 0, 0, 0);                      \
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[kk], qf[kk], s1, 0, 0, 0);                      \
+            s0 = Mma<F16>::mma32(fa_[kk], qf[kk], s0);                                                       \
+            s1 = Mma<F16>::mma32(fb_[kk], qf[kk], s1);                                                       \
         }                                                                                                    \
         if constexpr (WITH_V) {   /* these variants have registers to spare */                               \
             __builtin_amdgcn_sched_group_barrier(0x100, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                    \
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg_ref));                                         \
             rs += s0[r] + s1[r];                                                                             \
         }                                                                                                    \
-        if (__builtin_amdgcn_ballot_w64(!(rs <= 1073741824.f)) != 0) {                                       \
+        if (__builtin_amdgcn_ballot_w64(!(rs <= kRescaleAbove)) != 0) {                                      \
             KASCADE_SCORES(tK_, buf_, kb_)                                                                   \
             float mx = s0[0];                                                                                \
             _Pragma("unroll") for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);                             \
@@ -331,11 +334,12 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         if constexpr (WITH_V) {                                                                              \
             const unsigned char* tV_ = smV + (buf_) * TILE;                                                  \
             bf16x8_t pf[4];                                                                                  \
-            pf[0] = pack_p(s0, 0); pf[1] = pack_p(s0, 8); pf[2] = pack_p(s1, 0); pf[3] = pack_p(s1, 8);      \
+            pf[0] = Mma<F16>::pack_tile(s0, 0); pf[1] = Mma<F16>::pack_tile(s0, 8);                          \
+            pf[2] = Mma<F16>::pack_tile(s1, 0); pf[3] = Mma<F16>::pack_tile(s1, 8);                          \
             _Pragma("unroll") for (int i = 0; i < DBLK; ++i) {                                                \
                 _Pragma("unroll") for (int st = 0; st < 4; ++st) {                                            \
                     const bf16x8_t va = vt_frag<D>(tV_, i, st * 16);                                         \
-                    acc_o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[st], acc_o[i], 0, 0, 0);       \
+                    acc_o[i] = Mma<F16>::mma32(va, pf[st], acc_o[i]);                                        \
                 }                                                                                            \
             }                                                                                                \
         }                                                                                                    \
@@ -370,8 +374,8 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             for (int r4 = 0; r4 < 4; ++r4) {
                 const int d0 = i * 32 + r4 * 8 + h * 4;
                 uint2 pk;
-                pk.x = pack_bf16(acc_o[i][r4 * 4 + 0] * inv, acc_o[i][r4 * 4 + 1] * inv);
-                pk.y = pack_bf16(acc_o[i][r4 * 4 + 2] * inv, acc_o[i][r4 * 4 + 3] * inv);
+                pk.x = Mma<F16>::bits(acc_o[i][r4 * 4 + 0] * inv) | (Mma<F16>::bits(acc_o[i][r4 * 4 + 1] * inv) << 16);
+                pk.y = Mma<F16>::bits(acc_o[i][r4 * 4 + 2] * inv) | (Mma<F16>::bits(acc_o[i][r4 * 4 + 3] * inv) << 16);
                 *reinterpret_cast<uint2*>(op + d0) = pk;
             }
         }
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
 
 // One 64-key block of anchor pass 2 for this wave: S = Q K^T from the staged tile, pooled
 // weights 2^(s c - e_r), column sums over the wave's 32 rows into part[w][key].
-template <int D>
+template <int D, bool F16>
 __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*part)[BK], const bf16x8_t (&qf)[D / 16],
                                            const float (&e_r)[16], float c, int key0, int key1, int h, int w) {
     constexpr int KSTEPS = D / 16;
@@ -391,8 +395,8 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
     for (int kk = 0; kk < KSTEPS; ++kk) {
         const bf16x8_t b0 = lds_frag(tile + k_off<D>(key0, kk * 2 + h));
         const bf16x8_t b1 = lds_frag(tile + k_off<D>(key1, kk * 2 + h));
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b0, s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], b1, s1, 0, 0, 0);
+        s0 = Mma<F16>::mma32(qf[kk], b0, s0);
+        s1 = Mma<F16>::mma32(qf[kk], b1, s1);
     }
     float c0 = 0.f, c1 = 0.f;
 #pragma unroll
@@ -410,7 +414,7 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
 // taken after the next barrier (two partial buffers), so it needs no barrier of its own.
 // MULTI: the tile has more than 128 rows and is swept in parts (kept out of the one-part kernel,
 // whose register budget it would break).
-template <int D, bool MULTI>
+template <int D, bool MULTI, bool F16>
 __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
     constexpr int PART = kPW * BK * (int)sizeof(float);
@@ -488,7 +492,7 @@ __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shap
             __syncthreads();                                                                                   \
             if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(nxt_, Kb, row_bytes, ((kb_) + 1) * BK, prefix - 1, coff, w); \
             if ((kb_) > 0) KASCADE_POOL_STORE(part_prev_, (kb_) - 1)                                           \
-            pool_block<D>(cur_, part_cur_, qf, e_r, c, key0, key1, h, w);                                      \
+            pool_block<D, F16>(cur_, part_cur_, qf, e_r, c, key0, key1, h, w);                                      \
         }
         int kb = 0;
         for (; kb + 1 < n_blocks; kb += 2) {
@@ -527,12 +531,18 @@ __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shap
 
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
     dim3 grid(a.n_sub * s.Hkv), block(kPB);   // one workgroup per 128 rows
-#define KASCADE_LAUNCH_ATTEND(DD)                                                                                      \
-    if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true>), grid, block, 0, st, s, a);                 \
-    else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true>), grid, block, 0, st, s, a);           \
-    else hipLaunchKernelGGL((prefill_attend_kernel<DD, false, false>), grid, block, 0, st, s, a);
-    if (s.D == 128) { KASCADE_LAUNCH_ATTEND(128) }
-    else if (s.D == 64) { KASCADE_LAUNCH_ATTEND(64) }
+    if (s.dtype != 1 && s.dtype != 2) return hipErrorInvalidValue;
+    const bool f16 = s.dtype == 2;
+#define KASCADE_LAUNCH_ATTEND(DD, FF)                                                                                  \
+    {                                                                                                                  \
+        if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true, FF>), grid, block, 0, st, s, a);         \
+        else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true, FF>), grid, block, 0, st, s, a);   \
+        else hipLaunchKernelGGL((prefill_attend_kernel<DD, false, false, FF>), grid, block, 0, st, s, a);              \
+    }
+    if (s.D == 128 && !f16) KASCADE_LAUNCH_ATTEND(128, false)
+    else if (s.D == 128) KASCADE_LAUNCH_ATTEND(128, true)
+    else if (s.D == 64 && !f16) KASCADE_LAUNCH_ATTEND(64, false)
+    else if (s.D == 64) KASCADE_LAUNCH_ATTEND(64, true)
     else return hipErrorInvalidValue;
 #undef KASCADE_LAUNCH_ATTEND
     return hipGetLastError();
@@ -540,12 +550,19 @@ hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool spar
 
 hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t st) {
     dim3 grid(a.n_tiles * s.Hkv), block(kPB);
-    const bool multi = a.tile_tokens != a.sub_tokens;
-    if (s.D == 128 && !multi) hipLaunchKernelGGL((prefill_pool_kernel<128, false>), grid, block, 0, st, s, a);
-    else if (s.D == 128) hipLaunchKernelGGL((prefill_pool_kernel<128, true>), grid, block, 0, st, s, a);
-    else if (s.D == 64 && !multi) hipLaunchKernelGGL((prefill_pool_kernel<64, false>), grid, block, 0, st, s, a);
-    else if (s.D == 64) hipLaunchKernelGGL((prefill_pool_kernel<64, true>), grid, block, 0, st, s, a);
+    if (s.dtype != 1 && s.dtype != 2) return hipErrorInvalidValue;
+    const bool multi = a.tile_tokens != a.sub_tokens, f16 = s.dtype == 2;
+#define KASCADE_LAUNCH_POOL(DD, FF)                                                                              \
+    {                                                                                                            \
+        if (multi) hipLaunchKernelGGL((prefill_pool_kernel<DD, true, FF>), grid, block, 0, st, s, a);            \
+        else hipLaunchKernelGGL((prefill_pool_kernel<DD, false, FF>), grid, block, 0, st, s, a);                 \
+    }
+    if (s.D == 128 && !f16) KASCADE_LAUNCH_POOL(128, false)
+    else if (s.D == 128) KASCADE_LAUNCH_POOL(128, true)
+    else if (s.D == 64 && !f16) KASCADE_LAUNCH_POOL(64, false)
+    else if (s.D == 64) KASCADE_LAUNCH_POOL(64, true)
     else return hipErrorInvalidValue;
+#undef KASCADE_LAUNCH_POOL
     return hipGetLastError();
 }
 

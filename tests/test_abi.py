@@ -66,6 +66,7 @@ def test_argument_checks_happen_before_any_launch(lib):
     # the pointers are fake: every call below must return from validation
     assert call_reuse(lib, make_desc(head_dim=96)) == -2
     assert call_reuse(lib, make_desc(dtype=7)) == -2
+    assert call_reuse(lib, make_desc(dtype=3)) == -2
     assert call_reuse(lib, make_desc(n_q_heads=6, n_kv_heads=2)) == -2          # G = 3 in fp32 / head_dim 64: not built
     wide = dict(head_dim=128, dtype=binding.KASCADE_BF16, q_stride=(34 * 128, 0, 128), o_stride=(34 * 128, 0, 128),
                 kv_stride=(2 * 100 * 128, 100 * 128, 128))
