@@ -354,10 +354,10 @@ def test_decode_anchor_random_shapes(seed):
 
 @pytest.mark.parametrize("seed", range(8))
 def test_decode_anchor_random_shapes_matrix_unit(seed):
-    """The same for the bf16 kernels that run on the matrix unit: any group size from 5 to 16, both head
-    dimensions, lengths around the 128-row pass, the 8-logit store runs and the 1024-row chunk."""
+    """The same for the kernels that run on the matrix unit, bf16 and fp16: any group size from 5 to 16, both
+    head dimensions, lengths around the 32-row batch, the 8-logit store runs and the 1024-row chunk."""
     rs = np.random.default_rng(7000 + seed)
-    dtype = torch.bfloat16
+    dtype = [torch.bfloat16, torch.float16][(seed // 2) % 2]
     d = [128, 64][seed % 2]
     G = int(rs.integers(5, 17))
     Hkv = int(rs.integers(1, 3))
@@ -365,7 +365,7 @@ def test_decode_anchor_random_shapes_matrix_unit(seed):
     lens = [int(rs.choice([1, 7, 8, 9, 127, 128, 129, 1023, 1025, 2050, 5000])) for _ in range(B)]
     W = int(rs.choice([0, 0, 1, 16]))
     ks = [int(min(L, max(W, rs.choice([1, 2, 31, 64, 100, 1500, L])))) for L in lens]
-    print(f"case decode anchor random matrix unit seed={seed}: d={d} G={G} Hkv={Hkv} lens={lens} ks={ks} W={W}", flush=True)
+    print(f"case decode anchor random matrix unit seed={seed}: {dtype} d={d} G={G} Hkv={Hkv} lens={lens} ks={ks} W={W}", flush=True)
     q, k, v = random_case(8000 + seed, B, G * Hkv, Hkv, d, dtype, lens, Lmax=max(lens) + int(rs.integers(0, 70)))
     run_anchor_case(q, k, v, lens, ks, min(W, min(ks)), seed % 2, dtype, where=f"random matrix unit {seed}")
 
