@@ -601,7 +601,9 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(Shape s, int n_chun
 template <int G_>
 __global__ __launch_bounds__(kBlock) void decode_pool_kernel(Shape s, int n_chunks, DecodePoolArgs a) {
     const int G = G_ ? G_ : s.G;
-    const int b = blockIdx.z, hk = blockIdx.y;
+    // sequences in descending order: the sweep wrote the logits of the last sequences last, and what of them
+    // is still in L2 / the memory-side cache is read before this pass's own traffic evicts it
+    const int b = (int)gridDim.z - 1 - (int)blockIdx.z, hk = blockIdx.y;
     const int L = bounded_len(a.seqlens[b], a.max_seqlen);
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.seg_info) a.seg_info[((int64_t)b * s.Hkv + hk) * 8] = 0u;
     if (blockIdx.x * kBlock * 4 >= L) return;   // uniform per workgroup
