@@ -17,6 +17,8 @@ HIPCC_FLAGS = [
     "-ffp-contract=fast",
     # keep MFMA accumulators in VGPRs: the softmax reads them right away, AGPR copies cost VALU slots
     "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+    # the sources compile side by side
+    "-parallel-jobs=6",
 ]
 
 
