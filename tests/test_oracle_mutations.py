@@ -171,6 +171,24 @@ def pooled_query_first_row(rows, storage):
     return (ko.round_to_bf16(row) if storage == "bf16" else row).astype(np.float64)
 
 
+def pooled_query_fp16_truncates(rows, storage):
+    if storage != "fp16":
+        return ORIGINAL_POOL_QUERY_VECTORS(rows, storage)
+    rows = np.asarray(rows, dtype=np.float32)
+    acc = np.zeros(rows.shape[1], dtype=np.float32)
+    for r in rows:
+        acc = acc + r
+    mean = acc / np.float32(rows.shape[0])
+    up = mean.astype(np.float16)                      # nearest; step back where that went away from zero
+    away = np.abs(up.astype(np.float32)) > np.abs(mean)
+    toward = np.nextafter(up, np.float16(0.0))
+    return np.where(away, toward, up).astype(np.float64)
+
+
+def pooled_query_fp16_as_bf16(rows, storage):
+    return ORIGINAL_POOL_QUERY_VECTORS(rows, "bf16" if storage == "fp16" else storage)
+
+
 def presoftmax_wrong_groups(q, K, scale, k, storage, recent_window=0):
     q, K = np.asarray(q, dtype=np.float64), np.asarray(K, dtype=np.float64)
     Hkv = K.shape[0]
@@ -188,6 +206,8 @@ def presoftmax_tile_includes_diagonal(Q, Kp, t, T, scale, k_t, storage):
                   for hk in range(Hkv)])
     return np.stack([ko.select_topk(a[hk], k_t, 0) for hk in range(Hkv)]), a
 
+
+ORIGINAL_POOL_QUERY_VECTORS = ko.pool_query_vectors
 
 MUTATIONS = [
     P("decode_logits", wrong_group_logits, id="heads grouped h mod Hkv"),
@@ -212,6 +232,8 @@ MUTATIONS = [
     P("round_to_bf16", bf16_ties_away, id="bf16 ties away from zero"),
     P("pool_query_vectors", pooled_query_is_the_sum, id="pooled query not divided"),
     P("pool_query_vectors", pooled_query_first_row, id="pooled query from one row"),
+    P("pool_query_vectors", pooled_query_fp16_truncates, id="fp16 pooled query by truncation"),
+    P("pool_query_vectors", pooled_query_fp16_as_bf16, id="fp16 pooled query rounded to bf16"),
     P("decode_presoftmax_indices", presoftmax_wrong_groups, id="pre-softmax pooling over the wrong heads"),
     P("prefill_presoftmax_indices_tile", presoftmax_tile_includes_diagonal, id="pre-softmax candidates include the tile"),
 ]
