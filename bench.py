@@ -5,15 +5,19 @@ One "step" = one pass of the hot path over one batch of seeded synthetic input:
   decode  - the Llama-3.1-8B-shaped configuration (32 query / 8 key heads, d 128, bf16,
             batch 8, 32768-token contiguous KV cache per sequence, k = 10 %): one anchor
             layer followed by three reuse layers, each layer with its own Q/K/V;
-  prefill - (when the prefill kernels are built) batch 1, 32768 tokens causal, same heads,
-            tiles of 32 tokens x 4 heads, k_t = 10 % of the prefix (min 256): one anchor
-            layer followed by three reuse layers.
+  prefill - batch 1, 32768 tokens causal, same heads, tiles of 32 tokens x 4 heads,
+            k_t = 10 % of the prefix (min 256): one anchor layer followed by three reuse layers.
 All inputs are resident in HBM before the timed region; nothing is allocated inside it.
+A second leg, outside the step, runs the bandwidth-stress decode configuration (batch 32,
+ragged 65536-131072 tokens, k = 5 %, 64-token recent window; one anchor + three reuse layers)
+and reports its reuse layer against the HBM peak.
 
 Prints ONE JSON line.  `value` is the decode attention time per layer (the headline metric's
 first component); HBM GB/s of the reuse gather and prefill TFLOP/s ride along in extra keys.
-Per-kernel durations come from HIP events recorded by the library around each launch on the
-launch stream, inside the timed region.
+Per-kernel durations are the begin-to-end device times of the library's own dispatches (a start and
+a stop event bound to each dispatch, recorded by the library on the launch stream in a second timed
+pass of the same K steps) - the figure a rocprofv3 kernel trace of this command reports; nothing is
+subtracted from them.
 """
 import argparse
 import json
@@ -35,8 +39,56 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-config3", action="store_true")
     ap.add_argument("--cpu-sample-seqs", type=int, default=8)
     return ap.parse_args()
+
+
+def hbm_roofline(kernel, nbytes, t_us, traffic=None, **extra):
+    gbs = nbytes / t_us / 1e3
+    r = {"kernel": kernel, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "algorithmic_bytes": int(nbytes),
+         "avg_kernel_us": round(t_us, 2)}
+    r.update(extra)
+    return r
+
+
+def mfma_roofline(kernel, flop, t_us, traffic=None, **extra):
+    tf = flop / (t_us * 1e-6) / 1e12
+    r = {"kernel": kernel, "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic, "algorithmic_flop": float(flop),
+         "avg_kernel_us": round(t_us, 1)}
+    r.update(extra)
+    return r
+
+
+def profiled(binding, fn, reps):
+    """Runs fn() reps times with a start/stop event on every dispatch; returns {step name: average us per run of
+    that step} (a step that needs several dispatches is their sum)."""
+    import torch
+    binding.kascade_profile_enable(True)
+    binding.kascade_profile_reset()
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    prof = binding.kascade_profile_read()
+    binding.kascade_profile_enable(False)
+    return {k: v[0] * 1e3 / v[1] for k, v in prof.items()}
+
+
+def wall_us(fn, reps, warm=2):
+    """Average wall time of fn() on the device, event pair around `reps` back-to-back calls."""
+    import torch
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
 
 
 def main():
@@ -60,29 +112,13 @@ def main():
     wl = workloads.config2(device=dev)
     B, Hq, Hkv, d = wl.B, wl.Hq, wl.Hkv, wl.d
     L, kmax = wl.Lmax, wl.k_max
-    seqlens = torch.tensor(wl.seqlens, dtype=torch.int32, device=dev)
-    kps = torch.tensor(wl.k_per_seq, dtype=torch.int32, device=dev)
-    idx = torch.empty(B, Hkv, kmax, dtype=torch.int32, device=dev)
-    outs = [torch.empty_like(l.q) for l in wl.layers]
-    desc = binding.decode_desc(wl.layers[0].q, wl.layers[0].k)
-    ws_bytes = max(binding.kascade_workspace_bytes(binding.OP_DECODE_ANCHOR, desc, L, kmax),
-                   binding.kascade_workspace_bytes(binding.OP_DECODE_REUSE, desc, L, kmax))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-
-    def decode_step(out_mode=binding.KASCADE_OUT_SPARSE):
-        a = wl.layers[0]
-        binding.kascade_decode_anchor(a.q, a.k, a.v, seqlens, kps, L, kmax, 0, out_mode, idx, outs[0], ws)
-        for i in range(1, len(wl.layers)):
-            r = wl.layers[i]
-            binding.kascade_decode_reuse(r.q, r.k, r.v, seqlens, kps, kmax, idx, None, outs[i], ws)
+    dec = DecodeLeg(dev, wl)
 
     # ---------------- prefill workload ----------------
-    prefill = None
-    if not args.no_prefill:
-        prefill = PrefillBench(dev)
+    prefill = None if args.no_prefill else PrefillBench(dev)
 
     def step():
-        decode_step()
+        dec.step()
         if prefill is not None:
             prefill.step()
 
@@ -92,14 +128,7 @@ def main():
     cal_dst = torch.empty_like(cal_src)
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
-    # the same copy timed: what a plain device-to-device copy reaches on this machine (read + write bytes)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(5):
-        cal_dst.copy_(cal_src)
-    c1.record()
-    c1.synchronize()
-    copy_gbs = 5 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    copy_gbs = 2.0 * (1 << 30) / (wall_us(lambda: cal_dst.copy_(cal_src), 5, warm=0) * 1e-6) / 1e9
     del cal_src, cal_dst
 
     for _ in range(args.warmup):
@@ -112,7 +141,7 @@ def main():
     t0 = time.perf_counter()
     for e0, e1 in evs:
         e0.record()
-        decode_step()
+        dec.step()
         e1.record()
         if prefill is not None:
             prefill.step()
@@ -125,19 +154,8 @@ def main():
     per_step = sorted(e0.elapsed_time(e1) * 1e3 / n_layers for e0, e1 in evs)
     pct = lambda f: round(per_step[min(len(per_step) - 1, int(f * len(per_step)))], 2)
 
-    # ---- timed region 2: the same K steps with a HIP event pair around every kernel launch --------
-    binding.kascade_profile_enable(True)
-    binding.kascade_profile_reset()
-    torch.cuda.synchronize()
-    for _ in range(args.steps):
-        step()
-    binding.kascade_profile_calibrate(50)
-    torch.cuda.synchronize()
-    prof = binding.kascade_profile_read()
-    binding.kascade_profile_enable(False)
-    # what an event pair reports around an empty kernel; subtracted from every kernel's average
-    pair_us = prof.pop("empty_kernel", (0.0, 1))
-    pair_us = pair_us[0] * 1e3 / pair_us[1]
+    # ---- timed region 2: the same K steps, every dispatch carrying its own start/stop event --------
+    kus = profiled(binding, step, args.steps)
 
     # ---- the decode step as one HIP graph (no launch gaps): replayed K times -----------------------
     graph_us_per_layer = None
@@ -145,51 +163,24 @@ def main():
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            decode_step()
+            dec.step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        ref_outs = [o.clone() for o in outs]
+        ref_outs = [o.clone() for o in dec.outs]
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            decode_step()
+            dec.step()
         for _ in range(3):
             g.replay()
         torch.cuda.synchronize()
-        same = all(torch.equal(a_, b_) for a_, b_ in zip(ref_outs, outs))
-        reps = max(args.steps, 20)
-        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        g0.record()
-        for _ in range(reps):
-            g.replay()
-        g1.record()
-        g1.synchronize()
+        same = all(torch.equal(a_, b_) for a_, b_ in zip(ref_outs, dec.outs))
         if same:
-            graph_us_per_layer = g0.elapsed_time(g1) * 1e3 / reps / n_layers
+            graph_us_per_layer = wall_us(g.replay, max(args.steps, 20), warm=0) / n_layers
     except Exception as exc:   # graph capture is an extra, never the headline
         print(f"bench.py: graph replay skipped: {exc}", file=sys.stderr)
 
-    def avg_us(name):
-        return max(prof[name][0] * 1e3 / prof[name][1] - pair_us, 0.01) if name in prof else None
-
-    # algorithmic bytes per launch (bf16 rows of d elements, int32 indices, Q and O)
-    row_pairs = sum(wl.k_per_seq) * Hkv
-    gather_bytes = row_pairs * (2 * d * 2 + 4) + 2 * B * Hq * d * 2
-    stream_bytes = sum(wl.seqlens) * Hkv * d * 2 + sum(wl.seqlens) * Hq * 4 + B * Hq * d * 2
-    t_gather, t_stream = avg_us("decode_gather"), avg_us("decode_stream")
-    kernels_us = {k: round(avg_us(k), 2) for k in prof}
-    kernels_us_raw = {k: round(v[0] * 1e3 / v[1], 2) for k, v in prof.items()}
-    # dominant kernel of the decode step by total device time
-    roofline = {"kernel": "decode_stream", "bound": "hbm", "achieved": round(stream_bytes / t_stream / 1e3, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(stream_bytes / t_stream / 1e3 / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes": stream_bytes, "avg_kernel_us": round(t_stream, 2)}
-    roofline_reuse = {"kernel": "decode_gather", "bound": "hbm", "achieved": round(gather_bytes / t_gather / 1e3, 1),
-                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gather_bytes / t_gather / 1e3 / HBM_PEAK_GBS, 4),
-                      "traffic": None, "algorithmic_bytes": gather_bytes, "avg_kernel_us": round(t_gather, 2)}
-
     traffic = load_traffic()
-    roofline["traffic"] = traffic.get("decode_stream")
-    roofline_reuse["traffic"] = traffic.get("decode_gather")
-
+    layer_us = dec.layer_times()
     rec = {
         "metric": "sparse decode attn us/layer + HBM GB/s; prefill attn TFLOPS at 32K ctx",
         "value": round(dec_us_per_layer, 2), "unit": "us/layer (decode, mean of 1 anchor + 3 reuse layers)",
@@ -201,61 +192,140 @@ def main():
         "decode_us_per_layer_p10_p50_p90": [pct(0.1), pct(0.5), pct(0.9)],
         "decode_tokens_per_s": round(B / (dec_us_per_layer * n_layers * 1e-6), 1),
         "decode_us_per_layer_hip_graph": round(graph_us_per_layer, 2) if graph_us_per_layer else None,
-        "kernel_timing": "second timed pass of the same K steps, HIP event pair around every launch, minus the "
-                         "pair's reading around an empty kernel",
-        "event_pair_overhead_us": round(pair_us, 2),
-        "decode_reuse_hbm_GBps": roofline_reuse["achieved"],
+        "kernel_timing": "second timed pass of the same K steps; begin-to-end device time of each dispatch from a start "
+                         "and a stop event bound to the dispatch itself (what a kernel trace reports), nothing subtracted",
         "device_copy_GBps_measured": round(copy_gbs, 1),
-        "kernel_us": kernels_us,
-        "kernel_us_raw_event_pairs": kernels_us_raw,
-        "roofline": roofline,
-        "roofline_reuse": roofline_reuse,
+        "kernel_us": {k: round(v, 2) for k, v in kus.items()},
+        "decode_layer_us": layer_us,
     }
+    # ---- rooflines.  `roofline` is the kernel that takes the most device time in the step.
+    dec_roof = dec.rooflines(kus, layer_us, traffic)
     if prefill is not None:
-        rec.update(prefill.report(avg_us, MFMA_BF16_PEAK_TFLOPS))
+        pre = prefill.report(kus, traffic, binding)
+        rec["roofline"] = pre.pop("roofline")
+        rec.update(pre)
         rec["prefill_layer_ms"] = prefill.layer_times()
+    else:
+        rec["roofline"] = dec_roof["roofline_decode_stream"]
+    rec.update(dec_roof)
+    rec["decode_reuse_hbm_GBps"] = dec_roof["roofline_decode_gather"]["achieved"]
 
-    # anchor with dense output (layer 0) measured outside the timed region, for the paper's
-    # per-layer weighting (1 dense-output anchor, 4 anchors, 27 reuse layers of 32)
-    a = wl.layers[0]
-    tt = []
-    for mode in (binding.KASCADE_OUT_DENSE, binding.KASCADE_OUT_SPARSE):
-        for _ in range(3):
-            binding.kascade_decode_anchor(a.q, a.k, a.v, seqlens, kps, L, kmax, 0, mode, idx, outs[0], ws)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(20):
-            binding.kascade_decode_anchor(a.q, a.k, a.v, seqlens, kps, L, kmax, 0, mode, idx, outs[0], ws)
-        e1.record()
-        e1.synchronize()
-        tt.append(e0.elapsed_time(e1) * 1e3 / 20)
-    r1 = wl.layers[1]
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(21):
-        r = wl.layers[1 + i % 3]
-        binding.kascade_decode_reuse(r.q, r.k, r.v, seqlens, kps, kmax, idx, None, outs[1 + i % 3], ws)
-    e1.record()
-    e1.synchronize()
-    t_reuse = e0.elapsed_time(e1) * 1e3 / 21
-    # the same reuse layer over and over: its 108 MB of selected rows then sit in the 256 MB Infinity Cache,
-    # which the rotation over three layers above (and over four in the timed steps) avoids
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(21):
-        binding.kascade_decode_reuse(r1.q, r1.k, r1.v, seqlens, kps, kmax, idx, None, outs[1], ws)
-    e1.record()
-    e1.synchronize()
-    t_reuse_warm = e0.elapsed_time(e1) * 1e3 / 21
-    rec["decode_layer_us"] = {"anchor_dense_out": round(tt[0], 2), "anchor_sparse_out": round(tt[1], 2),
-                              "reuse": round(t_reuse, 2), "reuse_same_layer_cache_warm": round(t_reuse_warm, 2),
-                              "paper_weighted_avg_32_layers_5_anchors": round((tt[0] + 4 * tt[1] + 27 * t_reuse) / 32, 2)}
+    del dec
+    torch.cuda.empty_cache()
+    if not args.no_config3:
+        rec["config3"] = config3_leg(dev, traffic, max(5, min(args.steps, 20)))
 
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_seqs)
         if prefill is not None:
             rec["cpu_baseline_prefill"] = cpu_baseline_prefill(prefill)
     print(json.dumps(rec), flush=True)
+
+
+class DecodeLeg:
+    """One anchor layer (sparse output) followed by the reuse layers of a decode workload, every buffer
+    allocated up front."""
+
+    def __init__(self, dev, wl):
+        import torch
+        from paper_2512_16391_amd import binding
+        self.binding, self.wl = binding, wl
+        self.seqlens = torch.tensor(wl.seqlens, dtype=torch.int32, device=dev)
+        self.kps = torch.tensor(wl.k_per_seq, dtype=torch.int32, device=dev)
+        self.idx = torch.empty(wl.B, wl.Hkv, wl.k_max, dtype=torch.int32, device=dev)
+        self.outs = [torch.empty_like(l.q) for l in wl.layers]
+        desc = binding.decode_desc(wl.layers[0].q, wl.layers[0].k)
+        need = max(binding.kascade_workspace_bytes(binding.OP_DECODE_ANCHOR, desc, wl.Lmax, wl.k_max),
+                   binding.kascade_workspace_bytes(binding.OP_DECODE_REUSE, desc, wl.Lmax, wl.k_max))
+        self.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+    def anchor(self, out_mode=None):
+        b, wl, a = self.binding, self.wl, self.wl.layers[0]
+        mode = b.KASCADE_OUT_SPARSE if out_mode is None else out_mode
+        b.kascade_decode_anchor(a.q, a.k, a.v, self.seqlens, self.kps, wl.Lmax, wl.k_max, wl.recent_window, mode,
+                                self.idx, self.outs[0], self.ws)
+
+    def reuse(self, i):
+        b, wl, r = self.binding, self.wl, self.wl.layers[i]
+        b.kascade_decode_reuse(r.q, r.k, r.v, self.seqlens, self.kps, wl.k_max, self.idx, None, self.outs[i], self.ws)
+
+    def step(self):
+        self.anchor()
+        for i in range(1, len(self.wl.layers)):
+            self.reuse(i)
+
+    def layer_times(self):
+        """Wall time per layer kind (event pair around back-to-back calls of that layer, launch gaps included);
+        the reuse figure rotates over the reuse layers' own K/V so that the selected rows do not sit in the
+        Infinity Cache from the previous call."""
+        b = self.binding
+        n = len(self.wl.layers)
+        dense = wall_us(lambda: self.anchor(b.KASCADE_OUT_DENSE), 20, warm=3)
+        sparse = wall_us(lambda: self.anchor(b.KASCADE_OUT_SPARSE), 20, warm=3)
+        state = {"i": 0}
+
+        def rotate():
+            self.reuse(1 + state["i"] % (n - 1))
+            state["i"] += 1
+        reuse = wall_us(rotate, 7 * (n - 1), warm=n - 1)
+        warm = wall_us(lambda: self.reuse(1), 21, warm=2)
+        return {"anchor_dense_out": round(dense, 2), "anchor_sparse_out": round(sparse, 2), "reuse": round(reuse, 2),
+                "reuse_same_layer_cache_warm": round(warm, 2),
+                "paper_weighted_avg_32_layers_5_anchors": round((dense + 4 * sparse + 27 * reuse) / 32, 2)}
+
+    def bytes(self):
+        """Algorithmic bytes per launch: bf16 rows of d elements, int32 indices, fp32 logits, Q and O."""
+        wl = self.wl
+        row_pairs = sum(wl.k_per_seq) * wl.Hkv
+        gather = row_pairs * (2 * wl.d * 2 + 4) + 2 * wl.B * wl.Hq * wl.d * 2
+        stream = sum(wl.seqlens) * wl.Hkv * wl.d * 2 + sum(wl.seqlens) * wl.Hq * 4 + wl.B * wl.Hq * wl.d * 2
+        return gather, stream
+
+    def rooflines(self, kus, layer_us, traffic, suffix=""):
+        gather_b, stream_b = self.bytes()
+        t_layer_kernels = kus["decode_gather"] + kus.get("decode_merge", 0.0)
+        return {
+            "roofline_decode_stream" + suffix: hbm_roofline("decode_stream (anchor pass 1: K sweep + logits)", stream_b,
+                                                            kus["decode_stream"], traffic.get("decode_stream" + suffix)),
+            "roofline_decode_gather" + suffix: hbm_roofline("decode_gather (reuse layer / anchor pass 4, gather kernel alone)",
+                                                            gather_b, kus["decode_gather"], traffic.get("decode_gather" + suffix)),
+            "roofline_decode_reuse_layer" + suffix: hbm_roofline(
+                "reuse layer = gather + merge", gather_b, layer_us["reuse"], None,
+                kernels_only_us=round(t_layer_kernels, 2),
+                frac_kernels_only=round(gather_b / t_layer_kernels / 1e3 / HBM_PEAK_GBS, 4),
+                note="avg_kernel_us is the layer's wall time (dispatch gaps included), K/V rotating over the reuse layers"),
+        }
+
+
+def config3_leg(dev, traffic, reps):
+    """Bandwidth-stress decode (batch 32, ragged 65536-131072 tokens, k = 5 % with a 64-token recent window):
+    one anchor + three reuse layers, each with its own Q/K/V (69 GB resident)."""
+    import torch
+    from paper_2512_16391_amd import binding, workloads
+    t0 = time.perf_counter()
+    wl = workloads.config3(device=dev)
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t0
+    leg = DecodeLeg(dev, wl)
+    for _ in range(2):
+        leg.step()
+    step_us = wall_us(leg.step, reps, warm=0)
+    kus = profiled(binding, leg.step, reps)
+    layer_us = leg.layer_times()
+    gather_b, stream_b = leg.bytes()
+    out = {"workload": wl.name + " k=5% (64-token recent window inside k), 1 anchor + 3 reuse layers",
+           "batch": wl.B, "sum_seqlens": sum(wl.seqlens), "sum_k": sum(wl.k_per_seq), "steps": reps,
+           "us_per_layer": round(step_us / len(wl.layers), 2),
+           "tokens_per_s": round(wl.B / (step_us * 1e-6), 1),
+           "kernel_us": {k: round(v, 2) for k, v in kus.items()}, "decode_layer_us": layer_us,
+           "input_generation_s": round(gen_s, 1)}
+    roofs = leg.rooflines(kus, layer_us, traffic, suffix="_cfg3")
+    out["roofline_reuse_cfg3"] = roofs.pop("roofline_decode_gather_cfg3")
+    out["roofline_reuse_layer_cfg3"] = roofs.pop("roofline_decode_reuse_layer_cfg3")
+    out["roofline_stream_cfg3"] = roofs.pop("roofline_decode_stream_cfg3")
+    del leg, wl
+    torch.cuda.empty_cache()
+    return out
 
 
 class PrefillBench:
@@ -285,75 +355,66 @@ class PrefillBench:
         self.sparse_flop = 4.0 * d * Hq * sum(min(T, S - t * T) * (kt + (min(T, S - t * T) + 1) / 2.0)
                                               for t, kt in enumerate(wl.k_per_tile))
 
+    def anchor(self, out_mode):
+        b, wl, a = self.binding, self.wl, self.wl.layers[0]
+        b.kascade_prefill_anchor(a.q, a.k, a.v, wl.T, self.kpt, self.off, self.idx_total, out_mode, self.idx, self.outs[0], self.ws)
+
+    def reuse(self, i):
+        b, wl, r = self.binding, self.wl, self.wl.layers[i]
+        b.kascade_prefill_reuse(r.q, r.k, r.v, wl.T, self.kpt, self.off, self.idx_total, self.idx, None, None, self.outs[i], self.ws)
+
     def step(self):
-        b, wl = self.binding, self.wl
-        a = wl.layers[0]
-        b.kascade_prefill_anchor(a.q, a.k, a.v, wl.T, self.kpt, self.off, self.idx_total, b.KASCADE_OUT_SPARSE,
-                                 self.idx, self.outs[0], self.ws)
-        for i in range(1, len(wl.layers)):
-            r = wl.layers[i]
-            b.kascade_prefill_reuse(r.q, r.k, r.v, wl.T, self.kpt, self.off, self.idx_total, self.idx, None, None,
-                                    self.outs[i], self.ws)
+        self.anchor(self.binding.KASCADE_OUT_SPARSE)
+        for i in range(1, len(self.wl.layers)):
+            self.reuse(i)
 
     def layer_times(self):
         """Per-layer wall time of the three layer kinds, and the paper's weighting (Table 3 caption)."""
-        import torch
-        b, wl = self.binding, self.wl
-        a, r = wl.layers[0], wl.layers[1]
-
-        def timed(fn, n=5):
-            fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(n):
-                fn()
-            e1.record()
-            e1.synchronize()
-            return e0.elapsed_time(e1) / n
-
-        dense = timed(lambda: b.kascade_prefill_anchor(a.q, a.k, a.v, wl.T, self.kpt, self.off, self.idx_total,
-                                                       b.KASCADE_OUT_DENSE, self.idx, self.outs[0], self.ws))
-        sparse = timed(lambda: b.kascade_prefill_anchor(a.q, a.k, a.v, wl.T, self.kpt, self.off, self.idx_total,
-                                                        b.KASCADE_OUT_SPARSE, self.idx, self.outs[0], self.ws))
-        reuse = timed(lambda: b.kascade_prefill_reuse(r.q, r.k, r.v, wl.T, self.kpt, self.off, self.idx_total, self.idx,
-                                                      None, None, self.outs[1], self.ws))
+        b = self.binding
+        dense = wall_us(lambda: self.anchor(b.KASCADE_OUT_DENSE), 5, warm=1) / 1e3
+        sparse = wall_us(lambda: self.anchor(b.KASCADE_OUT_SPARSE), 5, warm=1) / 1e3
+        reuse = wall_us(lambda: self.reuse(1), 5, warm=1) / 1e3
         avg = (dense + 4 * sparse + 27 * reuse) / 32
         return {"anchor_dense_out": round(dense, 3), "anchor_sparse_out": round(sparse, 3), "reuse": round(reuse, 3),
                 "paper_weighted_avg_32_layers_5_anchors": round(avg, 3),
                 "dense_attention_equivalent_tflops_at_weighted_avg_counting_skipped_work": round(2 * self.U / (avg * 1e-3) / 1e12, 1)}
 
-    def report(self, us, peak_tflops):
+    def report(self, kus, traffic, binding):
         # the per-head Top-k selection runs inside the pass-2 kernel; a separate selection kernel exists
         # only for the shared-set variant
-        t1, t2, tk, ts = us("prefill_sweep1"), us("prefill_sweep2"), us("prefill_topk") or 0.0, us("prefill_sparse")
+        t1, t2, ts = kus["prefill_sweep1"], kus["prefill_sweep2"], kus["prefill_sparse"]
+        tk = kus.get("prefill_topk", 0.0)
         anchor_us = t1 + t2 + tk + ts
         anchor_flop = 2 * self.U + self.sparse_flop
+        # layer 0 (dense output): pass 1 carries P.V as well (2U); measured in a short pass of its own
+        kd = profiled(binding, lambda: self.anchor(binding.KASCADE_OUT_DENSE), 3)
+        t1v, t2d = kd["prefill_sweep1_v"], kd["prefill_sweep2"]
         tf = lambda flop, t_us: flop / (t_us * 1e-6) / 1e12
-        # pass 1 is the plain causal Q.K^T sweep; pass 2 does the same product plus the pooling and, in its
-        # tail, the tile's Top-k selection, so pass 1 is the kernel priced against the matrix peak
-        sweep_tf = tf(self.U, t1)
         return {
             "prefill_anchor_ms": round(anchor_us / 1e3, 3), "prefill_reuse_ms": round(ts / 1e3, 3),
             "prefill_anchor_tflops": round(tf(anchor_flop, anchor_us), 1),
             "prefill_reuse_tflops": round(tf(self.sparse_flop, ts), 1),
             "prefill_tokens_per_s": round(self.wl.S / ((anchor_us + 3 * ts) * 1e-6), 1),
-            "roofline_prefill": {"kernel": "prefill_sweep1", "bound": "mfma",
-                                 "achieved": round(sweep_tf, 1), "peak": peak_tflops, "unit": "TFLOP/s",
-                                 "frac": round(sweep_tf / peak_tflops, 4), "traffic": None,
-                                 "algorithmic_flop": self.U, "avg_kernel_us": round(t1, 1),
-                                 "pass2_with_pooling_and_selection_us": round(t2, 1)},
-            "roofline_prefill_anchor": {"bound": "mfma", "achieved": round(tf(anchor_flop, anchor_us), 1),
-                                        "peak": peak_tflops, "unit": "TFLOP/s",
-                                        "frac": round(tf(anchor_flop, anchor_us) / peak_tflops, 4),
-                                        "algorithmic_flop": anchor_flop, "out_mode": "sparse"},
+            "roofline": mfma_roofline("prefill_sweep2 (prefill_pool_kernel: anchor pass 2, tile pooling and the per-tile Top-k)",
+                                      self.U, t2, traffic.get("prefill_sweep2")),
+            "roofline_prefill_sweep1": mfma_roofline("prefill_sweep1 (anchor pass 1, row statistics only)", self.U, t1,
+                                                     traffic.get("prefill_sweep1")),
+            "roofline_prefill_sweep1_dense_out": mfma_roofline("prefill_sweep1_v (layer 0: pass 1 with P.V, dense output)",
+                                                               2 * self.U, t1v, traffic.get("prefill_sweep1_v")),
+            "roofline_prefill_sparse": mfma_roofline("prefill_sparse (reuse layer / anchor pass 4)", self.sparse_flop, ts,
+                                                     traffic.get("prefill_sparse")),
+            "roofline_prefill_anchor": mfma_roofline("anchor layer, sparse output: sweep 1 + sweep 2 + sparse attention",
+                                                     anchor_flop, anchor_us, None, out_mode="sparse"),
+            "roofline_prefill_anchor_dense_out": mfma_roofline("anchor layer 0, dense output: sweep 1 with P.V + sweep 2",
+                                                               3 * self.U, t1v + t2d, None, out_mode="dense"),
         }
 
 
 def load_traffic():
     """HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same
-    command (scaled by the 1 GiB copy above): the table in profiles/bench_cfg2_cfg4_hbm_traffic.txt
+    command (scaled by the 1 GiB copy above): the table in profiles/bench_hbm_traffic.txt
     (columns: kernel, read MB, write MB, total MB)."""
-    path = os.path.join(ROOT, "profiles", "bench_cfg2_cfg4_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "bench_hbm_traffic.txt")
     out = {}
     try:
         with open(path) as f:
@@ -366,20 +427,25 @@ def load_traffic():
     return out
 
 
-def _blas_threads():
-    """Threads numpy's BLAS (the oracle's matrix products) actually runs with."""
+def _cpu_threads():
+    """Threads numpy's BLAS (the oracle's matrix products) runs with, and the cores the box reports."""
+    blas = 1
     try:
         from threadpoolctl import threadpool_info
         n = [i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"]
-        return int(max(n)) if n else 1
+        blas = int(max(n)) if n else 1
     except Exception:
-        return 1
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return blas, os.cpu_count() or 1, usable
 
 
 def cpu_baseline(wl, n_seqs):
     """The fp64 oracle, as it stands, on a bounded sample of the decode workload: the first
     `n_seqs` sequences of the batch through the same four layers.  Scaled to the full batch."""
-    import numpy as np
     import torch
     from oracle import kascade_oracle as ko
 
@@ -400,16 +466,19 @@ def cpu_baseline(wl, n_seqs):
         dt += time.perf_counter() - t0
         del host
     us_per_layer = dt * 1e6 / len(wl.layers) * (wl.B / n_seqs)
+    blas, cores, usable = _cpu_threads()
     return {"value": round(us_per_layer, 1), "unit": "us/layer (decode, scaled to the full batch)",
-            "cores": _blas_threads(), "kind": "oracle",
+            "cores": blas, "host_cores_reported": cores, "host_cores_usable": usable, "kind": "oracle",
+            "threads_note": "matrix products run on `cores` BLAS threads; the oracle's own loops are one Python thread",
             "sample": f"{n_seqs} of {wl.B} sequences, all heads, 1 anchor + 3 reuse layers, {dt:.2f} s measured"}
 
 
-def cpu_baseline_prefill(pb, tiles=(0, 1, 80, 81, 300, 600, 1023)):
-    """The fp64 oracle on a sample of query tiles of the prefill anchor layer (first tiles, the tiles
-    where 10 % of the prefix passes the minimum budget, some in between, the last one): pooled scores,
+def cpu_baseline_prefill(pb, n_random=16):
+    """The fp64 oracle on a sample of query tiles of the prefill anchor layer (the first tiles, the tiles
+    where 10 % of the prefix passes the minimum budget, the last one, and seeded random ones): pooled scores,
     Top-k and sparse attention per tile.  A tile's work grows with the keys before it, so the sample
     is extrapolated to the whole layer by (prefix + half a tile) and reported as such."""
+    import numpy as np
     import torch
     from oracle import kascade_oracle as ko
 
@@ -418,6 +487,8 @@ def cpu_baseline_prefill(pb, tiles=(0, 1, 80, 81, 300, 600, 1023)):
     f = lambda t: t.to("cpu").to(torch.float32).to(torch.float64).numpy()
     Q, Kp, Vp = f(a.q), f(a.k), f(a.v)
     scale = ko.default_scale(wl.d)
+    rs = np.random.default_rng(4)
+    tiles = sorted(set([0, 1, 80, 81, wl.n_tiles - 1] + rs.integers(2, wl.n_tiles, n_random).tolist()))
     tiles = [t for t in tiles if t < wl.n_tiles]
     weight = lambda t: t * wl.T + 0.5 * wl.T
     t0 = time.perf_counter()
@@ -428,9 +499,11 @@ def cpu_baseline_prefill(pb, tiles=(0, 1, 80, 81, 300, 600, 1023)):
     dt = time.perf_counter() - t0
     full_s = dt * sum(weight(t) for t in range(wl.n_tiles)) / sum(weight(t) for t in tiles)
     flop = 2.0 * pb.U + pb.sparse_flop
+    blas, cores, usable = _cpu_threads()
     return {"value": round(flop / full_s / 1e12, 5), "unit": "TFLOP/s (prefill anchor layer, sparse output, extrapolated)",
-            "cores": _blas_threads(), "kind": "oracle",
-            "sample": f"tiles {tiles} of {wl.n_tiles}, all heads, {dt:.2f} s measured, {full_s:.0f} s extrapolated by keys per tile",
+            "cores": blas, "host_cores_reported": cores, "host_cores_usable": usable, "kind": "oracle",
+            "sample": f"{len(tiles)} tiles of {wl.n_tiles} (first, budget boundary, last, {n_random} seeded random), all heads, "
+                      f"{dt:.2f} s measured, {full_s:.0f} s extrapolated by keys per tile",
             "anchor_layer_s_extrapolated": round(full_s, 1)}
 
 

@@ -290,21 +290,43 @@ size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max
 const char* kascade_status_string(int32_t status);
 
 /*
- * Measurement aid (not part of the method): per-kernel device time through HIP events.
- * kascade_profile_enable(1) makes every later kernel launch of the library record a start and
- * a stop event on the call's stream; events are created on demand (so do not enable it under
- * stream capture) and destroyed by kascade_profile_enable(0).  kascade_profile_read waits for
- * the recorded events of kernel `kernel` (0 <= kernel < kascade_profile_kernels()), and returns
- * its name, the summed elapsed milliseconds and the number of launches since the last
- * kascade_profile_reset().  With profiling off (the default) the library creates no events.
- * kascade_profile_calibrate launches `launches` empty kernels bracketed the same way (reported as
- * kernel "empty_kernel"): the duration an event pair reports for no work at all.
+ * Measurement aid (not part of the method): per-kernel device time.
+ * kascade_profile_enable(1) makes every later kernel dispatch of the library carry a start and a
+ * stop event bound to that dispatch (their difference is the dispatch's begin-to-end time on the
+ * device, the figure a kernel trace reports); events are created on demand (so do not enable it
+ * under stream capture) and destroyed by kascade_profile_enable(0).  kascade_profile_read waits
+ * for the recorded events of step `kernel` (0 <= kernel < kascade_profile_kernels()) and returns
+ * its name, the summed milliseconds of its dispatches and the number of times the step ran since
+ * the last kascade_profile_reset() (a step that takes several dispatches, such as the split Top-k
+ * selection, counts once).  With profiling off (the default) the library creates no events and
+ * launches plainly.  Process-wide state, guarded by a mutex.
  */
 int kascade_profile_enable(int32_t on);
-int kascade_profile_calibrate(int32_t launches, void* hip_stream);
 int kascade_profile_reset(void);
 int32_t kascade_profile_kernels(void);
 int kascade_profile_read(int32_t kernel, const char** name, double* total_ms, int64_t* launches);
+
+/*
+ * Test and measurement aid (not part of the method): overrides of the launch plan, process-wide.
+ * value 0 (the default) leaves the choice to the library.  The overrides change the number of
+ * partial results and with it kascade_workspace_bytes(): the size query and the call read the same
+ * process-wide value, and a call whose workspace is smaller than its plan needs returns
+ * KASCADE_WORKSPACE_TOO_SMALL as always.  The library reads no environment variables.
+ *   KASCADE_TUNE_DECODE_FAMILY  1 = vector-ALU decode row kernels, 2 = matrix-unit kernels (where both exist)
+ *   KASCADE_TUNE_STREAM_CHUNK   key rows per workgroup of the decode anchor's sweep (rounded up to 64)
+ *   KASCADE_TUNE_GATHER_CHUNK   index entries per workgroup of the decode gather (rounded up to 64)
+ *   KASCADE_TUNE_TOPK_PARTS     workgroups per (sequence, key head) of the decode selection (1 = one workgroup)
+ * Returns KASCADE_INVALID_ARG for an unknown knob or a negative value.
+ */
+enum {
+    KASCADE_TUNE_DECODE_FAMILY = 0,
+    KASCADE_TUNE_STREAM_CHUNK = 1,
+    KASCADE_TUNE_GATHER_CHUNK = 2,
+    KASCADE_TUNE_TOPK_PARTS = 3,
+    KASCADE_TUNE_COUNT = 4
+};
+int kascade_tuning_set(int32_t knob, int32_t value);
+int32_t kascade_tuning_get(int32_t knob);
 
 /* Library version, "major.minor". */
 const char* kascade_version(void);

@@ -411,25 +411,34 @@ def round_to_bf16(x):
     return rounded.astype(np.uint32).view(np.float32)
 
 
+def round_nearest_even(x, sig_bits, min_exp):
+    """Nearest value of a binary floating-point format to each float64 in x, ties to the
+    even neighbour, in ONE rounding.  The format has `sig_bits` significant bits (hidden
+    bit included) and smallest normal value 2**min_exp; below that the step stays that of
+    the smallest normals (subnormals).  bfloat16: (8, -126); binary16: (11, -14);
+    binary32: (24, -126).  Overflow to infinity is not modelled (not reachable from
+    averages of finite inputs of the same format).  Returns float64."""
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)                       # x = m * 2**e with 0.5 <= |m| < 1, so |x| < 2**e
+    step_exp = np.maximum(e - 1, min_exp) - (sig_bits - 1)
+    # x / step is exact (a power of two), rint rounds half to even, the product is exact
+    return np.ldexp(np.rint(np.ldexp(x, -step_exp)), step_exp)
+
+
+STORAGE_FORMATS = {"bf16": (8, -126), "fp16": (11, -14), "fp32": (24, -126)}
+
+
 def pool_query_vectors(rows, storage):
-    """Pooled query of Pre-Softmax pooling (Sec. 3.4): the average of the given
-    query vectors [n, d].  The average is itself a query the attention kernels
-    consume, so it exists in the tensors' storage type: accumulated in float32
-    in the order given, divided by n in float32, then rounded to `storage`
-    ("fp32": as is, "bf16" / "fp16": nearest even).  The rounding decides index sets, so
-    it is taken here exactly as on the device.  Returns float64 [d]."""
-    rows = np.asarray(rows, dtype=np.float32)
-    acc = np.zeros(rows.shape[1], dtype=np.float32)
-    for r in rows:
-        acc = acc + r
-    mean = acc / np.float32(rows.shape[0])
-    if storage == "bf16":
-        mean = round_to_bf16(mean)
-    elif storage == "fp16":
-        mean = mean.astype(np.float16).astype(np.float32)   # IEEE binary16, ties to even
-    elif storage != "fp32":
+    """Pooled query of Pre-Softmax pooling (Sec. 3.4): the average of the given query
+    vectors [n, d].  The average is itself a query that the attention kernels consume, so
+    it exists in the tensors' storage type: the mean is taken exactly (float64; the inputs
+    are 16- or 32-bit values) and rounded ONCE to `storage` ("fp32", "bf16", "fp16";
+    nearest, ties to even).  Returns float64 [d]."""
+    if storage not in STORAGE_FORMATS:
         raise ValueError("storage is 'fp32', 'bf16' or 'fp16'")
-    return mean.astype(np.float64)
+    rows = np.asarray(rows, dtype=np.float64)
+    mean = rows.sum(axis=0) / rows.shape[0]
+    return round_nearest_even(mean, *STORAGE_FORMATS[storage])
 
 
 def decode_presoftmax_indices(q, K, scale, k, storage, recent_window=0):

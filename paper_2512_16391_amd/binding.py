@@ -29,7 +29,7 @@ EXPORTS = [
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
     "kascade_decode_pooled", "kascade_topk_similarity", "kascade_select_anchor_layers",
     "kascade_head_similarity", "kascade_head_map", "kascade_layer_importance",
-    "kascade_profile_enable", "kascade_profile_calibrate", "kascade_profile_reset", "kascade_profile_kernels", "kascade_profile_read",
+    "kascade_profile_enable", "kascade_profile_reset", "kascade_tuning_set", "kascade_tuning_get", "kascade_profile_kernels", "kascade_profile_read",
 ]
 
 
@@ -100,8 +100,10 @@ def load_library(path: Optional[str] = None):
     lib.kascade_version.restype = ctypes.c_char_p
     lib.kascade_profile_enable.argtypes = [i32]
     lib.kascade_profile_enable.restype = ctypes.c_int
-    lib.kascade_profile_calibrate.argtypes = [i32, vp]
-    lib.kascade_profile_calibrate.restype = ctypes.c_int
+    lib.kascade_tuning_set.argtypes = [i32, i32]
+    lib.kascade_tuning_set.restype = ctypes.c_int
+    lib.kascade_tuning_get.argtypes = [i32]
+    lib.kascade_tuning_get.restype = i32
     lib.kascade_profile_reset.argtypes = []
     lib.kascade_profile_reset.restype = ctypes.c_int
     lib.kascade_profile_kernels.argtypes = []
@@ -125,8 +127,16 @@ def kascade_profile_enable(on: bool) -> None:
     _check(load_library().kascade_profile_enable(1 if on else 0), "kascade_profile_enable")
 
 
-def kascade_profile_calibrate(launches: int = 50) -> None:
-    _check(load_library().kascade_profile_calibrate(int(launches), _stream()), "kascade_profile_calibrate")
+TUNE_DECODE_FAMILY, TUNE_STREAM_CHUNK, TUNE_GATHER_CHUNK, TUNE_TOPK_PARTS = 0, 1, 2, 3
+DECODE_FAMILY_AUTO, DECODE_FAMILY_VECTOR, DECODE_FAMILY_MATRIX = 0, 1, 2
+
+
+def kascade_tuning_set(knob: int, value: int) -> None:
+    _check(load_library().kascade_tuning_set(int(knob), int(value)), "kascade_tuning_set")
+
+
+def kascade_tuning_get(knob: int) -> int:
+    return int(load_library().kascade_tuning_get(int(knob)))
 
 
 def kascade_profile_reset() -> None:

@@ -1,12 +1,16 @@
 // C ABI of the Kascade hot path: argument checks, launch planning, workspace carving.
-// No allocation, no synchronisation, no state kept between calls.
+// No device allocation and no synchronisation.  The attention calls keep nothing between calls; the only
+// process-wide state is what the two aids at the end of the header own: the tuning overrides
+// (kascade_tuning_set, four integers) and the per-kernel timing records (kascade_profile_*).
 #include "../../include/kascade.h"
 
+#include <hip/hip_ext.h>
 #include <limits.h>
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -24,12 +28,9 @@ constexpr int kTargetBlocks = 1024;   // about four workgroups per compute unit 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int64_t round_up_i(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-int env_int(const char* name, int fallback) {
-    const char* v = getenv(name);
-    if (!v || !*v) return fallback;
-    int x = atoi(v);
-    return x > 0 ? x : fallback;
-}
+// Tuning overrides (kascade_tuning_set): 0 = the library's own plan.  Test and measurement aids.
+std::atomic<int> g_tuning[KASCADE_TUNE_COUNT];
+int tuning(int knob) { return g_tuning[knob].load(std::memory_order_relaxed); }
 
 int check_desc(const kascade_desc* d, bool prefill) {
     if (!d) return KASCADE_INVALID_ARG;
@@ -73,7 +74,7 @@ Shape make_shape(const kascade_desc* d) {
 }
 
 // rows per workgroup for `n_rows` rows in each of `pairs` (sequence, key head) problems
-DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk, int max_chunks, const char* env_name) {
+DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk, int max_chunks, int forced_chunk) {
     DecodePlan p;
     if (max_chunks > kMaxChunks) max_chunks = kMaxChunks;
     int64_t want = (target_blocks + pairs - 1) / pairs;
@@ -82,7 +83,7 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
     if (chunk < min_chunk) chunk = min_chunk;
     const int64_t floor_chunk = round_up_i((n_rows + max_chunks - 1) / max_chunks, 256);
     if (chunk < floor_chunk) chunk = floor_chunk;
-    chunk = round_up_i(env_int(env_name, (int)chunk), 64);
+    if (forced_chunk > 0) chunk = round_up_i(forced_chunk, 64);
     if (chunk < floor_chunk) chunk = floor_chunk;
     p.chunk = (int)chunk;
     p.n_chunks = (int)((n_rows + chunk - 1) / chunk);
@@ -97,7 +98,9 @@ DecodePlan plan_rows(int64_t n_rows, int pairs, int target_blocks, int min_chunk
 // serves groups of eight heads is fastest with the same split.  Other shapes keep that older rule.
 DecodePlan plan_gather(const Shape& s, int64_t k_max) {
     const int pairs = s.B * s.Hkv;
-    if (s.dtype != 0 && s.D == 128 && !getenv("KASCADE_GATHER_CHUNK")) {
+    const int forced = tuning(KASCADE_TUNE_GATHER_CHUNK);
+    if (k_max < 1) k_max = 1;   // a size query may ask about an empty budget
+    if (s.dtype != 0 && s.D == 128 && forced == 0) {
         int64_t n = 512 / pairs;
         n = n < 1 ? 1 : (n > 64 ? 64 : n);
         DecodePlan p;
@@ -106,10 +109,10 @@ DecodePlan plan_gather(const Shape& s, int64_t k_max) {
         if (p.n_chunks < 1) p.n_chunks = 1;
         return p;
     }
-    DecodePlan p = plan_rows(k_max, pairs, kTargetBlocks, 256, 64, "KASCADE_GATHER_CHUNK");
+    DecodePlan p = plan_rows(k_max, pairs, kTargetBlocks, 256, 64, forced);
     // 256 rows are a single pass of a workgroup; if that still leaves three or more workgroups per compute
     // unit, two passes per workgroup amortise its start-up and merge better (measured, cold caches)
-    if (p.chunk == 256 && !getenv("KASCADE_GATHER_CHUNK") && (int64_t)p.n_chunks * pairs >= 3 * 256) {
+    if (p.chunk == 256 && forced == 0 && (int64_t)p.n_chunks * pairs >= 3 * 256) {
         p.chunk = 512;
         p.n_chunks = (int)((k_max + 511) / 512);
     }
@@ -118,15 +121,14 @@ DecodePlan plan_gather(const Shape& s, int64_t k_max) {
 // stream: many small workgroups - with ragged sequence lengths whole chunks fall away and few large
 // workgroups leave a long tail (measured: 1024 rows per workgroup wherever the 256-chunk limit allows;
 // with ragged lengths 2048 is 4 % slower)
-DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) { return plan_rows(max_seqlen, s.B * s.Hkv, 32 * kTargetBlocks, 1024, 256, "KASCADE_STREAM_CHUNK"); }
+DecodePlan plan_stream(const Shape& s, int64_t max_seqlen) {
+    return plan_rows(max_seqlen, s.B * s.Hkv, 32 * kTargetBlocks, 1024, 256, tuning(KASCADE_TUNE_STREAM_CHUNK));
+}
 
 // Workgroups per segment of the decode selection.  One is the single-workgroup kernel; more pay two extra
 // launches, so the split is used only when segments are few (the chip would idle) and long.
 int plan_topk_parts(const Shape& s, int64_t max_seqlen) {
-    if (const char* e = getenv("KASCADE_TOPK_PARTS")) {
-        const int v = atoi(e);
-        return v < 1 ? 1 : (v > kTopkMaxParts ? kTopkMaxParts : v);
-    }
+    if (const int v = tuning(KASCADE_TUNE_TOPK_PARTS)) return v > kTopkMaxParts ? kTopkMaxParts : v;
     const int64_t segments = (int64_t)s.B * s.Hkv;
     if (segments > 128 || max_seqlen < 65536) return 1;          // measured: no gain below 64k scores per segment
     int64_t parts = 256 / segments;                               // about one workgroup per compute unit in total
@@ -243,14 +245,13 @@ int hip_status(hipError_t e) { return e == hipSuccess ? KASCADE_OK : KASCADE_HIP
 // way.  The matrix-unit kernels are ahead from four heads on (batch 8 x 32768, 128-wide heads, four heads: gather
 // 19.5 -> 15.6 us, key sweep 101 -> 96 us, sweep with dense output 191 -> 184 us; eight heads: 34.5 -> 18 us,
 // 161 -> 101 us, 385 -> 194 us; 64-wide heads, four heads: gather 10.9 -> 8.2 us) and equal or a little behind
-// below that.  KASCADE_DECODE_MFMA=0/1 forces one or the other (tests).
+// below that.  kascade_tuning_set(KASCADE_TUNE_DECODE_FAMILY, 1 / 2) forces one or the other (tests).
 bool use_matrix_unit(const Shape& s) {
     if (s.dtype == 0 || s.G > 16) return false;
     if (s.dtype == 2) return true;   // fp16 exists on the matrix unit only
     if (s.G != 1 && s.G != 2 && s.G != 4 && s.G != 8) return true;   // the only kernels for these groups
-    bool mfma = s.G >= 4;
-    if (const char* e = getenv("KASCADE_DECODE_MFMA")) mfma = *e == '1';
-    return mfma;
+    const int forced = tuning(KASCADE_TUNE_DECODE_FAMILY);
+    return forced ? forced == 2 : s.G >= 4;
 }
 // Attention over a gathered index list.
 hipError_t launch_gather(const Shape& s, const DecodePlan& plan, const DecodeRowsArgs& a, hipStream_t st) {
@@ -264,21 +265,24 @@ hipError_t launch_stream(const Shape& s, const DecodePlan& plan, const DecodeRow
 }
 
 // ---- optional per-kernel timing (measurement aid, off by default) -----------------
-// When enabled every kernel launch is bracketed by two hipEvents on the call's stream.
-// Events are created on demand and kept until profiling is disabled; with profiling off
-// the library creates nothing.
+// When enabled, every kernel dispatch carries its own start and stop event (hipExtLaunchKernelGGL): both
+// events are bound to the dispatch itself, so their difference is the dispatch's begin-to-end time on the
+// device - the figure a kernel trace of the same run reports - and not the time between two markers around
+// it.  Events are created on demand and kept until profiling is disabled; with profiling off the library
+// creates nothing and launches plainly.
 enum KernelId { K_STREAM = 0, K_STREAM_V, K_GATHER, K_MERGE, K_POOL, K_TOPK, K_PF_SWEEP1, K_PF_SWEEP1_V, K_PF_SWEEP2,
-                K_PF_TOPK, K_PF_SPARSE, K_NULL, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_POOL_HEADS, K_POOL_QUERIES, K_COUNT };
+                K_PF_TOPK, K_PF_SPARSE, K_SIMILARITY, K_HEAD_MAP, K_IMPORTANCE, K_POOL_HEADS, K_POOL_QUERIES, K_COUNT };
 const char* const kKernelNames[K_COUNT] = {
     "decode_stream", "decode_stream_v", "decode_gather", "decode_merge", "decode_pool", "decode_topk",
-    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse", "empty_kernel",
+    "prefill_sweep1", "prefill_sweep1_v", "prefill_sweep2", "prefill_topk", "prefill_sparse",
     "similarity", "head_map", "layer_importance", "pool_heads", "pool_queries"};
 
 struct ProfRec { int kid; hipEvent_t start, stop; };
 struct Profiler {
-    bool on = false;
+    std::atomic<bool> on{false};
     std::vector<ProfRec> recs;
     std::vector<hipEvent_t> free_events;
+    int64_t calls[K_COUNT] = {};
     std::mutex mu;
     hipEvent_t get() {
         if (!free_events.empty()) { hipEvent_t e = free_events.back(); free_events.pop_back(); return e; }
@@ -287,18 +291,34 @@ struct Profiler {
         return e;
     }
 } g_prof;
+thread_local int t_current_kernel = -1;   // the step a launch on this thread belongs to, set by timed()
 
 template <typename F>
 int timed(int kid, hipStream_t st, F&& launch) {
-    if (!g_prof.on) return hip_status(launch());
-    std::lock_guard<std::mutex> lock(g_prof.mu);
-    ProfRec r{kid, g_prof.get(), g_prof.get()};
-    if (r.start) (void)hipEventRecord(r.start, st);
+    (void)st;
+    if (!g_prof.on.load(std::memory_order_relaxed)) return hip_status(launch());
+    { std::lock_guard<std::mutex> lock(g_prof.mu); g_prof.calls[kid] += 1; }
+    t_current_kernel = kid;
     const int rc = hip_status(launch());
-    if (r.stop) (void)hipEventRecord(r.stop, st);
-    if (r.start && r.stop) g_prof.recs.push_back(r);
+    t_current_kernel = -1;
     return rc;
 }
+
+}  // namespace
+
+// called by KASCADE_LAUNCH before every dispatch
+kascade::LaunchEvents kascade::next_launch_events() {
+    LaunchEvents ev = {nullptr, nullptr};
+    if (t_current_kernel < 0 || !g_prof.on.load(std::memory_order_relaxed)) return ev;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    ProfRec r{t_current_kernel, g_prof.get(), g_prof.get()};
+    if (!r.start || !r.stop) return ev;
+    g_prof.recs.push_back(r);
+    ev.start = r.start; ev.stop = r.stop;
+    return ev;
+}
+
+namespace {
 
 }  // namespace
 
@@ -306,31 +326,27 @@ extern "C" {
 
 const char* kascade_version(void) { return "0.1"; }
 
+int kascade_tuning_set(int32_t knob, int32_t value) {
+    if (knob < 0 || knob >= KASCADE_TUNE_COUNT || value < 0) return KASCADE_INVALID_ARG;
+    if (knob == KASCADE_TUNE_DECODE_FAMILY && value > 2) return KASCADE_INVALID_ARG;
+    g_tuning[knob].store(value, std::memory_order_relaxed);
+    return KASCADE_OK;
+}
+
+int32_t kascade_tuning_get(int32_t knob) {
+    if (knob < 0 || knob >= KASCADE_TUNE_COUNT) return KASCADE_INVALID_ARG;
+    return tuning(knob);
+}
+
 int kascade_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lock(g_prof.mu);
-    g_prof.on = on != 0;
-    if (!g_prof.on) {
+    g_prof.on.store(on != 0, std::memory_order_relaxed);
+    if (!on) {
         for (auto& r : g_prof.recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
         for (auto e : g_prof.free_events) (void)hipEventDestroy(e);
         g_prof.recs.clear();
         g_prof.free_events.clear();
-    }
-    return KASCADE_OK;
-}
-
-// An empty kernel bracketed like every other launch: what the event pair itself costs.
-__global__ void kascade_empty_kernel() {}
-
-int kascade_profile_calibrate(int32_t launches, void* hip_stream) {
-    if (launches <= 0) return KASCADE_INVALID_ARG;
-    if (!g_prof.on) return KASCADE_INVALID_ARG;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    for (int i = 0; i < launches; ++i) {
-        const int st = timed(K_NULL, stream, [&] {
-            hipLaunchKernelGGL(kascade_empty_kernel, dim3(1), dim3(64), 0, stream);
-            return hipGetLastError();
-        });
-        if (st != KASCADE_OK) return st;
+        for (auto& c : g_prof.calls) c = 0;
     }
     return KASCADE_OK;
 }
@@ -339,6 +355,7 @@ int kascade_profile_reset(void) {
     std::lock_guard<std::mutex> lock(g_prof.mu);
     for (auto& r : g_prof.recs) { g_prof.free_events.push_back(r.start); g_prof.free_events.push_back(r.stop); }
     g_prof.recs.clear();
+    for (auto& c : g_prof.calls) c = 0;
     return KASCADE_OK;
 }
 
@@ -349,14 +366,13 @@ int kascade_profile_read(int32_t kernel, const char** name, double* total_ms, in
     std::lock_guard<std::mutex> lock(g_prof.mu);
     *name = kKernelNames[kernel];
     *total_ms = 0.0;
-    *launches = 0;
+    *launches = g_prof.calls[kernel];
     for (auto& r : g_prof.recs) {
         if (r.kid != kernel) continue;
         if (hipEventSynchronize(r.stop) != hipSuccess) return KASCADE_HIP_ERROR;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) return KASCADE_HIP_ERROR;
         *total_ms += ms;
-        *launches += 1;
     }
     return KASCADE_OK;
 }
@@ -398,10 +414,10 @@ size_t kascade_workspace_bytes(int32_t op, const kascade_desc* desc, int64_t max
     }
 }
 
-int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
-                         const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_in,
-                         int32_t n_anchor_heads, const int32_t* head_map, void* out, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+static int decode_reuse_impl(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_in,
+                             int32_t n_anchor_heads, const int32_t* head_map, void* out, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
     int st = check_desc(desc, false);
     if (st != KASCADE_OK) return st;
     if (!q || !k_cache || !v_cache || !seqlens || !k_per_seq || !idx_in || !out) return KASCADE_INVALID_ARG;
@@ -423,6 +439,14 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
     if (plan.n_chunks > 1)
         st = timed(K_MERGE, stream, [&] { return launch_decode_merge(s, plan.n_chunks, ws.part_ml, ws.part_acc, out, stream); });
     return st;
+}
+
+int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_in,
+                         int32_t n_anchor_heads, const int32_t* head_map, void* out, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+    return decode_reuse_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, k_max, idx_in, n_anchor_heads, head_map, out,
+                             workspace, workspace_bytes, hip_stream);
 }
 
 static int decode_anchor_impl(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,

@@ -34,7 +34,8 @@ __global__ __launch_bounds__(kSimBlock) void similarity_kernel(SimilarityArgs a)
     const int L = a.seqlens[b];
     int k = a.k_per_seq[b];
     k = k < 0 ? 0 : (k > a.k_max ? a.k_max : k);
-    const int src = a.all_pairs ? (int)blockIdx.z : (a.head_map ? a.head_map[hk] : hk);
+    int src = a.all_pairs ? (int)blockIdx.z : (a.head_map ? a.head_map[hk] : hk);
+    src = src < 0 ? 0 : (src >= a.n_heads_a ? a.n_heads_a - 1 : src);   // a map entry out of range is held to the range, as in the gather kernels
     const float* row = a.pooled + ((int64_t)b * a.Hkv + hk) * a.pitch;
     const int32_t* ia = a.idx_a + ((int64_t)b * a.n_heads_a + src) * a.k_max;
     const int32_t* ib = a.idx_b + ((int64_t)b * a.Hkv + hk) * a.k_max;
@@ -120,11 +121,29 @@ __global__ __launch_bounds__(kSimBlock) void pool_heads_kernel(float* rows, int6
     }
 }
 
+// One rounding, to nearest with ties to even, from fp64 to the storage type T.  Going through fp32 first
+// would round twice (a mean a hair above a tie of T can land on the tie in fp32), so the 16-bit types are
+// rounded here: the value is divided by the spacing of T at its magnitude (a power of two, exact), rounded
+// to an integer by rint (ties to even), and multiplied back (exact); the result is representable in T and
+// in fp32, so the conversions that follow do not round.  SIG = significant bits, EMIN = exponent of the
+// smallest normal value (below it the spacing stays that of the smallest normals).
+template <int SIG, int EMIN>
+__device__ __forceinline__ float round_once(double x) {
+    if (x == 0.0) return (float)x;
+    int e = ilogb(x);                      // floor(log2 |x|)
+    e = (e < EMIN ? EMIN : e) - (SIG - 1);
+    return (float)scalbn(rint(scalbn(x, -e)), e);
+}
+template <typename T> __device__ __forceinline__ T narrow_once(double x);
+template <> __device__ __forceinline__ float narrow_once<float>(double x) { return (float)x; }   // one rounding by definition
+template <> __device__ __forceinline__ bf16_t narrow_once<bf16_t>(double x) { return narrow<bf16_t>(round_once<8, -126>(x)); }
+template <> __device__ __forceinline__ f16_t narrow_once<f16_t>(double x) { return narrow<f16_t>(round_once<11, -14>(x)); }
+
 // Pre-Softmax pooling (Sec. 3.4): the query vectors of one pooling unit - decode: the G heads of key
 // head hk for sequence `unit`; prefill: tokens [unit*T, min((unit+1)*T, S)) times those G heads - are
-// averaged into one query of the tensors' own type.  grid (Hkv, units), one thread per dimension; the
-// sum runs in fp32, tokens ascending and heads ascending inside a token, then one division and one
-// rounding, so the result is the same on every run and can be restated exactly on a CPU.
+// averaged into one query of the tensors' own type.  grid (Hkv, units), one thread per dimension.  The
+// sum runs in fp64, where sums of 16- or 32-bit values are exact for any realistic tile, so the order of
+// the additions does not matter; then one fp64 division and ONE rounding to the storage type.
 // tile_lens (prefill): receives unit*T, the number of keys before the tile, for unit < n_units.
 template <typename T>
 __global__ void pool_queries_kernel(const T* q, int64_t unit_stride, int64_t token_stride, int64_t head_stride, int G,
@@ -135,14 +154,14 @@ __global__ void pool_queries_kernel(const T* q, int64_t unit_stride, int64_t tok
     int hi = tiles ? lo + tokens_per_unit : 1;
     if (tiles && hi > n_tokens) hi = n_tokens;
     if (tiles && hk == 0 && c == 0) tile_lens[unit] = lo;
-    float acc = 0.f;
+    double acc = 0.0;
     for (int i = lo; i < hi; ++i) {
         const T* row = q + (tiles ? 0 : unit * unit_stride) + (int64_t)i * token_stride + (int64_t)hk * G * head_stride + c;
-        for (int g = 0; g < G; ++g) acc += widen1(row[g * head_stride]);
+        for (int g = 0; g < G; ++g) acc += (double)widen1(row[g * head_stride]);
     }
-    const float mean = acc / (float)((hi - lo) * G);
+    const double mean = acc / (double)((hi - lo) * G);
     T* dst = qbar + ((int64_t)unit * Hkv + hk) * D + c;
-    *dst = narrow<T>(mean);
+    *dst = narrow_once<T>(mean);
 }
 
 }  // namespace
@@ -152,13 +171,13 @@ hipError_t launch_pool_queries(int dtype, const void* q, int64_t unit_stride, in
                                int32_t* tile_lens, hipStream_t st) {
     const dim3 grid(Hkv, n_units), block(D);
     if (dtype == 0)
-        hipLaunchKernelGGL(pool_queries_kernel<float>, grid, block, 0, st, (const float*)q, unit_stride, token_stride,
+        KASCADE_LAUNCH(pool_queries_kernel<float>, grid, block, 0, st, (const float*)q, unit_stride, token_stride,
                            head_stride, G, tokens_per_unit, n_tokens, (float*)qbar, Hkv, D, tile_lens);
     else if (dtype == 1)
-        hipLaunchKernelGGL(pool_queries_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)q, unit_stride, token_stride,
+        KASCADE_LAUNCH(pool_queries_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)q, unit_stride, token_stride,
                            head_stride, G, tokens_per_unit, n_tokens, (bf16_t*)qbar, Hkv, D, tile_lens);
     else
-        hipLaunchKernelGGL(pool_queries_kernel<f16_t>, grid, block, 0, st, (const f16_t*)q, unit_stride, token_stride,
+        KASCADE_LAUNCH(pool_queries_kernel<f16_t>, grid, block, 0, st, (const f16_t*)q, unit_stride, token_stride,
                            head_stride, G, tokens_per_unit, n_tokens, (f16_t*)qbar, Hkv, D, tile_lens);
     return hipGetLastError();
 }
@@ -166,19 +185,19 @@ hipError_t launch_pool_queries(int dtype, const void* q, int64_t unit_stride, in
 hipError_t launch_pool_heads(float* rows, int64_t batch_pitch, int64_t head_pitch, int n_heads, int n_batches, int64_t n,
                              const int32_t* lens, int32_t* zero_map, hipStream_t st) {
     const dim3 grid((unsigned)((n + kSimBlock * 4 - 1) / (kSimBlock * 4)), n_batches);
-    hipLaunchKernelGGL(pool_heads_kernel, grid, dim3(kSimBlock), 0, st, rows, batch_pitch, head_pitch, n_heads, n, lens,
+    KASCADE_LAUNCH(pool_heads_kernel, grid, dim3(kSimBlock), 0, st, rows, batch_pitch, head_pitch, n_heads, n, lens,
                        zero_map);
     return hipGetLastError();
 }
 
 hipError_t launch_similarity(const SimilarityArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(similarity_kernel, dim3(a.Hkv, a.B, a.all_pairs ? a.n_heads_a : 1), dim3(kSimBlock), 0, st, a);
+    KASCADE_LAUNCH(similarity_kernel, dim3(a.Hkv, a.B, a.all_pairs ? a.n_heads_a : 1), dim3(kSimBlock), 0, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_head_map(int B, int Hkv, int Ha, const float* sim, float* mean_out, int32_t* head_map_out,
                            hipStream_t st) {
-    hipLaunchKernelGGL(head_map_kernel, dim3(Hkv), dim3(kWave), 0, st, B, Hkv, Ha, sim, mean_out, head_map_out);
+    KASCADE_LAUNCH(head_map_kernel, dim3(Hkv), dim3(kWave), 0, st, B, Hkv, Ha, sim, mean_out, head_map_out);
     return hipGetLastError();
 }
 
@@ -186,13 +205,13 @@ hipError_t launch_importance(int dtype, const void* x, const void* y, int64_t n_
                              int64_t y_stride, float* w_out, hipStream_t st) {
     const dim3 grid((unsigned)((n_rows + kSimBlock / kWave - 1) / (kSimBlock / kWave))), block(kSimBlock);
     if (dtype == 0)
-        hipLaunchKernelGGL(importance_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)y, n_rows, n_cols,
+        KASCADE_LAUNCH(importance_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)y, n_rows, n_cols,
                            x_stride, y_stride, w_out);
     else if (dtype == 1)
-        hipLaunchKernelGGL(importance_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)y, n_rows,
+        KASCADE_LAUNCH(importance_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)y, n_rows,
                            n_cols, x_stride, y_stride, w_out);
     else
-        hipLaunchKernelGGL(importance_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)y, n_rows,
+        KASCADE_LAUNCH(importance_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)y, n_rows,
                            n_cols, x_stride, y_stride, w_out);
     return hipGetLastError();
 }

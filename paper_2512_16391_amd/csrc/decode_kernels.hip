@@ -665,11 +665,11 @@ hipError_t launch_rows_tdg(const Shape& s, const DecodePlan& plan, const DecodeR
                            bool with_v, bool store, hipStream_t st) {
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kBlock);
     if (gather) {
-        hipLaunchKernelGGL((decode_rows_kernel<T, D, G, true, true, false>), grid, block, 0, st, s, plan, a);
+        KASCADE_LAUNCH((decode_rows_kernel<T, D, G, true, true, false>), grid, block, 0, st, s, plan, a);
     } else if (with_v) {
-        hipLaunchKernelGGL((decode_rows_kernel<T, D, G, false, true, true>), grid, block, 0, st, s, plan, a);
+        KASCADE_LAUNCH((decode_rows_kernel<T, D, G, false, true, true>), grid, block, 0, st, s, plan, a);
     } else {
-        hipLaunchKernelGGL((decode_rows_kernel<T, D, G, false, false, true>), grid, block, 0, st, s, plan, a);
+        KASCADE_LAUNCH((decode_rows_kernel<T, D, G, false, false, true>), grid, block, 0, st, s, plan, a);
     }
     (void)store;
     return hipGetLastError();
@@ -699,18 +699,18 @@ hipError_t launch_rows_bf16_dg(const Shape& s, const DecodePlan& plan, const Dec
     const bool small = gather && G <= 4 && wgs <= 4 * 256;
     if constexpr (D == 128 && G <= 4) {
         if (small && wgs <= 2 * 256) {
-            hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false, 16>), grid, block, 0, st, s, plan, a);
+            KASCADE_LAUNCH((decode_rows_bf16_kernel<D, G, true, true, false, false, 16>), grid, block, 0, st, s, plan, a);
             return hipGetLastError();
         }
     }
-    if (gather && small) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, false>), grid, block, 0, st, s, plan, a);
-    else if (gather) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, true, true, false, true>), grid, block, 0, st, s, plan, a);
-    else if (with_v) hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, true, true, true>), grid, block, 0, st, s, plan, a);
+    if (gather && small) KASCADE_LAUNCH((decode_rows_bf16_kernel<D, G, true, true, false, false>), grid, block, 0, st, s, plan, a);
+    else if (gather) KASCADE_LAUNCH((decode_rows_bf16_kernel<D, G, true, true, false, true>), grid, block, 0, st, s, plan, a);
+    else if (with_v) KASCADE_LAUNCH((decode_rows_bf16_kernel<D, G, false, true, true, true>), grid, block, 0, st, s, plan, a);
     else {
         // the K stream without V has registers to spare: 8 rows per batch halve a wave's round trips, which
         // shortens the tail of the launch (2 % at batch 64; no difference at batch 8)
         constexpr int US = (D == 128 && G <= 4) ? 8 : 4;
-        hipLaunchKernelGGL((decode_rows_bf16_kernel<D, G, false, false, true, true, US>), grid, block, 0, st, s, plan, a);
+        KASCADE_LAUNCH((decode_rows_bf16_kernel<D, G, false, false, true, true, US>), grid, block, 0, st, s, plan, a);
     }
     return hipGetLastError();
 }
@@ -745,12 +745,12 @@ hipError_t launch_decode_rows(const Shape& s, const DecodePlan& plan, const Deco
 hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_ml, const float* part_acc,
                                void* out, hipStream_t st) {
     dim3 grid(s.Hq, s.B);
-    if (s.dtype == 0 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<float, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 0 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<float, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 1 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 1 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<bf16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 2 && s.D == 64) hipLaunchKernelGGL((decode_merge_kernel<f16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
-    else if (s.dtype == 2 && s.D == 128) hipLaunchKernelGGL((decode_merge_kernel<f16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    if (s.dtype == 0 && s.D == 64) KASCADE_LAUNCH((decode_merge_kernel<float, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 0 && s.D == 128) KASCADE_LAUNCH((decode_merge_kernel<float, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 1 && s.D == 64) KASCADE_LAUNCH((decode_merge_kernel<bf16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 1 && s.D == 128) KASCADE_LAUNCH((decode_merge_kernel<bf16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 2 && s.D == 64) KASCADE_LAUNCH((decode_merge_kernel<f16_t, 64>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
+    else if (s.dtype == 2 && s.D == 128) KASCADE_LAUNCH((decode_merge_kernel<f16_t, 128>), grid, dim3(kWave), 0, st, s, n_chunks, part_ml, part_acc, out);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -758,13 +758,13 @@ hipError_t launch_decode_merge(const Shape& s, int n_chunks, const float* part_m
 hipError_t launch_decode_pool(const Shape& s, int n_chunks, const DecodePoolArgs& a, hipStream_t st) {
     dim3 grid((a.max_seqlen + kBlock * 4 - 1) / (kBlock * 4), s.Hkv, s.B), block(kBlock);
     switch (s.G) {
-        case 1: hipLaunchKernelGGL((decode_pool_kernel<1>), grid, block, 0, st, s, n_chunks, a); break;
-        case 2: hipLaunchKernelGGL((decode_pool_kernel<2>), grid, block, 0, st, s, n_chunks, a); break;
-        case 4: hipLaunchKernelGGL((decode_pool_kernel<4>), grid, block, 0, st, s, n_chunks, a); break;
-        case 8: hipLaunchKernelGGL((decode_pool_kernel<8>), grid, block, 0, st, s, n_chunks, a); break;
+        case 1: KASCADE_LAUNCH((decode_pool_kernel<1>), grid, block, 0, st, s, n_chunks, a); break;
+        case 2: KASCADE_LAUNCH((decode_pool_kernel<2>), grid, block, 0, st, s, n_chunks, a); break;
+        case 4: KASCADE_LAUNCH((decode_pool_kernel<4>), grid, block, 0, st, s, n_chunks, a); break;
+        case 8: KASCADE_LAUNCH((decode_pool_kernel<8>), grid, block, 0, st, s, n_chunks, a); break;
         default:
             if (s.G > 16) return hipErrorInvalidValue;
-            hipLaunchKernelGGL((decode_pool_kernel<0>), grid, block, 0, st, s, n_chunks, a);
+            KASCADE_LAUNCH((decode_pool_kernel<0>), grid, block, 0, st, s, n_chunks, a);
             break;
     }
     return hipGetLastError();

@@ -474,10 +474,10 @@ hipError_t launch_decode_gather_mfma(const Shape& s, const DecodePlan& plan, con
     if ((s.dtype != 1 && s.dtype != 2) || (s.D != 128 && s.D != 64) || s.G > 16) return hipErrorInvalidValue;
     dim3 grid(plan.n_chunks, s.Hkv, s.B), block(kMB);
     const bool f16 = s.dtype == 2;
-    if (s.D == 128 && !f16) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, true, false>), grid, block, 0, st, s, plan, a);
-    else if (s.D == 128) hipLaunchKernelGGL((decode_rows_mfma16_kernel<128, true, true>), grid, block, 0, st, s, plan, a);
-    else if (!f16) hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
-    else hipLaunchKernelGGL((decode_rows_mfma16_kernel<64, true, true>), grid, block, 0, st, s, plan, a);
+    if (s.D == 128 && !f16) KASCADE_LAUNCH((decode_rows_mfma16_kernel<128, true, false>), grid, block, 0, st, s, plan, a);
+    else if (s.D == 128) KASCADE_LAUNCH((decode_rows_mfma16_kernel<128, true, true>), grid, block, 0, st, s, plan, a);
+    else if (!f16) KASCADE_LAUNCH((decode_rows_mfma16_kernel<64, true, false>), grid, block, 0, st, s, plan, a);
+    else KASCADE_LAUNCH((decode_rows_mfma16_kernel<64, true, true>), grid, block, 0, st, s, plan, a);
     return hipGetLastError();
 }
 
@@ -490,8 +490,8 @@ hipError_t launch_decode_stream_mfma(const Shape& s, const DecodePlan& plan, con
     const bool f16 = s.dtype == 2;
 #define KASCADE_LAUNCH_SWEEP(D_, F_)                                                                                   \
     {                                                                                                                  \
-        if (with_v) hipLaunchKernelGGL((decode_rows_mfma16_kernel<D_, false, F_>), grid, block, 0, st, s, plan, a);     \
-        else hipLaunchKernelGGL((decode_sweep_mfma_kernel<D_, F_>), grid, block, 0, st, s, plan, a);                   \
+        if (with_v) KASCADE_LAUNCH((decode_rows_mfma16_kernel<D_, false, F_>), grid, block, 0, st, s, plan, a);     \
+        else KASCADE_LAUNCH((decode_sweep_mfma_kernel<D_, F_>), grid, block, 0, st, s, plan, a);                   \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_SWEEP(128, false)
     else if (s.D == 128) KASCADE_LAUNCH_SWEEP(128, true)

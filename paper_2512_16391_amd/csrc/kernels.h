@@ -2,10 +2,23 @@
 // Everything here is internal to the library.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
 namespace kascade {
+
+// Every kernel of the library is launched through KASCADE_LAUNCH.  When the per-kernel timing aid of the
+// C ABI is switched on, next_launch_events() hands out a start and a stop event that are bound to the
+// dispatch itself; otherwise both are null and the launch is a plain one.
+struct LaunchEvents { hipEvent_t start, stop; };
+LaunchEvents next_launch_events();
+#define KASCADE_LAUNCH(kernel_, grid_, block_, shmem_, stream_, ...)                                            \
+    do {                                                                                                        \
+        const ::kascade::LaunchEvents ev_ = ::kascade::next_launch_events();                                    \
+        if (ev_.start) hipExtLaunchKernelGGL(kernel_, grid_, block_, shmem_, stream_, ev_.start, ev_.stop, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel_, grid_, block_, shmem_, stream_, __VA_ARGS__);                          \
+    } while (0)
 
 struct Shape {
     int B, Hq, Hkv, D, G;

@@ -327,7 +327,9 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
                     _Pragma("unroll") for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;                      \
             }                                                                                                \
             m_run = m_new;                                                                                   \
-            neg_ref = -m_safe;                                                                               \
+            /* no key seen yet (every slot so far masked or ignored): keep forcing the exact path, so    */ \
+            /* that the first block with a live key sets the reference                                    */ \
+            neg_ref = (m_new == -INFINITY) ? INFINITY : -m_safe;                                             \
         }                                                                                                    \
         rs = half_swap_sum(rs);                                                                              \
         l_run += rs;                                                                                         \
@@ -535,9 +537,9 @@ hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool spar
     const bool f16 = s.dtype == 2;
 #define KASCADE_LAUNCH_ATTEND(DD, FF)                                                                                  \
     {                                                                                                                  \
-        if (sparse) hipLaunchKernelGGL((prefill_attend_kernel<DD, true, true, FF>), grid, block, 0, st, s, a);         \
-        else if (with_v) hipLaunchKernelGGL((prefill_attend_kernel<DD, false, true, FF>), grid, block, 0, st, s, a);   \
-        else hipLaunchKernelGGL((prefill_attend_kernel<DD, false, false, FF>), grid, block, 0, st, s, a);              \
+        if (sparse) KASCADE_LAUNCH((prefill_attend_kernel<DD, true, true, FF>), grid, block, 0, st, s, a);         \
+        else if (with_v) KASCADE_LAUNCH((prefill_attend_kernel<DD, false, true, FF>), grid, block, 0, st, s, a);   \
+        else KASCADE_LAUNCH((prefill_attend_kernel<DD, false, false, FF>), grid, block, 0, st, s, a);              \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_ATTEND(128, false)
     else if (s.D == 128) KASCADE_LAUNCH_ATTEND(128, true)
@@ -554,8 +556,8 @@ hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t
     const bool multi = a.tile_tokens != a.sub_tokens, f16 = s.dtype == 2;
 #define KASCADE_LAUNCH_POOL(DD, FF)                                                                              \
     {                                                                                                            \
-        if (multi) hipLaunchKernelGGL((prefill_pool_kernel<DD, true, FF>), grid, block, 0, st, s, a);            \
-        else hipLaunchKernelGGL((prefill_pool_kernel<DD, false, FF>), grid, block, 0, st, s, a);                 \
+        if (multi) KASCADE_LAUNCH((prefill_pool_kernel<DD, true, FF>), grid, block, 0, st, s, a);            \
+        else KASCADE_LAUNCH((prefill_pool_kernel<DD, false, FF>), grid, block, 0, st, s, a);                 \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_POOL(128, false)
     else if (s.D == 128) KASCADE_LAUNCH_POOL(128, true)

@@ -244,19 +244,19 @@ __global__ __launch_bounds__(kTopkBlock) void topk_split_compact_kernel(Shape s,
 hipError_t launch_topk_decode_split(const Shape& s, const TopkArgs& a, hipStream_t st) {
     if (!a.hist11 || !a.cand || !a.seg_info || !a.part_info || a.n_parts < 2 || a.n_parts > kTopkMaxParts)
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL(topk_split_collect_kernel, dim3(a.n_parts, s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
-    hipLaunchKernelGGL(topk_split_threshold_kernel, dim3(s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
-    hipLaunchKernelGGL(topk_split_compact_kernel, dim3(a.n_parts, s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
+    KASCADE_LAUNCH(topk_split_collect_kernel, dim3(a.n_parts, s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
+    KASCADE_LAUNCH(topk_split_threshold_kernel, dim3(s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
+    KASCADE_LAUNCH(topk_split_compact_kernel, dim3(a.n_parts, s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_topk_decode(const Shape& s, const TopkArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(topk_decode_kernel, dim3(s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
+    KASCADE_LAUNCH(topk_decode_kernel, dim3(s.Hkv, s.B), dim3(kTopkBlock), 0, st, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_topk_prefill(const Shape& s, const TopkArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(topk_prefill_kernel, dim3(a.n_tiles * s.Hkv), dim3(kTopkBlock), 0, st, s, a);
+    KASCADE_LAUNCH(topk_prefill_kernel, dim3(a.n_tiles * s.Hkv), dim3(kTopkBlock), 0, st, s, a);
     return hipGetLastError();
 }
 

@@ -86,6 +86,41 @@ int main() {
                             }
                         }
     EXPECT(kascade_workspace_bytes(99, nullptr, 1, 1, 1) == 0);
+    // an empty budget is a valid size query (k = 0): no division by a zero chunk, a finite answer
+    for (int dtype = 0; dtype < 3; ++dtype)
+        for (int d : {64, 128})
+            for (int B : {1, 8, 64, 1000})
+                for (int forced_chunk : {0, 1, 300}) {
+                    EXPECT(kascade_tuning_set(KASCADE_TUNE_GATHER_CHUNK, forced_chunk) == KASCADE_OK);
+                    kascade_desc x = make_desc(B, 32, 8, d, dtype, 4096);
+                    const size_t wr0 = kascade_workspace_bytes(KASCADE_OP_DECODE_REUSE, &x, 4096, 0, 0);
+                    const size_t wr1 = kascade_workspace_bytes(KASCADE_OP_DECODE_REUSE, &x, 4096, 1, 0);
+                    const size_t wa0 = kascade_workspace_bytes(KASCADE_OP_DECODE_ANCHOR, &x, 4096, 0, 0);
+                    const size_t wa1 = kascade_workspace_bytes(KASCADE_OP_DECODE_ANCHOR, &x, 4096, 1, 0);
+                    EXPECT(wr0 == wr1 && wa0 == wa1 && wa0 > wr0);
+                }
+    EXPECT(kascade_tuning_set(KASCADE_TUNE_GATHER_CHUNK, 0) == KASCADE_OK);
+    // ---- launch-plan overrides: validation, and the size query follows them
+    EXPECT(kascade_tuning_set(-1, 1) == KASCADE_INVALID_ARG);
+    EXPECT(kascade_tuning_set(KASCADE_TUNE_COUNT, 1) == KASCADE_INVALID_ARG);
+    EXPECT(kascade_tuning_set(KASCADE_TUNE_TOPK_PARTS, -3) == KASCADE_INVALID_ARG);
+    EXPECT(kascade_tuning_set(KASCADE_TUNE_DECODE_FAMILY, 3) == KASCADE_INVALID_ARG);
+    EXPECT(kascade_tuning_get(KASCADE_TUNE_COUNT) == KASCADE_INVALID_ARG);
+    {
+        kascade_desc x = make_desc(8, 32, 8, 128, KASCADE_BF16, 32768);
+        const size_t w_auto = kascade_workspace_bytes(KASCADE_OP_DECODE_REUSE, &x, 32768, 3277, 0);
+        EXPECT(kascade_tuning_set(KASCADE_TUNE_GATHER_CHUNK, 64) == KASCADE_OK);
+        EXPECT(kascade_tuning_get(KASCADE_TUNE_GATHER_CHUNK) == 64);
+        const size_t w_small = kascade_workspace_bytes(KASCADE_OP_DECODE_REUSE, &x, 32768, 3277, 0);
+        EXPECT(w_small > w_auto);                      // more chunks, more partial results
+        // a workspace sized before the override is refused, not overrun
+        EXPECT(kascade_decode_reuse(&x, fake, fake, fake, (int32_t*)fake, (int32_t*)fake, 3277, (int32_t*)fake, 8, nullptr,
+                                    fake, fake, w_auto, nullptr) == KASCADE_WORKSPACE_TOO_SMALL);
+        for (int knob = 0; knob < KASCADE_TUNE_COUNT; ++knob) {
+            EXPECT(kascade_tuning_set(knob, 0) == KASCADE_OK);
+            EXPECT(kascade_tuning_get(knob) == 0);
+        }
+    }
 
     // ---- argument validation (decode)
     kascade_desc good = make_desc(2, 8, 2, 128, KASCADE_BF16, 4096);

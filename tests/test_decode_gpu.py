@@ -414,7 +414,7 @@ def test_decode_anchor_split_selection_falls_back_when_all_scores_are_equal():
     assert max_abs(f64(out)[0], ref) <= TOL_OUT[dtype]
 
 
-def test_decode_anchor_split_and_single_selection_agree(monkeypatch):
+def test_decode_anchor_split_and_single_selection_agree(tuning):
     dtype, d, Hq, Hkv = torch.bfloat16, 128, 8, 2
     lens, ks = [45000, 36000, 66000], [4500, 3600, 1]
     wl = workloads.make_decode_workload("split-ab", 12, 1, 3, Hq, Hkv, d, dtype, lens, ks, 700, 0.8)
@@ -422,7 +422,7 @@ def test_decode_anchor_split_and_single_selection_agree(monkeypatch):
     args = (a.q.to(DEV), a.k.to(DEV), a.v.to(DEV), i32(lens), i32(ks), max(lens), max(ks))
     res = {}
     for parts in ("1", "7", "64"):
-        monkeypatch.setenv("KASCADE_TOPK_PARTS", parts)
+        tuning(binding.TUNE_TOPK_PARTS, int(parts))
         idx, out = binding.kascade_decode_anchor(*args)
         torch.cuda.synchronize()
         res[parts] = (idx.clone(), out.clone())
@@ -480,13 +480,13 @@ def test_decode_anchor_degenerate_sequences(dtype, d, Hq, Hkv, variant):
 
 
 @pytest.mark.parametrize("G,Hkv,d", [(1, 3, 128), (2, 2, 128), (4, 2, 128), (8, 2, 128), (8, 1, 128), (2, 2, 64), (8, 2, 64)])
-def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv, d):
+def test_decode_reuse_matrix_unit_kernel_every_group_size(tuning, G, Hkv, d):
     """The gather kernel that runs q.k and P.V on the matrix unit (the default from eight heads per key
     head on), forced for every group size: ragged batch, one and many chunks, a head map, unordered
     lists with entries to ignore, an empty sequence; and the same bits as the unforced default where
     that is the same kernel."""
     print(f"case decode reuse on the matrix unit G={G} Hkv={Hkv} d={d}", flush=True)
-    monkeypatch.setenv("KASCADE_DECODE_MFMA", "1")
+    tuning(binding.TUNE_DECODE_FAMILY, binding.DECODE_FAMILY_MATRIX)
     dtype = torch.bfloat16
     Hq = G * Hkv
     lens, ks = [9000, 0, 777, 131, 40000], [4100, 0, 777, 5, 2000]
@@ -521,7 +521,7 @@ def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv, d
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
     if G >= 8:
-        monkeypatch.delenv("KASCADE_DECODE_MFMA")
+        tuning(binding.TUNE_DECODE_FAMILY, binding.DECODE_FAMILY_AUTO)
         out3 = binding.kascade_decode_reuse(*args, head_map=i32(hm))
         torch.cuda.synchronize()
         assert torch.equal(out, out3)
@@ -529,13 +529,13 @@ def test_decode_reuse_matrix_unit_kernel_every_group_size(monkeypatch, G, Hkv, d
 
 @pytest.mark.parametrize("G,Hkv,d", [(1, 2, 128), (2, 2, 128), (4, 2, 128), (8, 2, 128), (8, 1, 128), (4, 2, 64), (8, 1, 64)])
 @pytest.mark.parametrize("out_mode", [0, 1])
-def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv, d, out_mode):
+def test_decode_anchor_matrix_unit_kernels_every_group_size(tuning, G, Hkv, d, out_mode):
     """The anchor's sweep over every key on the matrix unit (the default from eight heads per key head
     on), forced for every group size, with dense and sparse output: ragged lengths that end inside a
     pass, inside a run of eight logits and after a single key, an empty sequence, several chunks per
     sequence; and the same bits as the unforced default where that is the same kernel."""
     print(f"case decode anchor on the matrix unit G={G} Hkv={Hkv} d={d} out_mode={out_mode}", flush=True)
-    monkeypatch.setenv("KASCADE_DECODE_MFMA", "1")
+    tuning(binding.TUNE_DECODE_FAMILY, binding.DECODE_FAMILY_MATRIX)
     dtype = torch.bfloat16
     lens = [5000, 0, 1027, 1, 133, 2048]
     ks = [500, 0, 103, 1, 133, 64]
@@ -564,7 +564,7 @@ def test_decode_anchor_matrix_unit_kernels_every_group_size(monkeypatch, G, Hkv,
     print(f"  swaps {swaps}, max-abs {worst:.3e}", flush=True)
     assert worst <= TOL_OUT[dtype]
     if G >= 8:
-        monkeypatch.delenv("KASCADE_DECODE_MFMA")
+        tuning(binding.TUNE_DECODE_FAMILY, binding.DECODE_FAMILY_AUTO)
         idx2, out2 = binding.kascade_decode_anchor(q.to(DEV), k.to(DEV), v.to(DEV), i32(lens), i32(ks), max(lens),
                                                    max(ks), recent_window=W, out_mode=out_mode)
         torch.cuda.synchronize()

@@ -161,28 +161,54 @@ def bf16_ties_away(x):
 
 
 def pooled_query_is_the_sum(rows, storage):
-    rows = np.asarray(rows, dtype=np.float32)
-    acc = rows.sum(axis=0, dtype=np.float32)
-    return (ko.round_to_bf16(acc) if storage == "bf16" else acc).astype(np.float64)
+    acc = np.asarray(rows, dtype=np.float64).sum(axis=0)
+    return ko.round_nearest_even(acc, *ko.STORAGE_FORMATS[storage])
 
 
 def pooled_query_first_row(rows, storage):
-    row = np.asarray(rows, dtype=np.float32)[0]
-    return (ko.round_to_bf16(row) if storage == "bf16" else row).astype(np.float64)
+    row = np.asarray(rows, dtype=np.float64)[0]
+    return ko.round_nearest_even(row, *ko.STORAGE_FORMATS[storage])
 
 
 def pooled_query_fp16_truncates(rows, storage):
     if storage != "fp16":
         return ORIGINAL_POOL_QUERY_VECTORS(rows, storage)
+    mean = np.asarray(rows, dtype=np.float64).mean(axis=0)
+    up = mean.astype(np.float16)                      # nearest; step back where that went away from zero
+    away = np.abs(up.astype(np.float64)) > np.abs(mean)
+    toward = np.nextafter(up, np.float16(0.0))
+    return np.where(away, toward, up).astype(np.float64)
+
+
+def pooled_query_fp32_running_sum(rows, storage):
+    """the mean from a float32 running sum and a float32 division, then the storage rounding"""
     rows = np.asarray(rows, dtype=np.float32)
     acc = np.zeros(rows.shape[1], dtype=np.float32)
     for r in rows:
         acc = acc + r
-    mean = acc / np.float32(rows.shape[0])
-    up = mean.astype(np.float16)                      # nearest; step back where that went away from zero
-    away = np.abs(up.astype(np.float32)) > np.abs(mean)
-    toward = np.nextafter(up, np.float16(0.0))
-    return np.where(away, toward, up).astype(np.float64)
+    mean = (acc / np.float32(rows.shape[0])).astype(np.float64)
+    return ko.round_nearest_even(mean, *ko.STORAGE_FORMATS[storage])
+
+
+def pooled_query_rounded_twice(rows, storage):
+    """exact mean, but rounded to float32 first and to the storage type after that"""
+    mean = np.asarray(rows, dtype=np.float64).mean(axis=0).astype(np.float32).astype(np.float64)
+    return ko.round_nearest_even(mean, *ko.STORAGE_FORMATS[storage])
+
+
+def nearest_ties_away(x, sig_bits, min_exp):
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)
+    step_exp = np.maximum(e - 1, min_exp) - (sig_bits - 1)
+    y = np.ldexp(x, -step_exp)
+    return np.ldexp(np.sign(y) * np.floor(np.abs(y) + 0.5), step_exp)
+
+
+def nearest_without_subnormals(x, sig_bits, min_exp):
+    x = np.asarray(x, dtype=np.float64)
+    _, e = np.frexp(x)
+    step_exp = (e - 1) - (sig_bits - 1)
+    return np.ldexp(np.rint(np.ldexp(x, -step_exp)), step_exp)
 
 
 def pooled_query_fp16_as_bf16(rows, storage):
@@ -234,6 +260,10 @@ MUTATIONS = [
     P("pool_query_vectors", pooled_query_first_row, id="pooled query from one row"),
     P("pool_query_vectors", pooled_query_fp16_truncates, id="fp16 pooled query by truncation"),
     P("pool_query_vectors", pooled_query_fp16_as_bf16, id="fp16 pooled query rounded to bf16"),
+    P("pool_query_vectors", pooled_query_fp32_running_sum, id="pooled query from a float32 running sum"),
+    P("pool_query_vectors", pooled_query_rounded_twice, id="pooled query rounded twice"),
+    P("round_nearest_even", nearest_ties_away, id="storage rounding ties away from zero"),
+    P("round_nearest_even", nearest_without_subnormals, id="storage rounding without subnormals"),
     P("decode_presoftmax_indices", presoftmax_wrong_groups, id="pre-softmax pooling over the wrong heads"),
     P("prefill_presoftmax_indices_tile", presoftmax_tile_includes_diagonal, id="pre-softmax candidates include the tile"),
 ]

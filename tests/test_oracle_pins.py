@@ -506,18 +506,70 @@ def test_round_to_bf16_matches_library_conversion():
                                   np.array([0x3F800000, 0x3F820000, 0xBF800000, 0x41000000, 0x00020000], dtype=np.uint32))
 
 
+def test_round_nearest_even_is_one_correct_rounding():
+    """Pins for the single rounding from float64: library conversions that are known to round once
+    (numpy float64 -> float16 / float32; torch float32 -> bfloat16 on values that are float32 already), and
+    hand-built values on which rounding in two steps (float64 -> float32 -> bfloat16) gives another answer."""
+    r = rng(74)
+    x = r.standard_normal(20000) * 10.0 ** r.integers(-6, 5, 20000)
+    np.testing.assert_array_equal(ko.round_nearest_even(x, 11, -14), x.astype(np.float16).astype(np.float64))
+    np.testing.assert_array_equal(ko.round_nearest_even(x, 24, -126), x.astype(np.float32).astype(np.float64))
+    x32 = x.astype(np.float32)
+    lib = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(ko.round_nearest_even(x32.astype(np.float64), 8, -126), lib)
+    np.testing.assert_array_equal(ko.round_nearest_even(x32.astype(np.float64), 8, -126),
+                                  ko.round_to_bf16(x32).astype(np.float64))
+    # subnormal range of binary16 and of bfloat16: the step stops shrinking
+    tiny = np.array([2.0 ** -25, 3 * 2.0 ** -25, 2.0 ** -24, 5 * 2.0 ** -26, 0.0, -2.0 ** -25 * 1.0001])
+    np.testing.assert_array_equal(ko.round_nearest_even(tiny, 11, -14),
+                                  np.array([0.0, 2.0 ** -23, 2.0 ** -24, 2.0 ** -24, 0.0, -2.0 ** -24]))
+    np.testing.assert_array_equal(ko.round_nearest_even(np.array([2.0 ** -134, 3 * 2.0 ** -134]), 8, -126),
+                                  np.array([0.0, 2.0 ** -132]))
+    # 1 + 2^-8 is the tie between the bfloat16 neighbours 1 and 1 + 2^-7; a value a hair above it must go up,
+    # although its float32 rounding is the tie itself (which would then go to the even neighbour 1)
+    above = 1.0 + 2.0 ** -8 + 2.0 ** -40
+    assert np.float32(above) == np.float32(1.0 + 2.0 ** -8)
+    assert ko.round_nearest_even(above, 8, -126) == 1.0 + 2.0 ** -7
+    assert ko.round_nearest_even(1.0 + 2.0 ** -8, 8, -126) == 1.0
+    assert ko.round_nearest_even(1.0 + 3 * 2.0 ** -8, 8, -126) == 1.0 + 2.0 ** -6
+
+
 def test_pooled_query_is_the_rounded_mean():
     r = rng(71)
     rows = r.standard_normal((12, 16)).astype(np.float32).astype(np.float64)
     exact = rows.mean(axis=0)
-    np.testing.assert_allclose(ko.pool_query_vectors(rows, "fp32"), exact, rtol=0, atol=3e-7)
+    np.testing.assert_array_equal(ko.pool_query_vectors(rows, "fp32"), exact.astype(np.float32).astype(np.float64))
     pb = ko.pool_query_vectors(rows, "bf16")
-    assert np.all(np.abs(pb - exact) <= np.abs(exact) * 2.0 ** -8 + 1e-6)          # half a bf16 step, and a bit
+    assert np.all(np.abs(pb - exact) <= np.abs(exact) * 2.0 ** -8)                  # at most half a bf16 step
     assert np.all(pb.astype(np.float32).view(np.uint32) & 0xFFFF == 0)             # representable in bf16
     # one vector, or equal vectors: the pooled query is that vector (already representable)
     v = torch.randn(16, generator=torch.Generator().manual_seed(3)).to(torch.bfloat16).to(torch.float64).numpy()
     np.testing.assert_array_equal(ko.pool_query_vectors(np.tile(v, (4, 1)), "bf16"), v)
     np.testing.assert_array_equal(ko.pool_query_vectors(v[None], "fp32"), v)
+
+
+def test_pooled_query_mean_is_exact_before_the_one_rounding():
+    """Hand-built bf16 rows whose exact mean lies a hair above a bf16 tie.  A float32 running sum drops the
+    small addend (the sum then lands on the tie and goes to the even neighbour), and so does a mean that is
+    rounded to float32 before it is rounded to bf16; the definition - exact mean, one rounding - goes up."""
+    col = np.array([1.0 + 2.0 ** -5, 1.0, 1.0, 1.0, 1.0, 1.0, 2.0, 2.0 ** -30])    # every value is a bf16
+    assert col.sum() == 8.0 + 2.0 ** -5 + 2.0 ** -30                               # exact in float64
+    acc32 = np.float32(0.0)
+    for v in col:
+        acc32 = np.float32(acc32 + np.float32(v))
+    assert acc32 == np.float32(8.0 + 2.0 ** -5)                                    # the small addend is gone
+    rows = np.stack([col, col[::-1], -col], axis=1)                                # three components
+    want = np.array([1.0 + 2.0 ** -7, 1.0 + 2.0 ** -7, -(1.0 + 2.0 ** -7)])
+    np.testing.assert_array_equal(ko.pool_query_vectors(rows, "bf16"), want)
+    # binary16 analogue: mean 1 + 2^-11 + 2^-33, tie between 1 and 1 + 2^-10
+    col16 = np.array([1.0 + 2.0 ** -8, 1.0, 1.0, 1.0, 1.0, 1.0, 2.0, 2.0 ** -24])   # the last: smallest subnormal
+    got = ko.pool_query_vectors(col16[:, None], "fp16")
+    assert col16.sum() / 8 == 1.0 + 2.0 ** -11 + 2.0 ** -27
+    np.testing.assert_array_equal(got, np.array([1.0 + 2.0 ** -10]))
+    # fp32 storage: mean 1 + 2^-24 + 2^-50 from float32 rows, tie between 1 and 1 + 2^-23
+    col32 = np.array([1.0 + 2.0 ** -21, 1.0, 1.0, 1.0, 1.0, 1.0, 2.0, 2.0 ** -47])
+    assert col32.sum() / 8 == 1.0 + 2.0 ** -24 + 2.0 ** -50
+    np.testing.assert_array_equal(ko.pool_query_vectors(col32[:, None], "fp32"), np.array([1.0 + 2.0 ** -23]))
 
 
 def test_pooled_query_in_fp16_storage():

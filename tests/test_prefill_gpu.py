@@ -462,3 +462,83 @@ def test_prefill_holds_device_side_budgets_to_the_index_arrays(variant):
                                            head_map=dev_i32([0] * Hkv) if n_src == 1 else None)
     torch.cuda.synchronize()
     assert torch.equal(out, out_ok)
+
+
+@pytest.mark.parametrize("dtype", [BF16, torch.float16])
+@pytest.mark.parametrize("out_mode", [0, 1])
+def test_prefill_token_major_kv(dtype, out_mode):
+    """K and V stored token major, [S, Hkv, d], and handed over through kv_stride (head stride d, token
+    stride Hkv*d): anchor in both output modes, then a reuse layer with its own token-major K/V; ragged
+    last tile, two key heads next to each other in memory."""
+    print(f"case prefill token-major K/V dtype={dtype} out_mode={out_mode}", flush=True)
+    S, Hq, Hkv, d, T = 333, 8, 2, 128, 32
+    g = torch.Generator().manual_seed(91)
+    q = torch.randn(S, Hq, d, generator=g).to(dtype)
+    k_tm = torch.randn(S, Hkv, d, generator=g).to(dtype).to(DEV)
+    v_tm = torch.randn(S, Hkv, d, generator=g).to(dtype).to(DEV)
+    k, v = k_tm.permute(1, 0, 2), v_tm.permute(1, 0, 2)        # [Hkv, S, d] views of the token-major storage
+    assert k.stride() == (d, Hkv * d, 1) and not k.is_contiguous()
+    kpt = workloads.prefill_budgets(S, T, 250, 20)
+    idx, _ = run_anchor(q, k, v, T, kpt, out_mode, where="token-major anchor")
+    # the same call on a head-major copy gives the same bits (same arithmetic, other addresses)
+    off = offsets(kpt)
+    idx2, out2 = binding.kascade_prefill_anchor(q.to(DEV), k.contiguous(), v.contiguous(), T, dev_i32(kpt), dev_i64(off),
+                                                off[-1], out_mode=out_mode)
+    idx1, out1 = binding.kascade_prefill_anchor(q.to(DEV), k, v, T, dev_i32(kpt), dev_i64(off), off[-1], out_mode=out_mode)
+    torch.cuda.synchronize()
+    assert torch.equal(idx1, idx2) and torch.equal(out1, out2)
+    # reuse layer: fresh Q/K/V, again token major
+    q2 = torch.randn(S, Hq, d, generator=g).to(dtype)
+    k2 = torch.randn(S, Hkv, d, generator=g).to(dtype).to(DEV).permute(1, 0, 2)
+    v2 = torch.randn(S, Hkv, d, generator=g).to(dtype).to(DEV).permute(1, 0, 2)
+    out = binding.kascade_prefill_reuse(q2.to(DEV), k2, v2, T, dev_i32(kpt), dev_i64(off), off[-1], torch.from_numpy(idx).to(DEV))
+    torch.cuda.synchronize()
+    o, worst = f64(out), 0.0
+    for t, kt in enumerate(kpt):
+        lo, hi = ko.tile_bounds(t, T, S)
+        ref = ko.prefill_sparse_tile(f64(q2), f64(k2), f64(v2), t, T, [idx[h, off[t]:off[t] + kt] for h in range(Hkv)],
+                                     ko.default_scale(d))
+        worst = max(worst, max_abs(o[lo:hi], ref))
+    print(f"  token-major reuse: max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[dtype]
+
+
+@pytest.mark.parametrize("dtype", [BF16, torch.float16])
+def test_prefill_reuse_list_starts_with_ignored_entries_and_logits_far_below_zero(dtype):
+    """An index list whose first 64 or more entries are all entries to ignore (negative, or not before the
+    tile), so that the first key block of a tile holds no key at all, while every live logit lies far
+    below zero (about -150 in base 2): the running softmax must take its reference exponent from the
+    first block that holds a key, not from the empty one."""
+    print(f"case prefill reuse, list begins with ignored entries, dtype={dtype}", flush=True)
+    S, Hq, Hkv, d, T = 165, 8, 2, 128, 32
+    g = torch.Generator().manual_seed(17)
+    u = torch.randn(d, generator=g)
+    u = u / u.norm()
+    q = (0.2 * torch.randn(S, Hq, d, generator=g) - 40.0 * u).to(dtype)
+    k = (0.2 * torch.randn(Hkv, S, d, generator=g) + 30.0 * u).to(dtype)
+    v = torch.randn(Hkv, S, d, generator=g).to(dtype)
+    n_tiles = (S + T - 1) // T
+    kpt = [0, 0, 0, 90, 128, 128][:n_tiles]
+    n_bad = [0, 0, 0, 64, 64, 100][:n_tiles]
+    off = offsets(kpt)
+    rs = np.random.default_rng(5)
+    idx = np.full((Hkv, off[-1]), -1, dtype=np.int32)
+    sets = {}
+    for t in range(n_tiles):
+        sets[t] = []
+        for h in range(Hkv):
+            good = rs.permutation(rs.choice(t * T, kpt[t] - n_bad[t], replace=False)) if kpt[t] > n_bad[t] else np.zeros(0, np.int64)
+            bad = rs.choice([-1, -9, t * T, t * T + 5, S + 3], size=n_bad[t])
+            idx[h, off[t]:off[t] + kpt[t]] = np.concatenate([bad, good])
+            sets[t].append(np.asarray(good, dtype=np.int64))
+    out = binding.kascade_prefill_reuse(q.to(DEV), k.to(DEV), v.to(DEV), T, dev_i32(kpt), dev_i64(off), off[-1],
+                                        torch.from_numpy(idx).to(DEV))
+    torch.cuda.synchronize()
+    o, worst = f64(out), 0.0
+    assert np.isfinite(o).all()
+    for t in range(n_tiles):
+        lo, hi = ko.tile_bounds(t, T, S)
+        ref = ko.prefill_sparse_tile(f64(q), f64(k), f64(v), t, T, sets[t], ko.default_scale(d))
+        worst = max(worst, max_abs(o[lo:hi], ref))
+    print(f"  max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[dtype]
