@@ -109,6 +109,25 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
                          size_t workspace_bytes, void* hip_stream);
 
 /*
+ * kascade_decode_reuse for callers that cannot allocate or pass scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and bits as
+ * kascade_decode_reuse, minus the workspace: the partial results of the gather live in a fixed
+ * 8 MiB array in device memory that belongs to the library (each GPU the library runs on holds its own
+ * copy until the process ends; its address is looked up once per device on the first call there).  The
+ * call allocates nothing and frees nothing.  A shape whose partial results need more than
+ * kascade_decode_reuse_static_capacity() bytes - what kascade_workspace_bytes(KASCADE_OP_DECODE_REUSE, ...)
+ * reports - returns KASCADE_WORKSPACE_TOO_SMALL before anything is enqueued (the Llama-shaped
+ * configurations need about 1 MiB at any batch size).  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (two streams, two threads) race on it; calls on one stream do not.
+ * Nothing in the array has to start at zero: every call writes all partial results it later reads.
+ */
+int kascade_decode_reuse_static(const kascade_desc* desc, const void* q, const void* k_cache,
+                                const void* v_cache, const int32_t* seqlens, const int32_t* k_per_seq,
+                                int32_t k_max, const int32_t* idx_in, int32_t n_anchor_heads,
+                                const int32_t* head_map, void* out, void* hip_stream);
+size_t kascade_decode_reuse_static_capacity(void);
+
+/*
  * Prefill, anchor layer (Sec. 3.6 passes 1-4 with the score matrix recomputed in
  * pass 2; tile pooling of Sec. 3.4; rolling Top-k of Sec. 4.1).  batch = 1.
  * Tile t covers tokens [t*T, min((t+1)*T, S)), T = q_tile_tokens; its rows are those

@@ -24,6 +24,7 @@ OP_PREFILL_ANCHOR_PRESOFTMAX = 5
 
 EXPORTS = [
     "kascade_decode_anchor", "kascade_decode_reuse", "kascade_prefill_anchor", "kascade_prefill_reuse",
+    "kascade_decode_reuse_static", "kascade_decode_reuse_static_capacity",
     "kascade_decode_anchor_shared", "kascade_prefill_anchor_shared",
     "kascade_decode_anchor_presoftmax", "kascade_prefill_anchor_presoftmax",
     "kascade_workspace_bytes", "kascade_status_string", "kascade_version",
@@ -70,6 +71,10 @@ def load_library(path: Optional[str] = None):
     lib.kascade_decode_anchor_presoftmax.restype = ctypes.c_int
     lib.kascade_decode_reuse.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp, sz, vp]
     lib.kascade_decode_reuse.restype = ctypes.c_int
+    lib.kascade_decode_reuse_static.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, vp, vp, vp]
+    lib.kascade_decode_reuse_static.restype = ctypes.c_int
+    lib.kascade_decode_reuse_static_capacity.argtypes = []
+    lib.kascade_decode_reuse_static_capacity.restype = sz
     lib.kascade_prefill_anchor.argtypes = [dp, vp, vp, vp, i32, i32, vp, vp, i64, i32, vp, vp, vp, sz, vp]
     lib.kascade_prefill_anchor.restype = ctypes.c_int
     lib.kascade_prefill_anchor_shared.argtypes = lib.kascade_prefill_anchor.argtypes
@@ -273,6 +278,27 @@ def kascade_decode_reuse(q, k_cache, v_cache, seqlens, k_per_seq, k_max, idx_in,
                                   _ptr(out), _ptr(workspace), nbytes, _stream())
     _check(st, "kascade_decode_reuse")
     return out
+
+
+def kascade_decode_reuse_static(q, k_cache, v_cache, seqlens, k_per_seq, k_max, idx_in, head_map=None, out=None,
+                                softmax_scale=0.0, kv_layout="BHLD"):
+    """kascade_decode_reuse without a workspace (the library's fixed scratch array).  Returns out [B,Hq,d]."""
+    _need_gpu(q, k_cache, v_cache, seqlens, k_per_seq, idx_in, head_map, out)
+    lib = load_library()
+    if out is None:
+        out = torch.empty_like(q)
+    desc = decode_desc(q, k_cache, out, softmax_scale, kv_layout)
+    if idx_in.dtype != torch.int32 or not idx_in.is_contiguous() or idx_in.shape[2] != k_max:
+        raise ValueError("idx_in must be a contiguous int32 [B, Hkv_anchor, k_max] tensor")
+    st = lib.kascade_decode_reuse_static(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seqlens),
+                                         _ptr(k_per_seq), int(k_max), _ptr(idx_in), int(idx_in.shape[1]), _ptr(head_map),
+                                         _ptr(out), _stream())
+    _check(st, "kascade_decode_reuse_static")
+    return out
+
+
+def kascade_decode_reuse_static_capacity() -> int:
+    return int(load_library().kascade_decode_reuse_static_capacity())
 
 
 def kascade_prefill_anchor(q, k, v, q_tile_tokens, k_per_tile, idx_offsets, idx_total,

@@ -449,6 +449,48 @@ int kascade_decode_reuse(const kascade_desc* desc, const void* q, const void* k_
                              workspace, workspace_bytes, hip_stream);
 }
 
+// ---- the reuse layer for callers that cannot allocate ---------------------------------------------
+// The partial results of the gather (per chunk: max, sum, accumulator) live in a fixed array in device
+// memory that is part of the library's code object; every GPU the library runs on holds its own copy
+// until the process ends.  In host code the array's name is only a handle: the device address comes
+// from hipGetSymbolAddress, once per device, and that address is what the kernels receive.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+static int scratch_of_current_device(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return KASCADE_HIP_ERROR;
+    if (dev < 0 || dev >= kMaxDevices) return KASCADE_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KASCADE_HIP_ERROR;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return KASCADE_OK;
+}
+
+size_t kascade_decode_reuse_static_capacity(void) { return kStaticScratchBytes; }
+
+int kascade_decode_reuse_static(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                                const int32_t* seqlens, const int32_t* k_per_seq, int32_t k_max, const int32_t* idx_in,
+                                int32_t n_anchor_heads, const int32_t* head_map, void* out, void* hip_stream) {
+    // sizes first: a shape whose partial results do not fit the fixed array is refused before anything else
+    if (check_desc(desc, false) == KASCADE_OK && k_max > 0) {
+        const Shape s = make_shape(desc);
+        if (carve_decode_reuse(s, plan_gather(s, k_max), nullptr).bytes > kStaticScratchBytes) return KASCADE_WORKSPACE_TOO_SMALL;
+    }
+    void* ptr = nullptr;
+    const int st = scratch_of_current_device(&ptr);
+    if (st != KASCADE_OK) return st;
+    return decode_reuse_impl(desc, q, k_cache, v_cache, seqlens, k_per_seq, k_max, idx_in, n_anchor_heads, head_map, out,
+                             ptr, kStaticScratchBytes, hip_stream);
+}
+
 static int decode_anchor_impl(const kascade_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                               const int32_t* seqlens, const int32_t* k_per_seq, int32_t max_seqlen, int32_t k_max,
                               int32_t recent_window, int32_t out_mode, int32_t* idx_out, void* out, void* workspace,
