@@ -13,15 +13,18 @@
 // at a block's maximum only when a term would exceed 2^30.
 //
 //  prefill_attend_kernel  flash-style attention over a key list:
-//      dense  - all keys up to the diagonal, causal (anchor pass 1, Sec. 3.6): emits the row
-//               statistics (max, sum) and, for layer 0, the dense output;
+//      dense  - all keys up to the diagonal, causal, with the dense output (anchor pass 1 of layer 0, Sec. 3.6);
 //      sparse - the tile's Top-k index list plus its diagonal block (reuse layers / pass 4).
 //      Scores are computed transposed (S^T = K Q^T) so that a lane owns one query row and the
 //      row max / row sum are in-lane reductions; O^T = V^T P^T accumulates in the same layout.
-//  prefill_pool_kernel    anchor pass 2: recomputes S = Q K^T over the strict prefix,
-//      normalises with the known statistics and sums the tile's 128 rows per key
-//      (post-softmax pooling, Sec. 3.4).  Here a lane owns one key column, so the row sum is
-//      again in-lane.
+//  prefill_stats_kernel   anchor pass 1 when only the row statistics (max, sum) are wanted: the same causal
+//      sweep without V, 64 rows per wave, the products of one key block issued between the exponentials of
+//      the block before.
+//  prefill_pool2_kernel   anchor pass 2 for 128-row tiles: recomputes S = Q K^T over the strict prefix,
+//      normalises with the known statistics and sums the tile's rows per key (post-softmax pooling,
+//      Sec. 3.4); a lane owns one key column, so the column sum is in-lane.  Same product order as the
+//      statistics kernel; then pass 3 (per-tile Top-k) in the same workgroup.
+//  prefill_pool_kernel    the same for tiles of more than 128 rows, swept in 128-row parts.
 #include <limits.h>
 
 #include "device_utils.h"
@@ -384,6 +387,272 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     }
 }
 
+// Anchor pass 1 when only the row statistics are wanted (anchors other than layer 0, Sec. 3.6): the causal
+// Q K^T sweep of prefill_attend_kernel without V and without an output.  Same tiles, same direct loads,
+// same transposed product (a lane owns a query row).  What differs is the order of the work inside a
+// wave: over the blocks that lie entirely before the workgroup's own tokens (no mask, every key exists)
+// the matrix products of block kb+1 are issued between the exponentials of block kb - one product, then
+// six vector operations - with two sets of score registers, so that a single wave keeps the matrix pipe
+// and the vector ALU busy at the same time instead of alternating between a phase of sixteen products
+// and a phase of a hundred vector operations.  (With phases, the four waves of a SIMD fall into step:
+// counters show the matrix pipe and the vector ALU busy together for only a quarter of the time.)
+// The reference exponent of that stretch is the row maximum of block 0 and is not looked at again; a row
+// whose sum overflows fp32 (a logit more than 2^127 above block 0's maximum) sends the whole workgroup
+// through the careful loop from the start.  The last blocks (causal mask, ragged end) always take the
+// careful loop, which continues from the state the fast stretch leaves.
+template <int D, bool F16>
+__global__ __launch_bounds__(kPB, 2) void prefill_stats_kernel(Shape s, PrefillArgs a) {
+    constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
+    constexpr int PF = 4;   // fragment reads issued ahead of the products that use them
+    // two tiles as two arrays: the compiler then knows that a fragment read from one cannot see a direct
+    // load into the other, and does not wait for the loads in flight before every read
+    __shared__ __align__(16) unsigned char smK0[TILE];
+    __shared__ __align__(16) unsigned char smK1[TILE];
+
+    // A workgroup owns two consecutive 128-row units (256 rows); wave w owns 64 rows of unit u0 + w/2: rows
+    // 64 (w%2) + q and 64 (w%2) + 32 + q of that unit for lane q - every K fragment read from LDS feeds two products.
+    const int hk = blockIdx.x % s.Hkv;
+    const int n_pairs = (a.n_sub + 1) / 2;
+    const int u0 = 2 * (n_pairs - 1 - blockIdx.x / s.Hkv);     // long ones first
+    const int Ts = a.sub_tokens, S = a.seqlen;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane & 31, h = lane >> 5;
+    const int u = u0 + (w >> 1);
+    const RowMap rmA = map_row((w & 1) * 64 + q, u, Ts, hk, s.G, S);
+    const RowMap rmB = map_row((w & 1) * 64 + 32 + q, u, Ts, hk, s.G, S);
+    const int tokA = rmA.ok ? rmA.token : INT_MAX - 1, tokB = rmB.ok ? rmB.token : INT_MAX - 1;
+    const float c = s.scale_log2;
+    const int own = u0 * Ts;                                    // first token of the workgroup's rows
+    const int diag_end = (own + 2 * Ts < S) ? own + 2 * Ts : S;
+    const int n_blocks = (diag_end + BK - 1) / BK;
+    const int n_full = own / BK;                                // blocks whose keys all precede every row here
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
+    const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
+    const uint32_t coff = Dma<D>::chunk_off();
+    // a whole block of existing rows: uniform block/pass offset + a constant per-thread part, no clamping
+    const uint32_t tofs = (uint32_t)(threadIdx.x / Dma<D>::PPR) * row_bytes + coff;
+#define KASCADE_DMA_FULL(tile_, kb_)                                                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < Dma<D>::PASSES; ++i_) {                                          \
+        const unsigned char* src_ = Kb + (size_t)((kb_) * BK + i_ * Dma<D>::RPP) * row_bytes + (size_t)tofs; \
+        __builtin_amdgcn_global_load_lds((gmem_ptr_t)src_, (lds_ptr_t)((tile_) + (i_ * kPB + w * kWave) * 16), 16, 0, 0); \
+    }
+
+    bf16x8_t qa[KSTEPS], qb[KSTEPS];
+    {
+        const bf16_t* pa = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rmA.token * s.q_stride[1] + (int64_t)rmA.head * s.q_stride[2];
+        const bf16_t* pb = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rmB.token * s.q_stride[1] + (int64_t)rmB.head * s.q_stride[2];
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 ra = make_uint4(0, 0, 0, 0), rb = make_uint4(0, 0, 0, 0);
+            if (rmA.ok) ra = *reinterpret_cast<const uint4*>(pa + kk * 16 + h * 8);
+            if (rmB.ok) rb = *reinterpret_cast<const uint4*>(pb + kk * 16 + h * 8);
+            qa[kk] = __builtin_bit_cast(bf16x8_t, ra);
+            qb[kk] = __builtin_bit_cast(bf16x8_t, rb);
+        }
+    }
+    // LDS byte offsets of this lane's K fragments (key slot perm_key(q), k-step kk); the second 32 keys of a
+    // block are a constant offset from them
+    const int key0 = perm_key(q);
+    int fo[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) fo[kk] = k_off<D>(key0, kk * 2 + h);
+    constexpr int KEY1 = 32 * D * 2;
+
+    // this lane's share of its two rows' sums, against the rows' reference exponents (the other half-wave holds
+    // the other keys of the same rows); two chains per row so that the additions do not wait for each other
+    float mA = -INFINITY, mB = -INFINITY, nrA = INFINITY, nrB = INFINITY;
+    float la0 = 0.f, la1 = 0.f, lb0 = 0.f, lb1 = 0.f;
+    f32x16_t zero;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+
+    // S^T of one block: (xa0, xa1) = keys 0-31 / 32-63 against row A, (xb0, xb1) against row B; plain order
+#define KASCADE_STATS_SCORES(tK_, xa0_, xa1_, xb0_, xb1_)                                    \
+    {                                                                                        \
+        _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                               \
+            const bf16x8_t f0_ = lds_frag((tK_) + fo[kk]);                                   \
+            const bf16x8_t f1_ = lds_frag((tK_) + fo[kk] + KEY1);                            \
+            xa0_ = Mma<F16>::mma32(f0_, qa[kk], kk == 0 ? zero : xa0_);                      \
+            xb0_ = Mma<F16>::mma32(f0_, qb[kk], kk == 0 ? zero : xb0_);                      \
+            xa1_ = Mma<F16>::mma32(f1_, qa[kk], kk == 0 ? zero : xa1_);                      \
+            xb1_ = Mma<F16>::mma32(f1_, qb[kk], kk == 0 ? zero : xb1_);                      \
+        }                                                                                    \
+    }
+    // the exponentials of one block's scores into the four chains
+#define KASCADE_STATS_EXPS(ca0_, ca1_, cb0_, cb1_)                                           \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                          \
+        la0 += __builtin_amdgcn_exp2f(fmaf(ca0_[r], c, nrA));                                \
+        lb0 += __builtin_amdgcn_exp2f(fmaf(cb0_[r], c, nrB));                                \
+        la1 += __builtin_amdgcn_exp2f(fmaf(ca1_[r], c, nrA));                                \
+        lb1 += __builtin_amdgcn_exp2f(fmaf(cb1_[r], c, nrB));                                \
+    }
+    // products of the block in tile tN_ into the n registers interleaved with the exponentials of the block
+    // whose scores are in the c registers, in an order written out step by step and fenced so that the compiler
+    // keeps it: per product two scale-and-shift, two exp2 and the two additions of the step before (an exp2
+    // result is never used by the next instruction), per two products one fragment read, issued PF reads
+    // ahead.  The empty asm statement pins the results to this point of the program: without it the compiler
+    // moves the arithmetic of one block across the barrier into the next.
+#define KASCADE_STATS_PIPE(tN_, na0_, na1_, nb0_, nb1_, ca0_, ca1_, cb0_, cb1_)              \
+    {                                                                                        \
+        constexpr int PPS_ = 32 / (4 * KSTEPS);   /* (row A, row B) score pairs per product */ \
+        __builtin_amdgcn_sched_barrier(0);                                                   \
+        bf16x8_t fr_[2 * KSTEPS];                                                            \
+        _Pragma("unroll") for (int j_ = 0; j_ < PF; ++j_)                                     \
+            fr_[j_] = lds_frag((tN_) + fo[j_ >> 1] + ((j_ & 1) ? KEY1 : 0));                 \
+        float pea_[PPS_], peb_[PPS_];   /* the exponentials of the step before */            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4 * KSTEPS; ++i_) {                           \
+            const int kk_ = i_ >> 2;                                                         \
+            if ((i_ & 1) == 0 && (i_ >> 1) + PF < 2 * KSTEPS) {                              \
+                const int j_ = (i_ >> 1) + PF;                                               \
+                fr_[j_] = lds_frag((tN_) + fo[j_ >> 1] + ((j_ & 1) ? KEY1 : 0));             \
+            }                                                                                \
+            if ((i_ & 3) == 0) na0_ = Mma<F16>::mma32(fr_[2 * kk_], qa[kk_], kk_ == 0 ? zero : na0_);          \
+            else if ((i_ & 3) == 1) nb0_ = Mma<F16>::mma32(fr_[2 * kk_], qb[kk_], kk_ == 0 ? zero : nb0_);     \
+            else if ((i_ & 3) == 2) na1_ = Mma<F16>::mma32(fr_[2 * kk_ + 1], qa[kk_], kk_ == 0 ? zero : na1_); \
+            else nb1_ = Mma<F16>::mma32(fr_[2 * kk_ + 1], qb[kk_], kk_ == 0 ? zero : nb1_);                    \
+            _Pragma("unroll") for (int p_ = 0; p_ < PPS_; ++p_) {                             \
+                const int P_ = i_ * PPS_ + p_, r_ = P_ >> 1;   /* pair P_: key half P_ & 1, register r_ */ \
+                const float xa_ = fmaf((P_ & 1) ? ca1_[r_] : ca0_[r_], c, nrA);              \
+                const float xb_ = fmaf((P_ & 1) ? cb1_[r_] : cb0_[r_], c, nrB);              \
+                if (i_ > 0) { if ((P_ - PPS_) & 1) { la1 += pea_[p_]; lb1 += peb_[p_]; } else { la0 += pea_[p_]; lb0 += peb_[p_]; } } \
+                pea_[p_] = __builtin_amdgcn_exp2f(xa_);                                      \
+                peb_[p_] = __builtin_amdgcn_exp2f(xb_);                                      \
+            }                                                                                \
+            __builtin_amdgcn_sched_barrier(0);                                               \
+        }                                                                                    \
+        _Pragma("unroll") for (int p_ = 0; p_ < PPS_; ++p_) {                                 \
+            if ((32 - PPS_ + p_) & 1) { la1 += pea_[p_]; lb1 += peb_[p_]; } else { la0 += pea_[p_]; lb0 += peb_[p_]; } \
+        }                                                                                    \
+        asm volatile("" : "+v"(na0_), "+v"(na1_), "+v"(nb0_), "+v"(nb1_), "+v"(la0), "+v"(la1), "+v"(lb0), "+v"(lb1)); \
+        __builtin_amdgcn_sched_barrier(0);                                                   \
+    }
+#define KASCADE_ROW_MAX(x0_, x1_, out_)                                                      \
+    {                                                                                        \
+        float mx_ = x0_[0];                                                                  \
+        _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, x0_[r]);              \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) mx_ = fmaxf(mx_, x1_[r]);              \
+        out_ = half_swap_max(mx_ * c);                                                       \
+    }
+
+    int kb_start = 0;
+    if (n_full >= 3) {
+        // ---- the fast stretch: blocks 0 .. n_full-1 ----
+        f32x16_t sa0, sa1, sb0, sb1, ta0, ta1, tb0, tb1;
+        KASCADE_DMA_FULL(smK0, 0)
+        wait_vmem();
+        __syncthreads();
+        KASCADE_DMA_FULL(smK1, 1)
+        KASCADE_STATS_SCORES(smK0, sa0, sa1, sb0, sb1)
+        // reference exponents: the row maxima of block 0
+        KASCADE_ROW_MAX(sa0, sa1, mA)
+        KASCADE_ROW_MAX(sb0, sb1, mB)
+        nrA = -mA; nrB = -mB;
+        // iteration kb: tile kb has landed in buffer kb & 1; its products run between the exponentials of
+        // block kb-1; tile kb+1 streams into the other buffer meanwhile
+        int kb = 1;
+        for (; kb + 1 < n_full; kb += 2) {
+            wait_vmem();
+            __syncthreads();
+            KASCADE_DMA_FULL(smK0, kb + 1)
+            KASCADE_STATS_PIPE(smK1, ta0, ta1, tb0, tb1, sa0, sa1, sb0, sb1)
+            wait_vmem();
+            __syncthreads();
+            if (kb + 2 < n_full) { KASCADE_DMA_FULL(smK1, kb + 2) }
+            KASCADE_STATS_PIPE(smK0, sa0, sa1, sb0, sb1, ta0, ta1, tb0, tb1)
+        }
+        if (kb < n_full) {      // one block left for the products (odd count): its scores end up in the t registers
+            wait_vmem();
+            __syncthreads();
+            KASCADE_STATS_PIPE(smK1, ta0, ta1, tb0, tb1, sa0, sa1, sb0, sb1)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { sa0[r] = ta0[r]; sa1[r] = ta1[r]; sb0[r] = tb0[r]; sb1[r] = tb1[r]; }
+        }
+        // the exponentials of the last block
+        KASCADE_STATS_EXPS(sa0, sa1, sb0, sb1)
+        const float partA = la0 + la1, partB = lb0 + lb1;
+        const int overflowed = __syncthreads_or(!(partA <= 3.0e38f) || !(partB <= 3.0e38f));   // also the barrier that frees the tiles
+        if (overflowed) {
+            mA = mB = -INFINITY; nrA = nrB = INFINITY;
+            la0 = la1 = lb0 = lb1 = 0.f;
+        } else {
+            la0 = partA; lb0 = partB; la1 = lb1 = 0.f;
+            kb_start = n_full;
+        }
+    }
+#undef KASCADE_STATS_PIPE
+#undef KASCADE_DMA_FULL
+
+    // ---- the careful loop: blocks kb_start .. n_blocks-1, two at a time so that the tile is a constant ----
+    // exp2 against the lagging reference; a block whose share of a row's sum is not a modest finite number
+    // (the first block: the reference is still +inf) renews that row's reference from the scores, which are
+    // still in registers.  Masks where the block reaches the workgroup's own tokens: key position > row's token.
+#define KASCADE_STATS_ROW(x0_, x1_, tok_, m_, nr_, l_, kb_)                                                    \
+    {                                                                                                          \
+        if (((kb_) + 1) * BK > own) {                                                                          \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                    \
+                const int slot = (kb_) * BK + (r >> 3) * 16 + h * 8 + (r & 7);                                 \
+                if (slot > tok_) x0_[r] = -INFINITY;                                                           \
+                if (slot + 32 > tok_) x1_[r] = -INFINITY;                                                      \
+            }                                                                                                  \
+        }                                                                                                      \
+        float rs = 0.f;                                                                                        \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                          \
+            rs += __builtin_amdgcn_exp2f(fmaf(x0_[r], c, nr_)) + __builtin_amdgcn_exp2f(fmaf(x1_[r], c, nr_)); \
+        if (__builtin_amdgcn_ballot_w64(!(rs <= 1073741824.f)) != 0) {                                         \
+            float mx;                                                                                          \
+            KASCADE_ROW_MAX(x0_, x1_, mx)                                                                      \
+            const float m_new = fmaxf(m_, mx);                                                                 \
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;                                           \
+            const float alpha = __builtin_amdgcn_exp2f(m_ - m_safe);   /* 0 while m_ is -inf */                \
+            rs = 0.f;                                                                                          \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r)                                                      \
+                rs += __builtin_amdgcn_exp2f(fmaf(x0_[r], c, -m_safe)) + __builtin_amdgcn_exp2f(fmaf(x1_[r], c, -m_safe)); \
+            l_ *= alpha;                                                                                       \
+            m_ = m_new;                                                                                        \
+            nr_ = (m_new == -INFINITY) ? INFINITY : -m_safe;                                                   \
+        }                                                                                                      \
+        l_ += rs;                                                                                              \
+    }
+#define KASCADE_STATS_CAREFUL(tK_, tNext_, kb_)                                                                \
+    {                                                                                                          \
+        wait_vmem();                                                                                           \
+        __syncthreads();                                                                                       \
+        f32x16_t xa0, xa1, xb0, xb1;                                                                           \
+        KASCADE_STATS_SCORES(tK_, xa0, xa1, xb0, xb1)                                                          \
+        if ((kb_) + 1 < n_blocks) dma_rows_seq<D>(tNext_, Kb, row_bytes, ((kb_) + 1) * BK, diag_end - 1, coff, w); \
+        KASCADE_STATS_ROW(xa0, xa1, tokA, mA, nrA, la0, kb_)                                                   \
+        KASCADE_STATS_ROW(xb0, xb1, tokB, mB, nrB, lb0, kb_)                                                   \
+    }
+    if (kb_start < n_blocks) dma_rows_seq<D>(smK0, Kb, row_bytes, kb_start * BK, diag_end - 1, coff, w);
+    {
+        int kb = kb_start;
+        for (; kb + 1 < n_blocks; kb += 2) {
+            KASCADE_STATS_CAREFUL(smK0, smK1, kb)
+            KASCADE_STATS_CAREFUL(smK1, smK0, kb + 1)
+        }
+        if (kb < n_blocks) { KASCADE_STATS_CAREFUL(smK0, smK1, kb) }
+    }
+#undef KASCADE_STATS_CAREFUL
+#undef KASCADE_STATS_ROW
+#undef KASCADE_ROW_MAX
+#undef KASCADE_STATS_EXPS
+#undef KASCADE_STATS_SCORES
+
+    const float lA = half_swap_sum(la0), lB = half_swap_sum(lb0);
+    if (a.stats && h == 0) {
+        if (rmA.ok) {
+            float* st = a.stats + ((int64_t)rmA.head * S + rmA.token) * 2;
+            st[0] = mA; st[1] = lA;
+        }
+        if (rmB.ok) {
+            float* st = a.stats + ((int64_t)rmB.head * S + rmB.token) * 2;
+            st[0] = mB; st[1] = lB;
+        }
+    }
+}
+
 // One 64-key block of anchor pass 2 for this wave: S = Q K^T from the staged tile, pooled
 // weights 2^(s c - e_r), column sums over the wave's 32 rows into part[w][key].
 template <int D, bool F16>
@@ -414,8 +683,8 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
 // Anchor pass 2 with two K tiles in LDS filled by direct loads: block kb+1 streams in while block
 // kb is multiplied; one barrier per block.  The cross-wave sum of block kb's column partials is
 // taken after the next barrier (two partial buffers), so it needs no barrier of its own.
-// MULTI: the tile has more than 128 rows and is swept in parts (kept out of the one-part kernel,
-// whose register budget it would break).
+// MULTI: the tile has more than 128 rows and is swept in parts (the form that runs: 128-row tiles go to
+// prefill_pool2_kernel).
 template <int D, bool MULTI, bool F16>
 __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
@@ -529,17 +798,254 @@ __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shap
     }
 }
 
+// Anchor pass 2 for tiles of exactly 128 rows (the paper's configuration), with the product order of
+// prefill_stats_kernel: a workgroup owns two consecutive tiles of one key head (256 rows), a wave 64 rows of
+// one of them, so that every K fragment read from LDS feeds two products; and the products of one half block
+// (32 keys) are issued between the exponentials of the half block before it.  S = Q K^T is not transposed
+// here - a lane owns a key column, the registers are rows - so the tile's column sums are in-lane additions;
+// two sets of score registers take turns (products into one while the vector ALU empties the other).
+// Column partials of the four waves meet in LDS (three rotating buffers: a block's second half is pooled
+// one barrier later than its first) and leave as coalesced stores two barriers after the block's products.
+// Both tiles sweep the longer prefix (T more keys than the first tile's); what a tile computes beyond its
+// own prefix is not stored.  Pass 3 (per-tile Top-k) follows in the same workgroup, one tile after the other.
+template <int D, bool F16>
+__global__ __launch_bounds__(kPB, 2) void prefill_pool2_kernel(Shape s, PrefillArgs a) {
+    constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
+    constexpr int PF = 4;
+    constexpr int PARTSZ = kPW * BK;   // floats per buffer of column partials
+    // The two tiles, the partials and the selection's state are separate arrays: the compiler then knows that
+    // a read from one cannot see a direct load into another, and does not wait for the loads in flight first.
+    __shared__ __align__(16) unsigned char smK0[TILE];
+    __shared__ __align__(16) unsigned char smK1[TILE];
+    __shared__ __align__(16) float smPart[3 * PARTSZ];
+    __shared__ SelectShared<kPB> smSel;
+
+    const int hk = blockIdx.x % s.Hkv;
+    const int n_pairs = (a.n_tiles + 1) / 2;
+    const int tA = 2 * (n_pairs - 1 - blockIdx.x / s.Hkv);      // long ones first
+    const int T = a.tile_tokens, S = a.seqlen;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane & 31, h = lane >> 5;
+    const int tw = tA + (w >> 1);                                 // this wave's tile
+    const bool tileB = tA + 1 < a.n_tiles;
+    const int prefixA = tA * T, prefixB = tileB ? prefixA + T : 0;
+    const int sweep = tileB ? prefixB : prefixA;                  // keys 0 .. sweep-1 are swept
+    if (sweep == 0) return;
+    const float c = s.scale_log2;
+    const int n_blocks = (sweep + BK - 1) / BK;
+
+    const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
+    const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
+    const uint32_t coff = Dma<D>::chunk_off();
+    const uint32_t tofs = (uint32_t)(threadIdx.x / Dma<D>::PPR) * row_bytes + coff;
+    // stage block kb_: whole blocks by uniform offsets, the ragged last one with clamped rows
+#define KASCADE_POOL_STAGE(tile_, kb_)                                                                          \
+    if (((kb_) + 1) * BK <= sweep) {                                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < Dma<D>::PASSES; ++i_) {                                          \
+            const unsigned char* src_ = Kb + (size_t)((kb_) * BK + i_ * Dma<D>::RPP) * row_bytes + (size_t)tofs; \
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)src_, (lds_ptr_t)((tile_) + (i_ * kPB + w * kWave) * 16), 16, 0, 0); \
+        }                                                                                                       \
+    } else {                                                                                                    \
+        dma_rows_seq<D>(tile_, Kb, row_bytes, (kb_) * BK, sweep - 1, coff, w);                                  \
+    }
+
+    // rows of this wave: 64 (w%2) + q (block A) and + 32 (block B) of tile tw; row rho of a tile is head rho / T,
+    // token rho % T
+    const RowMap rmA = map_row((w & 1) * 64 + q, tw, T, hk, s.G, S);
+    const RowMap rmB = map_row((w & 1) * 64 + 32 + q, tw, T, hk, s.G, S);
+    bf16x8_t qa[KSTEPS], qb[KSTEPS];
+    {
+        const bf16_t* pa = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rmA.token * s.q_stride[1] + (int64_t)rmA.head * s.q_stride[2];
+        const bf16_t* pb = reinterpret_cast<const bf16_t*>(a.q) + (int64_t)rmB.token * s.q_stride[1] + (int64_t)rmB.head * s.q_stride[2];
+        const bool live = tw < a.n_tiles;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            uint4 ra = make_uint4(0, 0, 0, 0), rb = make_uint4(0, 0, 0, 0);
+            if (live && rmA.ok) ra = *reinterpret_cast<const uint4*>(pa + kk * 16 + h * 8);
+            if (live && rmB.ok) rb = *reinterpret_cast<const uint4*>(pb + kk * 16 + h * 8);
+            qa[kk] = __builtin_bit_cast(bf16x8_t, ra);
+            qb[kk] = __builtin_bit_cast(bf16x8_t, rb);
+        }
+    }
+    // exponent offsets e = m + log2(l * rows of the tile) of the query rows whose scores land in this lane's
+    // registers; rows beyond the sequence (and a missing second tile) get weight 0
+    float ea[16], eb[16];
+    {
+        const int tile_end = ((tw + 1) * T < S) ? (tw + 1) * T : S;
+        const float rows = (float)((tile_end - tw * T) * s.G);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rho = (w & 1) * 64 + (r >> 2) * 8 + h * 4 + (r & 3);
+            const RowMap ra_ = map_row(rho, tw, T, hk, s.G, S), rb_ = map_row(rho + 32, tw, T, hk, s.G, S);
+            ea[r] = INFINITY; eb[r] = INFINITY;
+            if (tw < a.n_tiles && ra_.ok) {
+                const float* st = a.stats + ((int64_t)ra_.head * S + ra_.token) * 2;
+                ea[r] = st[0] + __builtin_amdgcn_logf(st[1] * rows);
+            }
+            if (tw < a.n_tiles && rb_.ok) {
+                const float* st = a.stats + ((int64_t)rb_.head * S + rb_.token) * 2;
+                eb[r] = st[0] + __builtin_amdgcn_logf(st[1] * rows);
+            }
+        }
+    }
+    // LDS byte offsets of this lane's K fragments: key column q of a half block, k-step kk
+    int fo[KSTEPS];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) fo[kk] = k_off<D>(q, kk * 2 + h);
+    constexpr int KEY1 = 32 * D * 2;
+    f32x16_t zero;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+    float* const dstA = a.pooled + hk * a.pooled_pitch + (int64_t)T * tA * (tA - 1) / 2;
+    float* const dstB = a.pooled + hk * a.pooled_pitch + (int64_t)T * (tA + 1) * tA / 2;
+
+    // products of one half block: keys KOFF_ .. KOFF_+31 of tile tK_ against both row blocks
+#define KASCADE_POOL_MMA(tK_, KOFF_, xa_, xb_)                                               \
+    _Pragma("unroll") for (int kk = 0; kk < KSTEPS; ++kk) {                                   \
+        const bf16x8_t f_ = lds_frag((tK_) + fo[kk] + (KOFF_));                              \
+        xa_ = Mma<F16>::mma32(qa[kk], f_, kk == 0 ? zero : xa_);                             \
+        xb_ = Mma<F16>::mma32(qb[kk], f_, kk == 0 ? zero : xb_);                             \
+    }
+    // pooled weights of one half block, summed over this wave's 64 rows for the lane's key column
+#define KASCADE_POOL_SUM(xa_, xb_, out_)                                                     \
+    {                                                                                        \
+        float c0_ = 0.f, c1_ = 0.f, c2_ = 0.f, c3_ = 0.f;   /* four chains: the additions do not wait for each other */ \
+        _Pragma("unroll") for (int r = 0; r < 16; r += 2) {                                   \
+            c0_ += __builtin_amdgcn_exp2f(fmaf(xa_[r], c, -ea[r]));                          \
+            c1_ += __builtin_amdgcn_exp2f(fmaf(xb_[r], c, -eb[r]));                          \
+            c2_ += __builtin_amdgcn_exp2f(fmaf(xa_[r + 1], c, -ea[r + 1]));                  \
+            c3_ += __builtin_amdgcn_exp2f(fmaf(xb_[r + 1], c, -eb[r + 1]));                  \
+        }                                                                                    \
+        out_ = (c0_ + c1_) + (c2_ + c3_);                                                    \
+    }
+    // one pipeline step: products of a half block into (na_, nb_) between the exponentials of the half block in
+    // (ca_, cb_), whose column sums go to pdst_[q]; the order is written out product by product and fenced so
+    // that the compiler keeps it (per product two scale-and-shift, two exp2, and the two additions of the
+    // product before; per two products one fragment read, PF reads ahead)
+#define KASCADE_POOL_PIPE(tK_, KOFF_, na_, nb_, ca_, cb_, pdst_)                             \
+    {                                                                                        \
+        constexpr int PPS_ = 16 / (2 * KSTEPS);   /* (row block A, row block B) score pairs per product */ \
+        __builtin_amdgcn_sched_barrier(0);                                                   \
+        bf16x8_t fr_[KSTEPS];                                                                \
+        _Pragma("unroll") for (int j_ = 0; j_ < (PF < KSTEPS ? PF : KSTEPS); ++j_) fr_[j_] = lds_frag((tK_) + fo[j_] + (KOFF_)); \
+        float pea_[PPS_], peb_[PPS_], c0_ = 0.f, c1_ = 0.f, c2_ = 0.f, c3_ = 0.f;            \
+        _Pragma("unroll") for (int i_ = 0; i_ < 2 * KSTEPS; ++i_) {                           \
+            const int kk_ = i_ >> 1;                                                         \
+            if ((i_ & 1) == 0 && kk_ + PF < KSTEPS) fr_[kk_ + PF] = lds_frag((tK_) + fo[kk_ + PF] + (KOFF_)); \
+            if ((i_ & 1) == 0) na_ = Mma<F16>::mma32(qa[kk_], fr_[kk_], kk_ == 0 ? zero : na_); \
+            else nb_ = Mma<F16>::mma32(qb[kk_], fr_[kk_], kk_ == 0 ? zero : nb_);            \
+            _Pragma("unroll") for (int p_ = 0; p_ < PPS_; ++p_) {                             \
+                const int r_ = i_ * PPS_ + p_;                                               \
+                const float xa_ = fmaf(ca_[r_], c, -ea[r_]);                                 \
+                const float xb_ = fmaf(cb_[r_], c, -eb[r_]);                                 \
+                if (i_ > 0) { if (i_ & 1) { c0_ += pea_[p_]; c1_ += peb_[p_]; } else { c2_ += pea_[p_]; c3_ += peb_[p_]; } } \
+                pea_[p_] = __builtin_amdgcn_exp2f(xa_);                                      \
+                peb_[p_] = __builtin_amdgcn_exp2f(xb_);                                      \
+            }                                                                                \
+            __builtin_amdgcn_sched_barrier(0);                                               \
+        }                                                                                    \
+        _Pragma("unroll") for (int p_ = 0; p_ < PPS_; ++p_) { c2_ += pea_[p_]; c3_ += peb_[p_]; } \
+        const float cs_ = half_swap_sum((c0_ + c1_) + (c2_ + c3_));                          \
+        if (h == 0) (pdst_)[q] = cs_;                                                        \
+        asm volatile("" : "+v"(na_), "+v"(nb_));                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                   \
+    }
+    // the tile's column sums of block kb_: threads 0-63 the first tile, 64-127 the second
+#define KASCADE_POOL_STORE(kb_)                                                              \
+    if (threadIdx.x < 2 * BK) {                                                              \
+        const int tl_ = threadIdx.x >> 6, j_ = (kb_) * BK + (threadIdx.x & 63);              \
+        if (j_ < (tl_ ? prefixB : prefixA)) {                                                \
+            const float* pp_ = smPart + ((kb_) % 3) * PARTSZ + 2 * tl_ * BK + (threadIdx.x & 63); \
+            (tl_ ? dstB : dstA)[j_] = pp_[0] + pp_[BK];                                      \
+        }                                                                                    \
+    }
+
+    // step s = 2 kb + half: products of step s run beside the sums of step s-1.  xs = (xa, xb) holds first
+    // halves, ys second halves.
+    f32x16_t xa, xb, ya, yb;
+    KASCADE_POOL_STAGE(smK0, 0)
+    wait_vmem();
+    __syncthreads();
+    if (1 < n_blocks) { KASCADE_POOL_STAGE(smK1, 1) }
+    KASCADE_POOL_MMA(smK0, 0, xa, xb)                                  // step 0, nothing to sum yet
+    KASCADE_POOL_PIPE(smK0, KEY1, ya, yb, xa, xb, smPart + w * BK)     // step 1: sums of block 0, first half
+    int kb = 1;
+    for (; kb + 1 < n_blocks; kb += 2) {
+        // block kb (tile 1), then block kb+1 (tile 0)
+        wait_vmem();
+        __syncthreads();
+        KASCADE_POOL_STAGE(smK0, kb + 1)
+        if (kb >= 2) KASCADE_POOL_STORE(kb - 2)
+        KASCADE_POOL_PIPE(smK1, 0, xa, xb, ya, yb, smPart + ((kb - 1) % 3) * PARTSZ + w * BK + 32)
+        KASCADE_POOL_PIPE(smK1, KEY1, ya, yb, xa, xb, smPart + (kb % 3) * PARTSZ + w * BK)
+        wait_vmem();
+        __syncthreads();
+        if (kb + 2 < n_blocks) { KASCADE_POOL_STAGE(smK1, kb + 2) }
+        KASCADE_POOL_STORE(kb - 1)
+        KASCADE_POOL_PIPE(smK0, 0, xa, xb, ya, yb, smPart + (kb % 3) * PARTSZ + w * BK + 32)
+        KASCADE_POOL_PIPE(smK0, KEY1, ya, yb, xa, xb, smPart + ((kb + 1) % 3) * PARTSZ + w * BK)
+    }
+    if (kb < n_blocks) {     // one block left (tile 1)
+        wait_vmem();
+        __syncthreads();
+        if (kb >= 2) KASCADE_POOL_STORE(kb - 2)
+        KASCADE_POOL_PIPE(smK1, 0, xa, xb, ya, yb, smPart + ((kb - 1) % 3) * PARTSZ + w * BK + 32)
+        KASCADE_POOL_PIPE(smK1, KEY1, ya, yb, xa, xb, smPart + (kb % 3) * PARTSZ + w * BK)
+        ++kb;
+    }
+    // kb == n_blocks: the second half of the last block is still in (ya, yb)
+    {
+        float cs;
+        KASCADE_POOL_SUM(ya, yb, cs)
+        cs = half_swap_sum(cs);
+        if (h == 0) smPart[((n_blocks - 1) % 3) * PARTSZ + w * BK + 32 + q] = cs;
+    }
+    __syncthreads();
+    if (n_blocks >= 2) KASCADE_POOL_STORE(n_blocks - 2)
+    KASCADE_POOL_STORE(n_blocks - 1)
+#undef KASCADE_POOL_STORE
+#undef KASCADE_POOL_PIPE
+#undef KASCADE_POOL_SUM
+#undef KASCADE_POOL_MMA
+#undef KASCADE_POOL_STAGE
+
+    // anchor pass 3: both tiles' pooled scores were written by this workgroup, so it selects right away, one
+    // tile after the other, while the other workgroup of the compute unit keeps the matrix pipe busy
+    if (a.topk_out) {
+        SelectShared<kPB>& sel = smSel;
+#pragma unroll 1
+        for (int i = 0; i < 2; ++i) {
+            const int t = tA + i, prefix = i ? prefixB : prefixA;
+            if (prefix == 0) continue;
+            __syncthreads();   // the pooled scores are visible to the whole workgroup; LDS is free
+            const TileSlot slot = bounded_tile_slot(a.k_per_tile[t], a.idx_offsets[t], prefix, a.idx_total);
+            Segment sg;
+            sg.scores = i ? dstB : dstA;
+            sg.out = a.topk_out + hk * a.idx_total + slot.off;
+            sg.hist11 = nullptr;
+            sg.n = prefix; sg.k_sel = slot.k; sg.forced = 0; sg.pad_to = slot.k;
+            select_segment<kPB>(sg, sel);
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool sparse, bool with_v, hipStream_t st) {
     dim3 grid(a.n_sub * s.Hkv), block(kPB);   // one workgroup per 128 rows
     if (s.dtype != 1 && s.dtype != 2) return hipErrorInvalidValue;
     const bool f16 = s.dtype == 2;
+#define KASCADE_LAUNCH_STATS(DD, FF)                                                                                   \
+    {                                                                                                                  \
+        const dim3 grid2(((a.n_sub + 1) / 2) * s.Hkv);   /* one workgroup per 256 rows */                              \
+        KASCADE_LAUNCH((prefill_stats_kernel<DD, FF>), grid2, block, 0, st, s, a);                                     \
+    }
 #define KASCADE_LAUNCH_ATTEND(DD, FF)                                                                                  \
     {                                                                                                                  \
         if (sparse) KASCADE_LAUNCH((prefill_attend_kernel<DD, true, true, FF>), grid, block, 0, st, s, a);         \
         else if (with_v) KASCADE_LAUNCH((prefill_attend_kernel<DD, false, true, FF>), grid, block, 0, st, s, a);   \
-        else KASCADE_LAUNCH((prefill_attend_kernel<DD, false, false, FF>), grid, block, 0, st, s, a);              \
+        else KASCADE_LAUNCH_STATS(DD, FF)                                                                              \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_ATTEND(128, false)
     else if (s.D == 128) KASCADE_LAUNCH_ATTEND(128, true)
@@ -557,7 +1063,7 @@ hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t
 #define KASCADE_LAUNCH_POOL(DD, FF)                                                                              \
     {                                                                                                            \
         if (multi) KASCADE_LAUNCH((prefill_pool_kernel<DD, true, FF>), grid, block, 0, st, s, a);            \
-        else KASCADE_LAUNCH((prefill_pool_kernel<DD, false, FF>), grid, block, 0, st, s, a);                 \
+        else KASCADE_LAUNCH((prefill_pool2_kernel<DD, FF>), dim3(((a.n_tiles + 1) / 2) * s.Hkv), block, 0, st, s, a); \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_POOL(128, false)
     else if (s.D == 128) KASCADE_LAUNCH_POOL(128, true)

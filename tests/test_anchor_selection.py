@@ -86,3 +86,25 @@ def test_library_selection_with_layer_weights():
     assert kb.kascade_select_anchor_layers(S, M, layer_weights=np.ones(L))[0] == kb.kascade_select_anchor_layers(S, M)[0]
     with pytest.raises(ValueError):
         kb.kascade_select_anchor_layers(S, M, layer_weights=np.ones(L + 1))
+
+
+def test_config5_anchor_layers_from_planted_drift_oracle_similarity():
+    """32 layers whose heavy hitters are redrawn at layers 0, 1, 4, 12, 20 and drift 5 % per layer in
+    between: from the oracle's similarity matrix (Eq. 3, minimum over the key heads) both the library's
+    host routine and the oracle's Algorithm 1 return exactly those layers for five anchors."""
+    from paper_2512_16391_amd import workloads
+    starts = workloads.CONFIG5_ANCHORS
+    wl = workloads.layer_stack("cpu", n_layers=32, block_starts=starts, B=1, Hq=8, Hkv=2, d=64,
+                               seqlens=(2000,), k=64, n_hitters=32, within=0.95)
+    f64 = lambda t: t.double().numpy()
+    ref = [ko.decode_anchor_indices(f64(l.q[0]), f64(l.k[0]), ko.default_scale(wl.d), 64) for l in wl.layers]
+    n = len(ref)
+    S = np.zeros((n, n))
+    for a in range(n):
+        for b in range(a, n):
+            S[a, b] = min(ko.topk_similarity(ref[b][1][h], ref[a][0][h], ref[b][0][h]) for h in range(wl.Hkv))
+    assert ko.select_anchor_layers(S, 5) == list(starts)
+    got, _ = kb.kascade_select_anchor_layers(S.astype(np.float32), 5)
+    assert got == list(starts)
+    # inside a block the similarity decays slowly, across a redraw it collapses
+    assert S[4, 11] > 0.3 and S[4, 12] < 0.1 and S[20, 31] > 0.3 and S[0, 1] < 0.1

@@ -177,3 +177,36 @@ def test_layer_importance_matches_oracle(dtype, tol):
     w2 = binding.kascade_layer_importance(wide[:, :200], wide[:, 256:456]).double().cpu().numpy()
     want2 = ko.layer_importance(f64(wide[:, :200].cpu()), f64(wide[:, 256:456].cpu()))
     assert np.abs(w2 - want2).max() <= tol
+
+
+def test_config5_anchor_layers_emerge_from_planted_drift():
+    """A 32-layer stack whose heavy-hitter positions are redrawn at layers 0, 1, 4, 12 and 20 and drift
+    slowly (5 % per layer) in between: the similarity matrix measured on the GPU path (pooled distributions,
+    Top-k sets, Eq. 3 with the minimum over the samples) makes Algorithm 1 return the configuration's anchor
+    layers {0, 1, 4, 12, 20} for five anchors - from the library's host routine and from the oracle's."""
+    print("case config5 anchors from planted drift", flush=True)
+    starts = workloads.CONFIG5_ANCHORS
+    wl = workloads.layer_stack("cpu", n_layers=32, block_starts=starts, B=1, Hq=8, Hkv=2, d=64,
+                               seqlens=(2000,), k=64, n_hitters=32, within=0.95)
+    n, Hkv = len(wl.layers), wl.Hkv
+    Lmax, k_max = max(wl.seqlens), max(wl.k_per_seq)
+    lens, ks = i32(wl.seqlens), i32(wl.k_per_seq)
+    pooled_d, idx_d = [], []
+    for layer in wl.layers:
+        q, k, v = layer.q.to(DEV), layer.k.to(DEV), layer.v.to(DEV)
+        pooled_d.append(binding.kascade_decode_pooled(q, k, lens, Lmax))
+        idx_d.append(binding.kascade_decode_anchor(q, k, v, lens, ks, Lmax, k_max)[0])
+    ref = [oracle_layer(layer, wl) for layer in wl.layers]
+    S_dev = np.zeros((n, n), dtype=np.float32)
+    S_ref = np.zeros((n, n))
+    for a in range(n):
+        for b_ in range(a, n):
+            smin = torch.ones(1, dtype=torch.float32, device=DEV)
+            binding.kascade_topk_similarity(pooled_d[b_], lens, ks, idx_d[a], idx_d[b_], sim_min=smin)
+            S_dev[a, b_] = smin.item()
+            S_ref[a, b_] = min(ko.topk_similarity(ref[b_][0][0][h], ref[a][1][0][h], ref[b_][1][0][h]) for h in range(Hkv))
+    assert np.abs(S_dev - S_ref).max() <= 2e-5
+    got, obj = binding.kascade_select_anchor_layers(S_dev, len(starts))
+    want = ko.select_anchor_layers(S_ref, len(starts))
+    print(f"  anchors {got}, objective {obj:.3f}", flush=True)
+    assert got == want == list(starts)

@@ -298,15 +298,17 @@ def test_decode_config2_full_size():
 
 def test_decode_config3_full_size_sampled():
     """Bandwidth-stress configuration (batch 32, ragged 65536..131072 tokens, k = 5 %, 64 recent
-    tokens forced): run at full size, check the shortest, the longest and one middle sequence
-    (all heads) against the oracle, and structural properties for every sequence."""
+    tokens forced), all four layers at full size: eight sequences spread over the length range - the
+    shortest, the longest and six at even steps of the sorted lengths in between - are checked against
+    the oracle in every layer (anchor sets and output, three reuse outputs, all heads); structural
+    properties for every sequence."""
     print("case config3 full size", flush=True)
-    wl = workloads.config3(device=DEV, n_layers=2)
+    wl = workloads.config3(device=DEV, n_layers=4)
     sl, kp = i32(wl.seqlens), i32(wl.k_per_seq)
-    a, r = wl.layers
+    a = wl.layers[0]
     W = wl.recent_window
     idx_d, out_a = binding.kascade_decode_anchor(a.q, a.k, a.v, sl, kp, wl.Lmax, wl.k_max, recent_window=W)
-    out_r = binding.kascade_decode_reuse(r.q, r.k, r.v, sl, kp, wl.k_max, idx_d)
+    outs_r = [binding.kascade_decode_reuse(r.q, r.k, r.v, sl, kp, wl.k_max, idx_d) for r in wl.layers[1:]]
     torch.cuda.synchronize()
     idx = idx_d.cpu().numpy()
     # properties at any size: set size, order, range, forced window, padding
@@ -318,9 +320,11 @@ def test_decode_config3_full_size_sampled():
             assert (row[kb - W:kb] == np.arange(L - W, L)).all()
             assert (row[kb:] == -1).all()
     order = np.argsort(wl.seqlens)
+    picks = sorted({int(order[round(i * (len(order) - 1) / 7)]) for i in range(8)}, key=lambda b: wl.seqlens[b])
+    assert len(picks) == 8
     scale = ko.default_scale(wl.d)
     worst, swaps = 0.0, 0
-    for b in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):
+    for b in picks:
         L, kb = wl.seqlens[b], wl.k_per_seq[b]
         qb, kc, vc = f64(a.q[b]), f64(a.k[b, :, :L]), f64(a.v[b, :, :L])
         idx_ref, pooled = ko.decode_anchor_indices(qb, kc, scale, kb, W)
@@ -328,7 +332,10 @@ def test_decode_config3_full_size_sampled():
             swaps += check_index_set(idx[b, h, :kb], idx_ref[h], pooled[h], n_forced=W, where=f"cfg3 b{b} h{h}")
         sets = [idx[b, h, :kb] for h in range(wl.Hkv)]
         worst = max(worst, max_abs(f64(out_a[b]), ko.sparse_decode(qb, kc, vc, sets, scale)))
-        worst = max(worst, max_abs(f64(out_r[b]), ko.sparse_decode(f64(r.q[b]), f64(r.k[b, :, :L]), f64(r.v[b, :, :L]), sets, scale)))
+        del qb, kc, vc
+        for r, o in zip(wl.layers[1:], outs_r):
+            ref = ko.sparse_decode(f64(r.q[b]), f64(r.k[b, :, :L]), f64(r.v[b, :, :L]), sets, scale)
+            worst = max(worst, max_abs(f64(o[b]), ref))
         print(f"  cfg3 b{b} L={L} k={kb}: swaps {swaps}, worst max-abs {worst:.3e}", flush=True)
     assert worst <= TOL_OUT[wl.dtype]
 
