@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-config3", action="store_true")
+    ap.add_argument("--only-config3", action="store_true",
+                    help="run the bandwidth-stress decode leg alone (profiling aid: its kernels then are the only ones of their names)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=8)
     return ap.parse_args()
 
@@ -107,6 +109,9 @@ def main():
     binding.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.only_config3:
+        print(json.dumps({"config3": config3_leg(dev, load_traffic(), max(5, min(args.steps, 20)))}), flush=True)
+        return
 
     # ---------------- decode workload (resident, preallocated) ----------------
     wl = workloads.config2(device=dev)
