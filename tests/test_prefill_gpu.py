@@ -329,6 +329,74 @@ def test_config5_shape_prefill_131072_then_decode():
         assert max(e1, e2) <= TOL_OUT[BF16]
 
 
+def test_config5_late_layers_prefill_131072_then_decode():
+    """The far end of the 32-layer stack at full length: layer 20 (the last anchor), layer 21 (its first reuse
+    layer) and layer 31 (its last, eleven layers of 15 % hitter drift away from the sets it reuses), on tiles
+    the other config-5 test does not sample, then three decode steps on the same caches (anchor on layer 20,
+    reuse on 21 and 31).  Reuse outputs are compared with oracle attention over the anchor's own sets."""
+    print("case cfg5 late layers S=131072", flush=True)
+    S, T, steps = 131072, 32, 3
+    wl = workloads.config5_prefill(device=DEV, layers=(20, 21, 31), S=S, T=T, decode_steps=steps)
+    off = wl.idx_offsets
+    kpt_d, off_d = dev_i32(wl.k_per_tile), dev_i64(off)
+    la, lr1, lr2 = wl.layers
+    scale = ko.default_scale(wl.d)
+    tiles = [9, 1023, 3071, wl.n_tiles - 2]
+
+    idx_a, out_a = binding.kascade_prefill_anchor(la.q, la.k[:, :S], la.v[:, :S], T, kpt_d, off_d, off[-1])
+    torch.cuda.synchronize()
+    sets_of = lambda t: [idx_a[h, off[t]:off[t + 1]].cpu().numpy() for h in range(wl.Hkv)]
+
+    def check_sparse(layer, out, where):
+        Q, Kp, Vp = f64(layer.q), f64(layer.k[:, :S]), f64(layer.v[:, :S])
+        worst = 0.0
+        for t in tiles:
+            ref = ko.prefill_sparse_tile(Q, Kp, Vp, t, T, sets_of(t), scale)
+            worst = max(worst, max_abs(f64(out[t * T:(t + 1) * T]), ref))
+        print(f"  {where}: worst max-abs {worst:.3e}", flush=True)
+        assert worst <= TOL_OUT[BF16]
+        return Q, Kp
+
+    Qa, Ka = check_sparse(la, out_a, "layer20 anchor")
+    swaps = 0
+    for t in tiles:
+        idx_ref, pooled = ko.prefill_anchor_indices_tile(Qa, Ka, t, T, scale, wl.k_per_tile[t])
+        got = sets_of(t)
+        for h in range(wl.Hkv):
+            swaps += check_index_set(got[h], idx_ref[h], pooled[h], where=f"cfg5 layer20 tile {t} head {h}")
+    print(f"  layer20 index sets: swaps {swaps}", flush=True)
+    del Qa, Ka, out_a
+    for layer, name in ((lr1, "layer21 reuse"), (lr2, "layer31 reuse")):
+        out = binding.kascade_prefill_reuse(layer.q, layer.k[:, :S], layer.v[:, :S], T, kpt_d, off_d, off[-1], idx_a)
+        torch.cuda.synchronize()
+        check_sparse(layer, out, name)
+        del out
+    del idx_a
+
+    g = torch.Generator(device=DEV).manual_seed(778)
+    for step in range(steps):
+        L = S + step + 1
+        kk = workloads.budget(L, 100)
+        newq = torch.randn(3, 1, wl.Hq, wl.d, generator=g, device=DEV).to(BF16)
+        for layer in wl.layers:
+            layer.k[:, L - 1] = torch.randn(wl.Hkv, wl.d, generator=g, device=DEV).to(BF16)
+            layer.v[:, L - 1] = torch.randn(wl.Hkv, wl.d, generator=g, device=DEV).to(BF16)
+        sl, kp = dev_i32([L]), dev_i32([kk])
+        caches = [(layer.k[None, :, :L], layer.v[None, :, :L]) for layer in wl.layers]
+        idx_d, o_a = binding.kascade_decode_anchor(newq[0], caches[0][0], caches[0][1], sl, kp, L, kk)
+        outs = [o_a] + [binding.kascade_decode_reuse(newq[i], caches[i][0], caches[i][1], sl, kp, kk, idx_d) for i in (1, 2)]
+        torch.cuda.synchronize()
+        idx_np = idx_d.cpu().numpy()
+        idx_ref, pooled = ko.decode_anchor_indices(f64(newq[0, 0]), f64(caches[0][0][0]), scale, kk)
+        sw = sum(check_index_set(idx_np[0, h], idx_ref[h], pooled[h], where=f"cfg5 late decode step {step} head {h}")
+                 for h in range(wl.Hkv))
+        sets = [idx_np[0, h] for h in range(wl.Hkv)]
+        errs = [max_abs(f64(outs[i][0]), ko.sparse_decode(f64(newq[i, 0]), f64(caches[i][0][0]), f64(caches[i][1][0]), sets, scale))
+                for i in range(3)]
+        print(f"  decode step {step} L={L} k={kk}: swaps {sw}, max-abs {['%.3e' % e for e in errs]}", flush=True)
+        assert max(errs) <= TOL_OUT[BF16]
+
+
 @pytest.mark.parametrize("out_mode", [0, 1])
 def test_prefill_anchor_logits_rising_and_falling_along_the_keys(out_mode):
     """Keys whose logits climb by hundreds of nats along the sequence (and drop again): the running
