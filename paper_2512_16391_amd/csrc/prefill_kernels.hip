@@ -97,16 +97,16 @@ __device__ __forceinline__ void dma_rows_seq(unsigned char* tile, const unsigned
 }
 
 
-// Flash-style attention over a key list with both tiles (K, and V when an output is wanted) double
+// Flash-style attention over a key list with both tiles (K and V) double
 // buffered in LDS and filled by direct loads: block kb+1 streams in while block kb is multiplied,
 // one barrier per block.  BUF is the LDS buffer of this block; it is a template constant so that all
 // LDS addresses of a block differ from the other buffer's only by an immediate offset.
-template <int D, bool SPARSE, bool WITH_V, bool F16>
-__global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(Shape s, PrefillArgs a) {
+template <int D, bool SPARSE, bool F16>
+__global__ __launch_bounds__(kPB, 2) void prefill_attend_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, DBLK = D / 32, TILE = BK * D * 2;
     constexpr int PASSES = Dma<D>::PASSES, RPP = Dma<D>::RPP, PPR = Dma<D>::PPR;
     __shared__ __align__(16) unsigned char smK[2 * TILE];
-    __shared__ __align__(16) unsigned char smV[WITH_V ? 2 * TILE : 16];
+    __shared__ __align__(16) unsigned char smV[2 * TILE];
     __shared__ int smPos[2][BK];
     __shared__ int smFlag[3];   // "block holds a slot without a key", rotating over three blocks
 
@@ -183,10 +183,8 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             const uint32_t off_ = (uint32_t)(pos_[i_] < 0 ? 0 : pos_[i_]) * row_bytes;                       \
             unsigned char* dk_ = smK + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
             __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + (size_t)(off_ + koff)), (lds_ptr_t)dk_, 16, 0, 0); \
-            if constexpr (WITH_V) {                                                                          \
-                unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                       \
-                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + (size_t)(off_ + voff)), (lds_ptr_t)dv_, 16, 0, 0); \
-            }                                                                                                \
+            unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + (size_t)(off_ + voff)), (lds_ptr_t)dv_, 16, 0, 0); \
             if (pp == 0) smPos[buf_][i_ * RPP + r0] = pos_[i_] < 0 ? INT_MAX : pos_[i_];                     \
             bad_ |= pos_[i_] < 0;                                                                            \
         }                                                                                                    \
@@ -200,10 +198,8 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             const size_t blk_ = (size_t)((kb_) * BK + i_ * RPP) * row_bytes;                                  \
             unsigned char* dk_ = smK + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
             __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Kb + blk_ + (size_t)seq_k), (lds_ptr_t)dk_, 16, 0, 0); \
-            if constexpr (WITH_V) {                                                                          \
-                unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                       \
-                __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + blk_ + (size_t)seq_v), (lds_ptr_t)dv_, 16, 0, 0); \
-            }                                                                                                \
+            unsigned char* dv_ = smV + (buf_) * TILE + (i_ * kPB + w * kWave) * 16;                           \
+            __builtin_amdgcn_global_load_lds((gmem_ptr_t)(Vb + blk_ + (size_t)seq_v), (lds_ptr_t)dv_, 16, 0, 0); \
         }                                                                                                    \
     }
 
@@ -222,9 +218,9 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
     // (m_run, l_run): reference exponent and the sum of 2^(s c - m_run) over the keys seen so far;
     // neg_ref = -m_run once a finite reference exists, +inf before (forces the exact path)
     float m_run = -INFINITY, l_run = 0.f, neg_ref = INFINITY;
-    f32x16_t acc_o[WITH_V ? DBLK : 1];
+    f32x16_t acc_o[DBLK];
 #pragma unroll
-    for (int i = 0; i < (WITH_V ? DBLK : 1); ++i)
+    for (int i = 0; i < DBLK; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
 
@@ -258,14 +254,12 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
             s0 = Mma<F16>::mma32(fa_[kk], qf[kk], s0);                                                       \
             s1 = Mma<F16>::mma32(fb_[kk], qf[kk], s1);                                                       \
         }                                                                                                    \
-        if constexpr (WITH_V) {   /* these variants have registers to spare */                               \
-            __builtin_amdgcn_sched_group_barrier(0x100, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                    \
-            _Pragma("unroll") for (int kk = 0; kk + 4 < KSTEPS; ++kk) {                                       \
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                           \
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                           \
-            }                                                                                                \
-            __builtin_amdgcn_sched_group_barrier(0x008, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                        \
+        _Pragma("unroll") for (int kk = 0; kk + 4 < KSTEPS; ++kk) {                                           \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                               \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                               \
         }                                                                                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, KSTEPS >= 4 ? 8 : 2 * KSTEPS, 0);                        \
         bool need_mask = smFlag[f_cur] != 0;                                                                 \
         if constexpr (SPARSE) need_mask |= (kb_) >= nb_gather;                                               \
         else need_mask |= ((kb_) + 1) * BK > prefix;                                                         \
@@ -325,10 +319,8 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
                 rs += s0[r] + s1[r];                                                                         \
             }                                                                                                \
             l_run *= alpha;                                                                                  \
-            if constexpr (WITH_V) {                                                                          \
-                _Pragma("unroll") for (int i = 0; i < DBLK; ++i)                                              \
-                    _Pragma("unroll") for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;                      \
-            }                                                                                                \
+            _Pragma("unroll") for (int i = 0; i < DBLK; ++i)                                                  \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;                          \
             m_run = m_new;                                                                                   \
             /* no key seen yet (every slot so far masked or ignored): keep forcing the exact path, so    */ \
             /* that the first block with a live key sets the reference                                    */ \
@@ -336,7 +328,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         }                                                                                                    \
         rs = half_swap_sum(rs);                                                                              \
         l_run += rs;                                                                                         \
-        if constexpr (WITH_V) {                                                                              \
+        {                                                                                                    \
             const unsigned char* tV_ = smV + (buf_) * TILE;                                                  \
             bf16x8_t pf[4];                                                                                  \
             pf[0] = Mma<F16>::pack_tile(s0, 0); pf[1] = Mma<F16>::pack_tile(s0, 8);                          \
@@ -370,7 +362,7 @@ __global__ __launch_bounds__(kPB, (WITH_V ? 2 : 4)) void prefill_attend_kernel(S
         st[0] = m_run;
         st[1] = l_run;
     }
-    if constexpr (WITH_V) {
+    {
         const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
         bf16_t* op = reinterpret_cast<bf16_t*>(a.out) + (int64_t)rm.token * s.o_stride[1] + (int64_t)rm.head * s.o_stride[2];
 #pragma unroll
@@ -683,10 +675,9 @@ __device__ __forceinline__ void pool_block(const unsigned char* tile, float (*pa
 // Anchor pass 2 with two K tiles in LDS filled by direct loads: block kb+1 streams in while block
 // kb is multiplied; one barrier per block.  The cross-wave sum of block kb's column partials is
 // taken after the next barrier (two partial buffers), so it needs no barrier of its own.
-// MULTI: the tile has more than 128 rows and is swept in parts (the form that runs: 128-row tiles go to
-// prefill_pool2_kernel).
-template <int D, bool MULTI, bool F16>
-__global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shape s, PrefillArgs a) {
+// For tiles of more than 128 rows, which are swept in parts of 128 (128-row tiles go to prefill_pool2_kernel).
+template <int D, bool F16>
+__global__ __launch_bounds__(kPB, 2) void prefill_pool_kernel(Shape s, PrefillArgs a) {
     constexpr int KSTEPS = D / 16, TILE = BK * D * 2;
     constexpr int PART = kPW * BK * (int)sizeof(float);
     // two K tiles and two buffers of column partials during the sweep; afterwards the same memory
@@ -710,7 +701,7 @@ __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shap
     const int tile_end = (prefix + T < S) ? prefix + T : S;
     const float inv_rows = 1.f / (float)((tile_end - prefix) * s.G);
     const int n_blocks = (prefix + BK - 1) / BK;
-    const int n_parts = MULTI ? (tile_end - prefix + Ts - 1) / Ts : 1;   // 128 rows at a time
+    const int n_parts = (tile_end - prefix + Ts - 1) / Ts;   // 128 rows at a time
 
     const unsigned char* Kb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(a.k) + hk * s.kv_stride[1]);
     const uint32_t row_bytes = (uint32_t)s.kv_stride[2] * 2u;
@@ -754,7 +745,7 @@ __global__ __launch_bounds__(kPB, (MULTI ? 2 : 3)) void prefill_pool_kernel(Shap
             if (j_ < prefix) {                                                                                 \
                 const float sum_ = (part_[0][threadIdx.x] + part_[1][threadIdx.x]) +                           \
                                    (part_[2][threadIdx.x] + part_[3][threadIdx.x]);                            \
-                dst[j_] = (!MULTI || part == 0) ? sum_ : dst[j_] + sum_;                                       \
+                dst[j_] = part == 0 ? sum_ : dst[j_] + sum_;                                                   \
             }                                                                                                  \
         }
 #define KASCADE_POOL_STEP(kb_, cur_, nxt_, part_cur_, part_prev_)                                              \
@@ -1043,8 +1034,8 @@ hipError_t launch_prefill_attend(const Shape& s, const PrefillArgs& a, bool spar
     }
 #define KASCADE_LAUNCH_ATTEND(DD, FF)                                                                                  \
     {                                                                                                                  \
-        if (sparse) KASCADE_LAUNCH((prefill_attend_kernel<DD, true, true, FF>), grid, block, 0, st, s, a);         \
-        else if (with_v) KASCADE_LAUNCH((prefill_attend_kernel<DD, false, true, FF>), grid, block, 0, st, s, a);   \
+        if (sparse) KASCADE_LAUNCH((prefill_attend_kernel<DD, true, FF>), grid, block, 0, st, s, a);         \
+        else if (with_v) KASCADE_LAUNCH((prefill_attend_kernel<DD, false, FF>), grid, block, 0, st, s, a);   \
         else KASCADE_LAUNCH_STATS(DD, FF)                                                                              \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_ATTEND(128, false)
@@ -1062,7 +1053,7 @@ hipError_t launch_prefill_pool(const Shape& s, const PrefillArgs& a, hipStream_t
     const bool multi = a.tile_tokens != a.sub_tokens, f16 = s.dtype == 2;
 #define KASCADE_LAUNCH_POOL(DD, FF)                                                                              \
     {                                                                                                            \
-        if (multi) KASCADE_LAUNCH((prefill_pool_kernel<DD, true, FF>), grid, block, 0, st, s, a);            \
+        if (multi) KASCADE_LAUNCH((prefill_pool_kernel<DD, FF>), grid, block, 0, st, s, a);            \
         else KASCADE_LAUNCH((prefill_pool2_kernel<DD, FF>), dim3(((a.n_tiles + 1) / 2) * s.Hkv), block, 0, st, s, a); \
     }
     if (s.D == 128 && !f16) KASCADE_LAUNCH_POOL(128, false)
