@@ -688,3 +688,43 @@ def test_decode_anchor_token_major_cache(dtype, d, G, out_mode):
         want = ko.dense_decode(qb, kb_, vb, 0.11) if out_mode == binding.KASCADE_OUT_DENSE else \
             ko.sparse_decode(qb, kb_, vb, [idx_h[b, h, :kb] for h in range(Hkv)], 0.11)
         assert max_abs(o[b], want) <= TOL_OUT[dtype]
+
+
+def test_decode_one_request_of_a_million_tokens():
+    """Longest single sequence the sweeps are timed at (Table 3's 512K, doubled): 32/8 heads, d 128, bf16, one
+    request of 1,048,576 tokens, k = 1 % with a 64-token recent window; anchor (sparse output) and a reuse
+    layer on a second query.  Row offsets pass 2^28 bytes per key head and the selection runs split over many
+    workgroups.  The oracle takes one key head at a time (a head's fp64 K and V are 2 GB)."""
+    print("case one million tokens", flush=True)
+    L, Hq, Hkv, d, W = 1 << 20, 32, 8, 128, 64
+    G = Hq // Hkv
+    kk = workloads.budget(L, 10)
+    g = torch.Generator(device=DEV).manual_seed(4242)
+    q = torch.randn(2, 1, Hq, d, generator=g, device=DEV).to(torch.bfloat16)
+    k = torch.randn(1, Hkv, L, d, generator=g, device=DEV).to(torch.bfloat16)
+    v = torch.randn(1, Hkv, L, d, generator=g, device=DEV).to(torch.bfloat16)
+    # planted hitters so that the pooled scores are not flat: 4096 keys per head lean towards the head's queries
+    for h in range(Hkv):
+        u = torch.nn.functional.normalize(torch.randn(d, generator=g, device=DEV), dim=0)
+        pos = torch.randperm(L, generator=g, device=DEV)[:4096]
+        k[0, h, pos] = (k[0, h, pos].float() + 3.0 * u).to(torch.bfloat16)
+        q[:, 0, h * G:(h + 1) * G] = (q[:, 0, h * G:(h + 1) * G].float() + u).to(torch.bfloat16)
+    sl, kp = i32([L]), i32([kk])
+    idx_d, o_anchor = binding.kascade_decode_anchor(q[0], k, v, sl, kp, L, kk, recent_window=W,
+                                                    out_mode=binding.KASCADE_OUT_SPARSE)
+    o_reuse = binding.kascade_decode_reuse(q[1], k, v, sl, kp, kk, idx_d)
+    torch.cuda.synchronize()
+    idx = idx_d.cpu().numpy()
+    scale = ko.default_scale(d)
+    swaps, worst = 0, 0.0
+    for h in range(Hkv):
+        kh, vh = f64(k[0, h:h + 1]), f64(v[0, h:h + 1])
+        qa, qr = f64(q[0, 0, h * G:(h + 1) * G]), f64(q[1, 0, h * G:(h + 1) * G])
+        idx_ref, pooled = ko.decode_anchor_indices(qa, kh, scale, kk, W)
+        swaps += check_index_set(idx[0, h, :kk], idx_ref[0], pooled[0], n_forced=W, where=f"1M head {h}")
+        sets = [idx[0, h, :kk]]
+        worst = max(worst, max_abs(f64(o_anchor[0, h * G:(h + 1) * G]), ko.sparse_decode(qa, kh, vh, sets, scale)),
+                    max_abs(f64(o_reuse[0, h * G:(h + 1) * G]), ko.sparse_decode(qr, kh, vh, sets, scale)))
+        del kh, vh
+    print(f"  1M tokens k={kk}: swaps {swaps}, max-abs {worst:.3e}", flush=True)
+    assert worst <= TOL_OUT[torch.bfloat16]
